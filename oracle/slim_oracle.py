@@ -1,0 +1,318 @@
+"""CPU oracle for the SlimInfer pruned prefill layer.  TEST INFRASTRUCTURE ONLY.
+
+This module is the slow, plain definition the HIP kernels are checked against.  Only the test-suite,
+the smoke check and the benchmark's `cpu_baseline` leg may import it; the product package never does,
+and this module imports nothing from the product package.
+
+Everything is NumPy on the host.  Arithmetic runs in `dtype` (float64 unless the caller asks for
+float32); RoPE angles are always formed in float64.  There is no blocking, fusion or re-association
+beyond what the paper's definitions state, except that attention is evaluated for a chunk of query rows
+at a time so the full score matrix is never held in memory (each row's arithmetic is unchanged).
+
+Notation follows the paper (Section 4.2): prompt blocks B_j of `block` tokens, each split into M
+TokenUnits of `unit` tokens; k_rep(j, m) is the unit's mean Key state (Eq. 1); q_l is the mean Query
+state of the last `window` tokens; r_block is the block score (Eq. 2).
+
+Pins (tests/test_oracle_*.py): brute-force softmax attention written with scalar loops; torch's CPU
+scaled-dot-product attention; closed-form score cases; exhaustive selection on tiny inputs;
+keep-ratio 1.0 equals the unpruned layer; gather commutation of the per-token steps; RoPE relative-
+position property.  The one thing with no pin is whether the heuristic preserves model accuracy
+(Table 1 needs LongBench and trained weights): "parity unpinned" for that claim only.
+
+`rounding="bf16"` makes every function round its result to bfloat16 precision at the points where a
+bf16 pipeline stores a tensor (after RMSNorm, after each projection, the softmax probabilities, the
+attention output, the activation, both residual sums).  It is used only to measure how far any bf16
+pipeline can be from the exact result, never as the parity reference.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------------------------------
+# rounding hook (identity for the reference; bf16 grid for the "how far can bf16 be" measurement)
+# --------------------------------------------------------------------------------------------------
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Round to the nearest bfloat16 value (ties to even); result keeps a's dtype."""
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    out = u.astype(np.uint32).view(np.float32)
+    return out.astype(a.dtype, copy=False)
+
+
+def _rnd(a, rounding):
+    return round_bf16(a) if rounding == "bf16" else a
+
+
+# --------------------------------------------------------------------------------------------------
+# per-token layer math ("QKV Generation" and "FFN" boxes of Fig. 2)
+# --------------------------------------------------------------------------------------------------
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """h_t = gain * x_t / sqrt(mean_c(x_t[c]^2) + eps), one row per token."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return gain * (x / np.sqrt(ms + eps))
+
+
+def linear(h: np.ndarray, W: np.ndarray) -> np.ndarray:
+    """y = h W^T with W stored [out_features, in_features] (no bias)."""
+    return h @ W.T
+
+
+def rope_cos_sin(pos: np.ndarray, head_dim: int, theta: float, dtype):
+    """cos/sin of pos * theta^(-2i/d), i = 0..d/2-1.  Angles in float64, then cast."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * i / head_dim)
+    ang = pos.astype(np.float64)[:, None] * inv_freq[None, :]
+    return np.cos(ang).astype(dtype), np.sin(ang).astype(dtype)
+
+
+def apply_rope(x: np.ndarray, cos: np.ndarray, sin: np.ndarray) -> np.ndarray:
+    """Rotate-half RoPE on x[n, H, d]: the pair is (i, i + d/2), rotated by the angle of index i."""
+    half = x.shape[-1] // 2
+    x1, x2 = x[..., :half], x[..., half:]
+    c, s = cos[:, None, :], sin[:, None, :]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def silu(a: np.ndarray) -> np.ndarray:
+    return a / (1.0 + np.exp(-a))
+
+
+# --------------------------------------------------------------------------------------------------
+# block-wise prompt token pruning (Section 4.2)
+# --------------------------------------------------------------------------------------------------
+def n_blocks(n_tokens: int, block: int) -> int:
+    return (n_tokens + block - 1) // block
+
+
+def n_keep_from_ratio(ratio: float, nb: int, n_forced: int = 2) -> int:
+    """Retained block count for a keep ratio: ceil(ratio * nb), clamped to [forced, nb]."""
+    return int(min(nb, max(min(n_forced, nb), math.ceil(ratio * nb - 1e-12))))
+
+
+def window_query(q_win: np.ndarray) -> np.ndarray:
+    """q_l: mean of the Query states of the local window.  q_win[w, Hq, d] -> [Hq, d]."""
+    return q_win.mean(axis=0)
+
+
+def unit_keys(k_block: np.ndarray, unit: int) -> np.ndarray:
+    """Eq. (1): representative keys of one block.  k_block[len, Hkv, d] -> [M, Hkv, d];
+    a short trailing unit is averaged over the tokens it actually has."""
+    reps = []
+    for s in range(0, k_block.shape[0], unit):
+        reps.append(k_block[s:s + unit].mean(axis=0))
+    return np.stack(reps)
+
+
+def block_scores(q_win: np.ndarray, k: np.ndarray, block: int, unit: int) -> np.ndarray:
+    """Eq. (2): r_j = max_m (1/H) sum_h q_l^h . k_rep^h(j, m), H = number of query heads;
+    query head h reads kv head h // (Hq/Hkv).  No softmax, no 1/sqrt(d).
+    q_win[w, Hq, d] (post-RoPE), k[N, Hkv, d] (post-RoPE) -> scores[nb]."""
+    Hq, Hkv = q_win.shape[1], k.shape[1]
+    G = Hq // Hkv
+    q_l = window_query(q_win)                                   # [Hq, d]
+    N = k.shape[0]
+    out = np.empty(n_blocks(N, block), dtype=k.dtype)
+    for j in range(out.shape[0]):
+        k_rep = unit_keys(k[j * block:min((j + 1) * block, N)], unit)   # [M, Hkv, d]
+        k_rep_h = np.repeat(k_rep, G, axis=1)                   # [M, Hq, d]: head h -> kv head h//G
+        per_head = np.einsum("hd,mhd->mh", q_l, k_rep_h)        # q_l^h . k_rep^h(j, m)
+        out[j] = per_head.mean(axis=1).max()
+    return out
+
+
+def select_blocks(scores: np.ndarray, n_keep: int, force_first: bool = True,
+                  force_last: bool = True) -> np.ndarray:
+    """Forced blocks (first = attention sink; last) are always kept; the remaining
+    n_keep - #forced slots go to the other blocks in order (score descending, index ascending).
+    Returns ascending int32 block indices; n_keep >= nb keeps everything."""
+    nb = scores.shape[0]
+    assert not np.isnan(scores).any(), "selection is undefined on NaN scores"
+    if n_keep >= nb:
+        return np.arange(nb, dtype=np.int32)
+    forced = set()
+    if force_first:
+        forced.add(0)
+    if force_last:
+        forced.add(nb - 1)
+    assert n_keep >= len(forced)
+    rest = [j for j in range(nb) if j not in forced]
+    rest.sort(key=lambda j: (-float(scores[j]), j))
+    kept = sorted(forced | set(rest[:n_keep - len(forced)]))
+    return np.asarray(kept, dtype=np.int32)
+
+
+def selection_cut(scores: np.ndarray, n_keep: int, force_first: bool = True,
+                  force_last: bool = True):
+    """Midpoint between the last taken and the first not-taken score among non-forced blocks
+    (None if nothing is dropped).  Blocks whose score lies within a tolerance of this cut may
+    legitimately go either way when the scores carry rounding error."""
+    nb = scores.shape[0]
+    forced = ({0} if force_first else set()) | ({nb - 1} if force_last else set())
+    rest = sorted((j for j in range(nb) if j not in forced), key=lambda j: (-float(scores[j]), j))
+    take = n_keep - len(forced)
+    if n_keep >= nb or take >= len(rest):
+        return None
+    if take == 0:
+        return float(scores[rest[0]]) + 1.0
+    return 0.5 * (float(scores[rest[take - 1]]) + float(scores[rest[take]]))
+
+
+def kept_token_index(kept_blocks: np.ndarray, block: int, n_tokens: int) -> np.ndarray:
+    """Token rows of the kept blocks, in ascending order (only the last block can be short)."""
+    parts = [np.arange(b * block, min((b + 1) * block, n_tokens)) for b in kept_blocks]
+    return np.concatenate(parts) if parts else np.zeros(0, dtype=np.int64)
+
+
+def compact_tokens(src: np.ndarray, pos: np.ndarray, kept_blocks: np.ndarray, block: int):
+    """Hidden-state pruning: keep only the rows of the kept blocks, and carry their original
+    positions along (they are what RoPE must see afterwards)."""
+    T = kept_token_index(kept_blocks, block, src.shape[0])
+    return src[T], pos[T]
+
+
+# --------------------------------------------------------------------------------------------------
+# attention ("Attention" box of Fig. 2): causal softmax attention with grouped kv heads
+# --------------------------------------------------------------------------------------------------
+def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float | None = None,
+                         rows: np.ndarray | None = None, chunk: int = 256,
+                         rounding: str | None = None) -> np.ndarray:
+    """o_i^h = sum_{j<=i} softmax_j(scale * q_i^h . k_j^{h//G}) v_j^{h//G}.
+
+    q[nq, Hq, d], k/v[n, Hkv, d].  `rows[nq]` gives each query's index in the key sequence
+    (default: nq == n and row i is query i), so a sample of rows can be evaluated on its own."""
+    nq, Hq, d = q.shape
+    n, Hkv, _ = k.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    if rows is None:
+        assert nq == n
+        rows = np.arange(n)
+    out = np.empty_like(q)
+    for h in range(Hq):
+        kh, vh = k[:, h // G, :], v[:, h // G, :]
+        for c0 in range(0, nq, chunk):
+            r = rows[c0:c0 + chunk]
+            jmax = int(r.max()) + 1
+            s = (q[c0:c0 + chunk, h, :] @ kh[:jmax].T) * scale            # [c, jmax]
+            s = np.where(np.arange(jmax)[None, :] <= r[:, None], s, -np.inf)
+            s = s - s.max(axis=1, keepdims=True)
+            p = np.exp(s)
+            den = p.sum(axis=1, keepdims=True)
+            out[c0:c0 + chunk, h, :] = (_rnd(p, rounding) @ vh[:jmax]) / den
+    return out
+
+
+# --------------------------------------------------------------------------------------------------
+# the pruned prefill layer
+# --------------------------------------------------------------------------------------------------
+@dataclass
+class LayerShape:
+    hidden: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    ffn: int
+    block: int
+    unit: int
+    window: int
+    rope_theta: float = 500000.0
+    rms_eps: float = 1e-5
+
+
+@dataclass
+class LayerWeights:
+    """All [out_features, in_features]; gains are vectors of length hidden."""
+    g_attn: np.ndarray
+    wq: np.ndarray
+    wk: np.ndarray
+    wv: np.ndarray
+    wo: np.ndarray
+    g_ffn: np.ndarray
+    w_gate: np.ndarray
+    w_up: np.ndarray
+    w_down: np.ndarray
+
+    def astype(self, dtype):
+        return LayerWeights(*[getattr(self, f).astype(dtype) for f in self.__dataclass_fields__])
+
+
+def project_heads(h, W, n_heads, head_dim, pos, theta, rope: bool, rounding=None):
+    """A projection reshaped to heads, with RoPE at the tokens' own positions when asked."""
+    y = linear(h, W).reshape(h.shape[0], n_heads, head_dim)
+    if rope:
+        cos, sin = rope_cos_sin(pos, head_dim, theta, h.dtype)
+        y = apply_rope(y, cos, sin)
+    return _rnd(y, rounding)
+
+
+def layer_scores(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray, rounding=None):
+    """Scoring inputs and Eq. (1)-(2) for one layer: Key states of all tokens, Query states of the
+    last min(window, N) tokens (both post-RoPE), then the block scores.  Returns (scores, k)."""
+    N = x.shape[0]
+    h = _rnd(rmsnorm(x, w.g_attn, s.rms_eps), rounding)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding)
+    w_eff = min(s.window, N)
+    q_win = project_heads(h[N - w_eff:], w.wq, s.n_q_heads, s.head_dim, pos[N - w_eff:],
+                          s.rope_theta, True, rounding)
+    return block_scores(q_win, k, s.block, s.unit), k
+
+
+def layer_after_selection(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
+                          kept_blocks: np.ndarray, rows: np.ndarray | None = None, rounding=None):
+    """Everything after the block set is known: compact, QKV for the kept tokens (RoPE with the
+    original positions), causal GQA attention over the compacted sequence, output projection
+    + residual, SwiGLU FFN + residual.  `rows` (indices into the compacted sequence) limits the
+    output to a sample of rows; attention for a sampled row still sees every kept key before it.
+    Returns (z[rows or n', hidden], pos'[n'])."""
+    xk, posk = compact_tokens(x, pos, kept_blocks, s.block)
+    n = xk.shape[0]
+    h = _rnd(rmsnorm(xk, w.g_attn, s.rms_eps), rounding)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, posk, s.rope_theta, True, rounding)
+    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, posk, s.rope_theta, False, rounding)
+    if rows is None:
+        rows = np.arange(n)
+    q = project_heads(h[rows], w.wq, s.n_q_heads, s.head_dim, posk[rows], s.rope_theta, True, rounding)
+    o = _rnd(causal_gqa_attention(q, k, v, rows=rows, rounding=rounding), rounding)
+    y = _rnd(xk[rows] + linear(o.reshape(len(rows), -1), w.wo), rounding)
+    r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
+    act = _rnd(silu(linear(r, w.w_gate)) * linear(r, w.w_up), rounding)
+    z = _rnd(y + linear(act, w.w_down), rounding)
+    return z, posk
+
+
+def pruned_layer(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray, n_keep: int,
+                 force_first: bool = True, force_last: bool = True, rounding=None):
+    """One Slim layer: score -> select -> compact -> attention -> FFN on the kept tokens.
+    n_keep >= number of blocks makes it a Preserve layer (nothing dropped).
+    Returns dict(z, pos, kept_blocks, scores)."""
+    nb = n_blocks(x.shape[0], s.block)
+    if n_keep >= nb:
+        kept = np.arange(nb, dtype=np.int32)
+        scores = None
+    else:
+        scores, _ = layer_scores(s, w, x, pos, rounding)
+        kept = select_blocks(scores, n_keep, force_first, force_last)
+    z, posk = layer_after_selection(s, w, x, pos, kept, rounding=rounding)
+    return dict(z=z, pos=posk, kept_blocks=kept, scores=scores)
+
+
+def prefill_model(s: LayerShape, weights_of_layer, n_layers: int, x: np.ndarray, pos: np.ndarray,
+                  schedule: dict, rounding=None):
+    """Preserve/Slim schedule (Section 4.1): layers run in order; layer l in `schedule` prunes its
+    incoming sequence to ceil(schedule[l] * incoming blocks) blocks, and the surviving set then
+    propagates unchanged until the next pruning layer.  `weights_of_layer(l)` supplies the weights.
+    Returns (residual stream after the last layer, its positions, list of per-layer kept sets)."""
+    kept_log = []
+    for l in range(n_layers):
+        nb = n_blocks(x.shape[0], s.block)
+        n_keep = n_keep_from_ratio(schedule[l], nb) if l in schedule else nb
+        res = pruned_layer(s, weights_of_layer(l), x, pos, n_keep, rounding=rounding)
+        x, pos = res["z"], res["pos"]
+        kept_log.append(res["kept_blocks"])
+    return x, pos, kept_log
