@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned prefill layer on one MI355X.
+
+A step is one call of slim_pruned_layer (RMSNorm, K projection of all N tokens, window Q, block
+scores, selection, compaction, Q/V projection, causal GQA attention, output projection, SwiGLU
+FFN) on a synthetic workload whose inputs are already in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu] [--no-stages]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+
+
+def time_gpu(fn, reps, warmup=3):
+    """Median / mean milliseconds of fn() measured with events on the current (launch) stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    torch.cuda.synchronize()
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], sum(ts) / len(ts)
+
+
+def stage_table(slim, wl, wd, x, pos, n_keep, reps):
+    """Each kernel of the layer timed alone on the layer's real shapes, with its algorithmic work."""
+    import torch
+    dev = x.device
+    N, Hd, Hq, Hkv, d, F = wl.seq, wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn
+    n = slim.kept_tokens(N, wl.block, n_keep)
+    bf = torch.bfloat16
+    es = 2
+    h_all = torch.randn(N, Hd, device=dev).to(bf)
+    h = h_all[:n].contiguous()
+    k_all = torch.randn(N, Hkv, d, device=dev).to(bf)
+    q_win = torch.randn(wl.window, Hq, d, device=dev).to(bf)
+    q = torch.randn(n, Hq, d, device=dev).to(bf)
+    k, v = k_all[:n].contiguous(), torch.randn(n, Hkv, d, device=dev).to(bf)
+    o = torch.empty_like(q)
+    act = torch.empty(n, F, device=dev, dtype=bf)
+    y = torch.randn(n, Hd, device=dev).to(bf)
+    out_kv = torch.empty(N, Hkv * d, device=dev, dtype=bf)
+    out_q = torch.empty(n, Hq * d, device=dev, dtype=bf)
+    out_h = torch.empty(n, Hd, device=dev, dtype=bf)
+    scores = torch.empty(slim.n_blocks(N, wl.block), device=dev, dtype=torch.float32)
+    sws = torch.empty(4096, device=dev, dtype=torch.uint8)
+    kept = slim.slim_select_topk_blocks(torch.randn_like(scores), n_keep)
+    lib = slim.load_library()
+    st = torch.cuda.current_stream().cuda_stream
+    xc = torch.empty(n, Hd, device=dev, dtype=bf)
+    pc = torch.empty(n, dtype=torch.int32, device=dev)
+
+    def compact():
+        lib.slim_compact_tokens(x.data_ptr(), pos.data_ptr(), kept.data_ptr(), n_keep, wl.block, N, Hd, 1,
+                                xc.data_ptr(), pc.data_ptr(), st)
+
+    rows = [
+        ("rmsnorm_all", "hbm", 2 * N * Hd * es, lambda: slim.slim_rmsnorm(x, wd["g_attn"], wl.rms_eps, out=h_all)),
+        ("k_proj_all", "mfma", 2 * N * Hd * Hkv * d, lambda: slim.slim_linear(h_all, wd["wk"], out=out_kv)),
+        ("rope_k_all", "hbm", 2 * N * Hkv * d * es, lambda: slim.slim_rope(k_all, pos, wl.rope_theta)),
+        ("score_blocks", "hbm", N * Hkv * d * es + wl.window * Hq * d * es + scores.numel() * 4,
+         lambda: slim.slim_score_blocks(q_win, k_all, wl.block, wl.unit, scores=scores, workspace=sws)),
+        ("select_topk", "latency", scores.numel() * 4 + n_keep * 4,
+         lambda: slim.slim_select_topk_blocks(scores, n_keep, kept=kept)),
+        ("compact_x", "hbm", 2 * n * Hd * es + n * 8, compact),
+        ("q_proj", "mfma", 2 * n * Hd * Hq * d, lambda: slim.slim_linear(h, wd["wq"], out=out_q)),
+        ("v_proj", "mfma", 2 * n * Hd * Hkv * d, lambda: slim.slim_linear(h, wd["wv"], out=out_kv[:n])),
+        ("prefill_attn", "mfma", 2 * n * n * d * Hq, lambda: slim.slim_prefill_attn(q, k, v, out=o)),
+        ("o_proj_residual", "mfma", 2 * n * Hd * Hq * d,
+         lambda: slim.slim_linear(o.view(n, Hq * d), wd["wo"], residual=y, out=out_h)),
+        ("ffn_gate_up_swiglu", "mfma", 4 * n * Hd * F,
+         lambda: slim.slim_swiglu_linear(h, wd["w_gate"], wd["w_up"], out=act)),
+        ("ffn_down_residual", "mfma", 2 * n * Hd * F, lambda: slim.slim_linear(act, wd["w_down"], residual=y, out=out_h)),
+    ]
+    table = {}
+    for name, bound, work, fn in rows:
+        med, mean = time_gpu(fn, reps)
+        e = {"bound": bound, "ms": round(mean, 4), "ms_median": round(med, 4)}
+        if bound == "mfma":
+            e["tflops"] = round(work / (mean * 1e-3) / 1e12, 1)
+            e["frac"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        else:
+            e["gbs"] = round(work / (mean * 1e-3) / 1e9, 1)
+            e["frac"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+        e["work"] = work
+        table[name] = e
+    return table
+
+
+def cpu_baseline(wl_full, sample_tokens=8192):
+    """The oracle, as it is, on the host cores: the same layer on the first `sample_tokens` tokens."""
+    import numpy as np
+    from oracle import slim_oracle as so
+    from paper_2508_06447_amd import inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    wl = inputs.scaled(wl_full, seq=min(sample_tokens, wl_full.seq))
+    x = inputs.hidden_states(wl_full)[: wl.seq].float().numpy()
+    w = inputs.layer_weights(wl_full)
+    ow = so.LayerWeights(**{k: v.float().numpy() for k, v in w.items()})
+    s = so.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit, wl.window,
+                      wl.rope_theta, wl.rms_eps)
+    pos = np.arange(wl.seq, dtype=np.int32)
+    t0 = time.perf_counter()
+    so.pruned_layer(s, ow, x, pos, wl.n_keep)
+    dt = time.perf_counter() - t0
+    return {"value": round(wl.seq / dt, 1), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": f"float32 oracle pruned layer on the first {wl.seq} of {wl_full.seq} tokens of {wl_full.name} "
+                      f"(same layer shapes, block {wl.block}, keep ratio {wl.keep_ratio}: {wl.n_keep} of "
+                      f"{wl.n_blocks} blocks); attention per token is cheaper at this length than at full length"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-stages", action="store_true", help="skip the per-kernel table")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (the pruned prefill layer of one sequence); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2508_06447_amd as slim
+    from paper_2508_06447_amd import inputs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    slim.load_library()
+    dev = torch.device("cuda:0")
+    wl = inputs.WORKLOADS[args.workload]
+    assert wl.n_layers == 1, "bench.py times single-layer workloads"
+    x = inputs.hidden_states(wl).to(dev)
+    wd = {k: v.to(dev) for k, v in inputs.layer_weights(wl).items()}
+    pos = inputs.positions(wl).to(dev)
+    n_keep = wl.n_keep
+    shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
+                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps)
+    ws = torch.empty(slim.pruned_layer_workspace_bytes(shape, wl.seq, n_keep), dtype=torch.uint8, device=dev)
+    n_out = slim.kept_tokens(wl.seq, wl.block, n_keep)
+    out = dict(x=torch.empty(n_out, wl.hidden, dtype=x.dtype, device=dev),
+               pos=torch.empty(n_out, dtype=torch.int32, device=dev),
+               kept=torch.empty(n_keep, dtype=torch.int32, device=dev),
+               scores=torch.empty(wl.n_blocks, dtype=torch.float32, device=dev))
+
+    def step():
+        slim.slim_pruned_layer(shape, wd, x, pos, n_keep, workspace=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    Hd, Hq, Hkv, d, F, N, n = wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.seq, n_out
+    layer_flops = (2 * N * Hd * Hkv * d + 2 * wl.window * Hd * Hq * d + 2 * n * Hd * (Hq + Hkv) * d
+                   + 2 * n * n * d * Hq + 2 * n * Hd * Hq * d + 6 * n * Hd * F)
+    rec = {
+        "metric": "pruned-prefill tokens/s", "value": round(wl.seq / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: LLaMA-3.1-8B-shaped pruned prefill layer, seq {wl.seq}, block {wl.block}, "
+                               f"window {wl.window}, keep ratio {wl.keep_ratio}",
+                   "n_tokens": wl.seq, "n_keep_blocks": n_keep, "n_kept_tokens": n_out, "hidden": Hd,
+                   "heads": f"{Hq}q/{Hkv}kv x {d}", "ffn": F, "seed": wl.seed},
+        "layer_ms": round(ms, 4),
+        "layer_tflops": round(layer_flops / (ms * 1e-3) / 1e12, 1),
+        "layer_mfma_frac": round(layer_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+    }
+    if not args.no_stages and wl.dtype == "bf16":
+        table = stage_table(slim, wl, wd, x, pos, n_keep, reps=max(5, args.steps))
+        rec["kernels"] = table
+        dom = table["ffn_gate_up_swiglu"]
+        rec["roofline"] = {"kernel": "gemm_bf16_kernel (SwiGLU gate/up projection)", "bound": "mfma",
+                           "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": dom["frac"], "traffic": None, "avg_ms": dom["ms"]}
+    if not args.no_cpu:
+        rec["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/*
+ * libslim -- the pruned prefill layer of SlimInfer (arXiv 2508.06447) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Conventions shared by every entry point:
+ *   - Every data pointer is a DEVICE pointer owned by the caller, unless marked "host".
+ *     The library never allocates, frees or keeps a pointer after the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only enqueues
+ *     kernels on that stream; it never synchronises with the host.
+ *   - `dtype`: SLIM_F32 (0) = IEEE binary32, SLIM_BF16 (1) = bfloat16.  It is the type of every
+ *     activation and weight tensor of the call.  Block scores are always float; indices are int32.
+ *   - Tensors are dense row-major; "x[n, H, d]" means d is contiguous.
+ *   - Return value: SLIM_OK (0) or a negative error code.  On error nothing has been enqueued.
+ *   - Calls on different streams may overlap as long as their buffers (workspace included) are
+ *     distinct.
+ *
+ * Notation (Section 4.2 of the paper): the N prompt tokens are split into blocks of `block`
+ * tokens (nb = ceil(N/block)); each block into TokenUnits of `unit` tokens; q_l is the mean Query
+ * state of the last `window` tokens; Hq / Hkv are the numbers of query / key-value heads and
+ * query head h reads kv head h / (Hq/Hkv).
+ */
+#ifndef SLIM_H
+#define SLIM_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { SLIM_F32 = 0, SLIM_BF16 = 1 };
+
+enum {
+    SLIM_OK = 0,
+    SLIM_INVALID_ARG = -1,        /* null pointer, non-positive size, Hq % Hkv != 0, bad n_keep ... */
+    SLIM_UNSUPPORTED = -2,        /* a shape or dtype the kernels do not cover (see each call)      */
+    SLIM_WORKSPACE_TOO_SMALL = -3,
+    SLIM_HIP_ERROR = -4           /* a launch failed; slim_last_hip_error() has the runtime's text  */
+};
+
+/* Force flags for slim_select_topk_blocks / layer flags. */
+enum { SLIM_FORCE_FIRST = 1u, SLIM_FORCE_LAST = 2u };
+
+const char* slim_status_string(int code);
+/* Text of the last HIP runtime error seen by this thread inside the library ("" if none). */
+const char* slim_last_hip_error(void);
+
+/* ------------------------------------------------------------------------------------------------
+ * Block importance scores -- Eq. (1) and Eq. (2), Section 4.2.
+ *   k_rep(j,m) = mean of the Key states of TokenUnit m of block j               (Eq. 1)
+ *   scores[j]  = max_m (1/Hq) sum_h  q_l^h . k_rep^{h/(Hq/Hkv)}(j,m)             (Eq. 2)
+ * with q_l^h the mean over the `window` rows of q_win.  Plain dot products: no softmax, no
+ * 1/sqrt(d).  A short last block / last unit is averaged over the tokens it really has.
+ *   q_win  [window, Hq, d]  Query states of the local window (post-RoPE), dtype
+ *   k      [N, Hkv, d]      Key states of all prompt tokens (post-RoPE), dtype
+ *   scores [nb]             out, float
+ *   workspace               >= slim_score_blocks_workspace_bytes(Hkv, d) bytes, 256-byte aligned;
+ *                           holds the head-group-summed window query between the two kernels.
+ * Errors: INVALID_ARG (null, sizes < 1, Hq % Hkv, unit > block), UNSUPPORTED ((Hkv*d) % 8 != 0 for
+ * bf16 or % 4 for f32, or Hkv*d > 8192), WORKSPACE_TOO_SMALL.
+ */
+size_t slim_score_blocks_workspace_bytes(int n_kv_heads, int head_dim);
+int slim_score_blocks(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads,
+                      int n_kv_heads, int head_dim, int block, int unit, int dtype, float* scores,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Block selection -- last paragraph of Section 4.2: the first block (attention sink) is always
+ * kept; here the last block can be forced as well.  The remaining n_keep - #forced slots go to the
+ * other blocks by (score descending, block index ascending).  n_keep counts the forced blocks.
+ *   scores      [n_blocks] float (NaN: unspecified which blocks win)
+ *   kept_blocks [min(n_keep, n_blocks)] out, int32, ascending
+ * n_keep >= n_blocks keeps every block.  Errors: INVALID_ARG (null, n_blocks < 1,
+ * n_keep < #forced blocks).
+ */
+int slim_select_topk_blocks(const float* scores, int n_blocks, int n_keep, unsigned force_flags,
+                            int* kept_blocks, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Hidden-state pruning -- Section 4.1 ("Slim layers"): rows of the kept blocks are gathered into a
+ * dense shorter sequence, original positions ride along for RoPE.
+ *   src         [N, row_elems] dtype          dst     [n', row_elems] out
+ *   pos_in      [N] int32 or NULL (= 0..N-1)  pos_out [n'] int32 out, or NULL
+ *   kept_blocks [n_keep] int32, ascending, device.  An entry outside [0, nb) is skipped.
+ * n' = sum of the kept blocks' lengths (only block nb-1 can be short).  dst must not overlap src.
+ * Errors: INVALID_ARG (null src/dst/kept, sizes < 1, n_keep > nb).
+ */
+int slim_compact_tokens(const void* src, const int* pos_in, const int* kept_blocks, int n_keep,
+                        int block, int n_tokens, int row_elems, int dtype, void* dst, int* pos_out,
+                        void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Causal grouped-query prefill attention over a (compacted) sequence -- the "Attention" stage of
+ * Fig. 2:  out[i,h,:] = sum_{j<=i} softmax_j(scale * q[i,h,:].k[j,g,:]) v[j,g,:],  g = h/(Hq/Hkv).
+ *   q, out [n, Hq, d]   k, v [n, Hkv, d]   all dtype;  softmax_scale 0 => 1/sqrt(d)
+ * Causality is in sequence index (rows are in ascending original position after compaction).
+ * Errors: INVALID_ARG, UNSUPPORTED (bf16: d != 128; f32: d > 128 or d % 4 != 0).
+ */
+int slim_prefill_attn(const void* q, const void* k, const void* v, int n, int n_q_heads,
+                      int n_kv_heads, int head_dim, float softmax_scale, int dtype, void* out,
+                      void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Per-token building blocks of the layer ("QKV Generation" and "FFN" of Fig. 2).  Exposed so that
+ * each kernel can be checked and timed on its own.
+ */
+/* out[t,:] = gain * x[t,:] / sqrt(mean(x[t,:]^2) + eps).  x, out [n, hidden], gain [hidden]. */
+int slim_rmsnorm(const void* x, const void* gain, int n, int hidden, float eps, int dtype,
+                 void* out, void* stream);
+/* In-place rotate-half RoPE on x[n, H, d] at positions pos[n] (NULL = 0..n-1):
+ * pair (i, i+d/2) is turned by pos * theta^(-2i/d); angles are formed in double precision. */
+int slim_rope(void* x, const int* pos, int n, int n_heads, int head_dim, float theta, int dtype,
+              void* stream);
+/* out[m, n_out] = a[m, k_in] . w[n_out, k_in]^T (+ residual[m, n_out] if not NULL; may alias out).
+ * Row strides in elements: lda for a, ldo for out and residual.  bf16 needs k_in % 8 == 0. */
+int slim_linear(const void* a, int lda, const void* w, const void* residual, int m, int n_out,
+                int k_in, int ldo, int dtype, void* out, void* stream);
+/* out[m, n_out] = silu(a . w_gate^T) * (a . w_up^T), both weights [n_out, k_in]. */
+int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m,
+                       int n_out, int k_in, int ldo, int dtype, void* out, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * The pruned prefill layer: score -> select -> compact -> attention -> FFN on the kept tokens.
+ */
+typedef struct slim_layer_shape {
+    int hidden, n_q_heads, n_kv_heads, head_dim, ffn;
+    int block, unit, window;
+    float rope_theta, rms_eps;
+    int dtype;
+    unsigned flags;               /* SLIM_FORCE_FIRST | SLIM_FORCE_LAST */
+} slim_layer_shape;
+
+typedef struct slim_layer_weights {   /* device pointers, [out_features, in_features] row-major */
+    const void *g_attn, *wq, *wk, *wv, *wo, *g_ffn, *w_gate, *w_up, *w_down;
+} slim_layer_weights;
+
+/* Tokens left after keeping n_keep of the blocks of an n_tokens sequence (last block among them). */
+int slim_kept_tokens(int n_tokens, int block, int n_keep);
+
+size_t slim_pruned_layer_workspace_bytes(const slim_layer_shape* s, int n_tokens, int n_keep);
+
+/* One layer.  With n_keep >= nb it is a Preserve layer (no scoring, nothing dropped).  Otherwise:
+ * Key states of all N tokens and Query states of the last `window` tokens are formed, blocks are
+ * scored (Eq. 1-2) and selected, hidden rows / positions / keys of the kept blocks are compacted,
+ * and attention, projections and the SwiGLU FFN run on the n' kept tokens only.
+ *   s, w            host structs (w holds device pointers)
+ *   x_in [N, hidden], pos_in [N] int32 (NULL = 0..N-1)
+ *   x_out [n', hidden] out, pos_out [n'] out, kept_blocks_out [min(n_keep, nb)] out (may be NULL
+ *   for a Preserve layer), scores_out [nb] float out or NULL.
+ *   workspace: >= slim_pruned_layer_workspace_bytes(...) bytes, 256-byte aligned.
+ * x_out must not overlap x_in.  Without SLIM_FORCE_LAST, N must be a multiple of block.
+ * Errors: as the stage calls, plus WORKSPACE_TOO_SMALL.
+ */
+int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, const void* x_in,
+                      const int* pos_in, int n_tokens, int n_keep, void* x_out, int* pos_out,
+                      int* kept_blocks_out, float* scores_out, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIM_H */

@@ -1,0 +1,270 @@
+"""ctypes binding of libslim.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their data pointers, sizes
+and the current HIP stream to the C entry point of the same name, and raises on a non-zero status.
+No arithmetic of the method happens here, and there is no fallback: if the library or a GPU is
+missing, the call fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libslim.so")
+
+F32, BF16 = 0, 1
+FORCE_FIRST, FORCE_LAST = 1, 2
+
+EXPORTS = (
+    "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
+    "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
+    "slim_linear", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
+    "slim_pruned_layer",
+)
+
+
+class SlimError(RuntimeError):
+    def __init__(self, code: int, where: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{where}: status {code} ({detail})")
+
+
+class LayerShape(C.Structure):
+    _fields_ = [("hidden", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+                ("ffn", C.c_int), ("block", C.c_int), ("unit", C.c_int), ("window", C.c_int),
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int), ("flags", C.c_uint)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_ffn", "w_gate", "w_up", "w_down")]
+
+
+_lib = None
+
+
+def load_library(path: str | None = None) -> C.CDLL:
+    """Load libslim.so (built by `python -m paper_2508_06447_amd.build`).  Fails loudly if absent."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(f"{p} not found: build it with __graft_entry__.build() or "
+                                "`python paper_2508_06447_amd/build.py`")
+    lib = C.CDLL(p)
+    vp, i, f, sz, u = C.c_void_p, C.c_int, C.c_float, C.c_size_t, C.c_uint
+    lib.slim_status_string.restype = C.c_char_p
+    lib.slim_status_string.argtypes = [i]
+    lib.slim_last_hip_error.restype = C.c_char_p
+    lib.slim_last_hip_error.argtypes = []
+    lib.slim_score_blocks_workspace_bytes.restype = sz
+    lib.slim_score_blocks_workspace_bytes.argtypes = [i, i]
+    lib.slim_score_blocks.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
+    lib.slim_select_topk_blocks.argtypes = [vp, i, i, u, vp, vp]
+    lib.slim_compact_tokens.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp, vp]
+    lib.slim_prefill_attn.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp, vp]
+    lib.slim_rmsnorm.argtypes = [vp, vp, i, i, f, i, vp, vp]
+    lib.slim_rope.argtypes = [vp, vp, i, i, i, f, i, vp]
+    lib.slim_linear.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp]
+    lib.slim_swiglu_linear.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp]
+    lib.slim_kept_tokens.argtypes = [i, i, i]
+    lib.slim_pruned_layer_workspace_bytes.restype = sz
+    lib.slim_pruned_layer_workspace_bytes.argtypes = [C.POINTER(LayerShape), i, i]
+    lib.slim_pruned_layer.argtypes = [C.POINTER(LayerShape), C.POINTER(LayerWeights), vp, vp, i, i, vp, vp, vp, vp,
+                                      vp, sz, vp]
+    for name in EXPORTS:
+        getattr(lib, name)                      # every declared symbol must resolve
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        lib = load_library()
+        detail = lib.slim_status_string(code).decode()
+        if code == -4:
+            detail += ": " + lib.slim_last_hip_error().decode()
+        raise SlimError(code, where, detail)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor | None, name: str):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def n_blocks(n_tokens: int, block: int) -> int:
+    return (n_tokens + block - 1) // block
+
+
+def kept_tokens(n_tokens: int, block: int, n_keep: int) -> int:
+    return load_library().slim_kept_tokens(n_tokens, block, n_keep)
+
+
+def slim_score_blocks(q_win: torch.Tensor, k: torch.Tensor, block: int, unit: int,
+                      scores: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q_win[w,Hq,d], k[N,Hkv,d] -> scores[nb] float32 (Eq. 1-2)."""
+    lib = load_library()
+    w, Hq, d = q_win.shape
+    N, Hkv, _ = k.shape
+    if scores is None:
+        scores = torch.empty(n_blocks(N, block), dtype=torch.float32, device=k.device)
+    need = lib.slim_score_blocks_workspace_bytes(Hkv, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=k.device)
+    _check(lib.slim_score_blocks(_dev(q_win, "q_win"), _dev(k, "k"), N, w, Hq, Hkv, d, block, unit, _dtype_code(k),
+                                 _dev(scores, "scores"), _dev(workspace, "workspace"), workspace.numel(), _stream()),
+           "slim_score_blocks")
+    return scores
+
+
+def slim_select_topk_blocks(scores: torch.Tensor, n_keep: int, force_flags: int = FORCE_FIRST | FORCE_LAST,
+                            kept: torch.Tensor | None = None) -> torch.Tensor:
+    """scores[nb] float32 -> ascending int32 indices of the kept blocks."""
+    lib = load_library()
+    nb = scores.numel()
+    if kept is None:
+        kept = torch.empty(min(max(n_keep, 1), nb), dtype=torch.int32, device=scores.device)
+    _check(lib.slim_select_topk_blocks(_dev(scores, "scores"), nb, n_keep, force_flags, _dev(kept, "kept"), _stream()),
+           "slim_select_topk_blocks")
+    return kept
+
+
+def slim_compact_tokens(src: torch.Tensor, kept: torch.Tensor, block: int, pos_in: torch.Tensor | None = None,
+                        want_pos: bool = True, n_out: int | None = None):
+    """src[N, row] -> (dst[n', row], pos_out[n'] or None).  `kept` is a device int32 tensor; n' is
+    computed on the host assuming the short last block (if any) is among the kept ones unless given."""
+    lib = load_library()
+    N = src.shape[0]
+    row = src[0].numel()
+    n_keep = kept.numel()
+    if n_out is None:
+        n_out = lib.slim_kept_tokens(N, block, n_keep)
+    dst = torch.empty((n_out,) + tuple(src.shape[1:]), dtype=src.dtype, device=src.device)
+    pos_out = torch.empty(n_out, dtype=torch.int32, device=src.device) if want_pos else None
+    _check(lib.slim_compact_tokens(_dev(src, "src"), _dev(pos_in, "pos_in"), _dev(kept, "kept"), n_keep, block, N,
+                                   row, _dtype_code(src), _dev(dst, "dst"), _dev(pos_out, "pos_out"), _stream()),
+           "slim_compact_tokens")
+    return dst, pos_out
+
+
+def slim_prefill_attn(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, softmax_scale: float = 0.0,
+                      out: torch.Tensor | None = None) -> torch.Tensor:
+    """q[n,Hq,d], k/v[n,Hkv,d] -> out[n,Hq,d], causal GQA attention."""
+    lib = load_library()
+    n, Hq, d = q.shape
+    Hkv = k.shape[1]
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib.slim_prefill_attn(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), n, Hq, Hkv, d, softmax_scale,
+                                 _dtype_code(q), _dev(out, "out"), _stream()), "slim_prefill_attn")
+    return out
+
+
+def slim_rmsnorm(x: torch.Tensor, gain: torch.Tensor, eps: float, out: torch.Tensor | None = None) -> torch.Tensor:
+    lib = load_library()
+    n, hidden = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    _check(lib.slim_rmsnorm(_dev(x, "x"), _dev(gain, "gain"), n, hidden, eps, _dtype_code(x), _dev(out, "out"),
+                            _stream()), "slim_rmsnorm")
+    return out
+
+
+def slim_rope(x: torch.Tensor, pos: torch.Tensor | None, theta: float) -> torch.Tensor:
+    """In place on x[n,H,d]."""
+    lib = load_library()
+    n, H, d = x.shape
+    _check(lib.slim_rope(_dev(x, "x"), _dev(pos, "pos"), n, H, d, theta, _dtype_code(x), _stream()), "slim_rope")
+    return x
+
+
+def slim_linear(a: torch.Tensor, w: torch.Tensor, residual: torch.Tensor | None = None,
+                out: torch.Tensor | None = None) -> torch.Tensor:
+    """a[m,k] . w[n,k]^T (+ residual[m,n])."""
+    lib = load_library()
+    m, k = a.shape
+    n = w.shape[0]
+    if out is None:
+        out = torch.empty((m, n), dtype=a.dtype, device=a.device)
+    _check(lib.slim_linear(_dev(a, "a"), k, _dev(w, "w"), _dev(residual, "residual"), m, n, k, n, _dtype_code(a),
+                           _dev(out, "out"), _stream()), "slim_linear")
+    return out
+
+
+def slim_swiglu_linear(a: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
+                       out: torch.Tensor | None = None) -> torch.Tensor:
+    lib = load_library()
+    m, k = a.shape
+    n = w_gate.shape[0]
+    if out is None:
+        out = torch.empty((m, n), dtype=a.dtype, device=a.device)
+    _check(lib.slim_swiglu_linear(_dev(a, "a"), k, _dev(w_gate, "w_gate"), _dev(w_up, "w_up"), m, n, k, n,
+                                  _dtype_code(a), _dev(out, "out"), _stream()), "slim_swiglu_linear")
+    return out
+
+
+def make_shape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window, dtype: torch.dtype,
+               rope_theta=500000.0, rms_eps=1e-5, flags=FORCE_FIRST | FORCE_LAST) -> LayerShape:
+    code = BF16 if dtype == torch.bfloat16 else F32
+    return LayerShape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window, rope_theta, rms_eps, code,
+                      flags)
+
+
+def make_weights(w: dict) -> LayerWeights:
+    """`w` maps the field names of slim_layer_weights to GPU tensors (kept alive by the caller)."""
+    return LayerWeights(*[_dev(w[n], n) for n, _ in LayerWeights._fields_])
+
+
+def pruned_layer_workspace_bytes(shape: LayerShape, n_tokens: int, n_keep: int) -> int:
+    return load_library().slim_pruned_layer_workspace_bytes(C.byref(shape), n_tokens, n_keep)
+
+
+def slim_pruned_layer(shape: LayerShape, weights: dict, x: torch.Tensor, pos: torch.Tensor | None, n_keep: int,
+                      workspace: torch.Tensor | None = None, out: dict | None = None, want_scores: bool = True):
+    """One pruned prefill layer.  Returns dict(x=[n',hidden], pos=[n'], kept=[n_keep], scores=[nb] or None).
+    `out` may carry preallocated x / pos / kept / scores tensors (for timing loops)."""
+    lib = load_library()
+    N = x.shape[0]
+    nb = n_blocks(N, shape.block)
+    prune = n_keep < nb
+    n_out = lib.slim_kept_tokens(N, shape.block, n_keep) if prune else N
+    dev = x.device
+    out = dict(out) if out else {}
+    if "x" not in out:
+        out["x"] = torch.empty((n_out, shape.hidden), dtype=x.dtype, device=dev)
+    if "pos" not in out:
+        out["pos"] = torch.empty(n_out, dtype=torch.int32, device=dev)
+    if "kept" not in out:
+        out["kept"] = torch.empty(min(n_keep, nb), dtype=torch.int32, device=dev)
+    if "scores" not in out:
+        out["scores"] = torch.empty(nb, dtype=torch.float32, device=dev) if (want_scores and prune) else None
+    need = lib.slim_pruned_layer_workspace_bytes(C.byref(shape), N, n_keep)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    wstruct = make_weights(weights)
+    _check(lib.slim_pruned_layer(C.byref(shape), C.byref(wstruct), _dev(x, "x"), _dev(pos, "pos"), N, n_keep,
+                                 _dev(out["x"], "x_out"), _dev(out["pos"], "pos_out"), _dev(out["kept"], "kept"),
+                                 _dev(out["scores"], "scores"), _dev(workspace, "workspace"), workspace.numel(),
+                                 _stream()), "slim_pruned_layer")
+    return out

@@ -1,0 +1,252 @@
+// C entry points of libslim: argument checks, workspace carving and the order of kernel launches of
+// the pruned prefill layer.  No kernel lives here.
+#include "slim_common.h"
+#include <string.h>
+
+namespace slim {
+
+static thread_local char g_hip_error[256] = "";
+
+int set_hip_error(hipError_t e) {
+    strncpy(g_hip_error, hipGetErrorString(e), sizeof(g_hip_error) - 1);
+    g_hip_error[sizeof(g_hip_error) - 1] = 0;
+    return SLIM_HIP_ERROR;
+}
+
+static bool dtype_ok(int dtype) { return dtype == SLIM_F32 || dtype == SLIM_BF16; }
+
+static int forced_count(unsigned flags, int nb) {
+    int c = ((flags & SLIM_FORCE_FIRST) ? 1 : 0) + ((flags & SLIM_FORCE_LAST) ? 1 : 0);
+    return c > nb ? nb : c;
+}
+
+// Workspace layout of slim_pruned_layer (every region 256-byte aligned).
+struct LayerPlan {
+    size_t h, k_all, q_win, qt, scores, kc, vc, qc, o, act, total;
+    int nb, n_out;
+    bool prune;
+};
+
+static LayerPlan plan_layer(const slim_layer_shape* s, int N, int n_keep) {
+    LayerPlan p{};
+    const size_t es = elem_size(s->dtype);
+    p.nb = (N + s->block - 1) / s->block;
+    p.prune = n_keep < p.nb;
+    p.n_out = p.prune ? slim_kept_tokens(N, s->block, n_keep) : N;
+    const size_t kv = (size_t)s->n_kv_heads * s->head_dim, qd = (size_t)s->n_q_heads * s->head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    p.h = take((size_t)N * s->hidden * es);              // RMSNorm output: all N rows, later n' rows
+    p.k_all = take((size_t)N * kv * es);                 // Key states of all tokens
+    p.q_win = take((size_t)s->window * qd * es);
+    p.qt = take(slim_score_blocks_workspace_bytes(s->n_kv_heads, s->head_dim));
+    p.scores = take((size_t)p.nb * sizeof(float));
+    p.kc = p.prune ? take((size_t)p.n_out * kv * es) : p.k_all;   // compacted keys
+    p.vc = take((size_t)p.n_out * kv * es);
+    p.qc = take((size_t)p.n_out * qd * es);
+    p.o = take((size_t)p.n_out * qd * es);
+    p.act = take((size_t)p.n_out * s->ffn * es);
+    p.total = off;
+    return p;
+}
+
+static int check_shape(const slim_layer_shape* s) {
+    if (!s) return SLIM_INVALID_ARG;
+    if (s->hidden < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 1 || s->ffn < 1 || s->block < 1 ||
+        s->unit < 1 || s->window < 1 || s->unit > s->block || s->n_q_heads % s->n_kv_heads != 0 ||
+        !(s->rope_theta > 0.f) || !(s->rms_eps >= 0.f))
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(s->dtype)) return SLIM_UNSUPPORTED;
+    if (s->dtype == SLIM_BF16 && (s->head_dim != 128 || s->hidden % 8 != 0 || s->ffn % 8 != 0)) return SLIM_UNSUPPORTED;
+    if (s->dtype == SLIM_F32 && (s->head_dim != 32 && s->head_dim != 64 && s->head_dim != 128)) return SLIM_UNSUPPORTED;
+    return SLIM_OK;
+}
+
+}  // namespace slim
+
+using namespace slim;
+
+extern "C" {
+
+const char* slim_status_string(int code) {
+    switch (code) {
+        case SLIM_OK: return "ok";
+        case SLIM_INVALID_ARG: return "invalid argument";
+        case SLIM_UNSUPPORTED: return "unsupported shape or dtype";
+        case SLIM_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case SLIM_HIP_ERROR: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* slim_last_hip_error(void) { return g_hip_error; }
+
+size_t slim_score_blocks_workspace_bytes(int n_kv_heads, int head_dim) {
+    if (n_kv_heads < 1 || head_dim < 1) return 0;
+    return align_up((size_t)n_kv_heads * head_dim * sizeof(float), 256);
+}
+
+int slim_score_blocks(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads, int n_kv_heads,
+                      int head_dim, int block, int unit, int dtype, float* scores, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (!q_win || !k || !scores || !workspace || n_tokens < 1 || window < 1 || n_q_heads < 1 || n_kv_heads < 1 ||
+        head_dim < 1 || block < 1 || unit < 1 || unit > block || n_q_heads % n_kv_heads != 0)
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const int E = n_kv_heads * head_dim;
+    if (E % (dtype == SLIM_BF16 ? 8 : 4) != 0 || E > 8192 || !aligned16(k)) return SLIM_UNSUPPORTED;
+    if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
+    return launch_score(q_win, k, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit, dtype, scores,
+                        (float*)workspace, (hipStream_t)stream);
+}
+
+int slim_select_topk_blocks(const float* scores, int n_blocks, int n_keep, unsigned force_flags, int* kept_blocks,
+                            void* stream) {
+    if (!scores || !kept_blocks || n_blocks < 1 || n_keep < 1) return SLIM_INVALID_ARG;
+    if (n_keep < n_blocks && n_keep < forced_count(force_flags, n_blocks)) return SLIM_INVALID_ARG;
+    return launch_select(scores, n_blocks, n_keep, force_flags, kept_blocks, (hipStream_t)stream);
+}
+
+int slim_compact_tokens(const void* src, const int* pos_in, const int* kept_blocks, int n_keep, int block,
+                        int n_tokens, int row_elems, int dtype, void* dst, int* pos_out, void* stream) {
+    if (!src || !dst || !kept_blocks || n_keep < 1 || block < 1 || n_tokens < 1 || row_elems < 1) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const int nb = (n_tokens + block - 1) / block;
+    if (n_keep > nb || n_keep > 65535) return n_keep > nb ? SLIM_INVALID_ARG : SLIM_UNSUPPORTED;
+    return launch_compact(src, pos_in, kept_blocks, n_keep, block, n_tokens, row_elems, dtype, dst, pos_out,
+                          (hipStream_t)stream);
+}
+
+int slim_prefill_attn(const void* q, const void* k, const void* v, int n, int n_q_heads, int n_kv_heads,
+                      int head_dim, float softmax_scale, int dtype, void* out, void* stream) {
+    if (!q || !k || !v || !out || n < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 ||
+        n_q_heads % n_kv_heads != 0 || softmax_scale < 0.f)
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    if (dtype == SLIM_BF16 && (head_dim != 128 || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)))
+        return SLIM_UNSUPPORTED;
+    if (dtype == SLIM_F32 && head_dim != 32 && head_dim != 64 && head_dim != 128) return SLIM_UNSUPPORTED;
+    if (dtype == SLIM_F32 && n_q_heads > 65535) return SLIM_UNSUPPORTED;
+    return launch_attn(q, k, v, n, n_q_heads, n_kv_heads, head_dim, softmax_scale, dtype, out, (hipStream_t)stream);
+}
+
+int slim_rmsnorm(const void* x, const void* gain, int n, int hidden, float eps, int dtype, void* out, void* stream) {
+    if (!x || !gain || !out || n < 1 || hidden < 1 || !(eps >= 0.f)) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    return launch_rmsnorm(x, gain, n, hidden, eps, dtype, out, (hipStream_t)stream);
+}
+
+int slim_rope(void* x, const int* pos, int n, int n_heads, int head_dim, float theta, int dtype, void* stream) {
+    if (!x || n < 1 || n_heads < 1 || head_dim < 1 || !(theta > 0.f)) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype) || head_dim % 4 != 0 || head_dim > 256) return SLIM_UNSUPPORTED;
+    return launch_rope(x, pos, 0, n, n_heads, head_dim, theta, dtype, (hipStream_t)stream);
+}
+
+static int linear_checks(const void* a, int lda, const void* w, int m, int n_out, int k_in, int ldo, int dtype,
+                         const void* out) {
+    if (!a || !w || !out || m < 1 || n_out < 1 || k_in < 1 || lda < k_in || ldo < n_out) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    if (dtype == SLIM_BF16 && (k_in % 8 != 0 || lda % 8 != 0 || !aligned16(a) || !aligned16(w))) return SLIM_UNSUPPORTED;
+    return SLIM_OK;
+}
+
+int slim_linear(const void* a, int lda, const void* w, const void* residual, int m, int n_out, int k_in, int ldo,
+                int dtype, void* out, void* stream) {
+    int rc = linear_checks(a, lda, w, m, n_out, k_in, ldo, dtype, out);
+    if (rc) return rc;
+    return launch_linear(a, lda, w, nullptr, residual, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
+}
+
+int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m, int n_out, int k_in,
+                       int ldo, int dtype, void* out, void* stream) {
+    if (!w_up) return SLIM_INVALID_ARG;
+    int rc = linear_checks(a, lda, w_gate, m, n_out, k_in, ldo, dtype, out);
+    if (rc) return rc;
+    if (dtype == SLIM_BF16 && !aligned16(w_up)) return SLIM_UNSUPPORTED;
+    return launch_linear(a, lda, w_gate, w_up, nullptr, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
+}
+
+int slim_kept_tokens(int n_tokens, int block, int n_keep) {
+    if (n_tokens < 1 || block < 1 || n_keep < 1) return 0;
+    const int nb = (n_tokens + block - 1) / block;
+    if (n_keep >= nb) return n_tokens;
+    return (n_keep - 1) * block + (n_tokens - (nb - 1) * block);
+}
+
+size_t slim_pruned_layer_workspace_bytes(const slim_layer_shape* s, int n_tokens, int n_keep) {
+    if (check_shape(s) != SLIM_OK || n_tokens < 1 || n_keep < 1) return 0;
+    return plan_layer(s, n_tokens, n_keep).total;
+}
+
+int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, const void* x_in, const int* pos_in,
+                      int n_tokens, int n_keep, void* x_out, int* pos_out, int* kept_blocks_out, float* scores_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(s);
+    if (rc) return rc;
+    if (!w || !w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_ffn || !w->w_gate || !w->w_up ||
+        !w->w_down || !x_in || !x_out || !workspace || n_tokens < 1 || n_keep < 1)
+        return SLIM_INVALID_ARG;
+    const int N = n_tokens;
+    const LayerPlan p = plan_layer(s, N, n_keep);
+    if (p.prune) {
+        if (!kept_blocks_out || !pos_out) return SLIM_INVALID_ARG;
+        if (n_keep < forced_count(s->flags, p.nb)) return SLIM_INVALID_ARG;
+        if (!(s->flags & SLIM_FORCE_LAST) && N % s->block != 0) return SLIM_INVALID_ARG;
+        if (n_keep > 65535) return SLIM_UNSUPPORTED;
+    }
+    if (workspace_bytes < p.total) return SLIM_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255u) || !aligned16(x_in) || !aligned16(x_out)) return SLIM_UNSUPPORTED;
+
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char* ws = (unsigned char*)workspace;
+    const int dt = s->dtype, Hd = s->hidden, Hq = s->n_q_heads, Hkv = s->n_kv_heads, d = s->head_dim;
+    const int qd = Hq * d, kvd = Hkv * d;
+    const size_t es = elem_size(dt);
+    void *h = ws + p.h, *k_all = ws + p.k_all, *q_win = ws + p.q_win, *kc = ws + p.kc, *vc = ws + p.vc,
+         *qc = ws + p.qc, *o = ws + p.o, *act = ws + p.act;
+    float* qt = (float*)(ws + p.qt);
+#define SLIM_TRY(call) do { rc = (call); if (rc) return rc; } while (0)
+
+    // Key states of every incoming token (both paths need them).
+    SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
+    SLIM_TRY(launch_linear(h, Hd, w->wk, nullptr, nullptr, N, kvd, Hd, kvd, dt, k_all, st));
+    SLIM_TRY(launch_rope(k_all, pos_in, 0, N, Hkv, d, s->rope_theta, dt, st));
+
+    const void* resid = x_in;          // residual stream entering the attention branch
+    const int* pos = pos_in;           // positions of the rows that continue
+    const int n = p.n_out;
+    if (p.prune) {
+        // Query states of the local window (last w_eff rows), block scores, selection.
+        const int w_eff = s->window < N ? s->window : N;
+        const unsigned char* h_win = (const unsigned char*)h + (size_t)(N - w_eff) * Hd * es;
+        SLIM_TRY(launch_linear(h_win, Hd, w->wq, nullptr, nullptr, w_eff, qd, Hd, qd, dt, q_win, st));
+        SLIM_TRY(launch_rope(q_win, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, d, s->rope_theta, dt, st));
+        float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
+        SLIM_TRY(launch_score(q_win, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, dt, scores, qt, st));
+        SLIM_TRY(launch_select(scores, p.nb, n_keep, s->flags, kept_blocks_out, st));
+        // Hidden rows + positions into x_out / pos_out, keys into kc.
+        SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
+        SLIM_TRY(launch_compact(k_all, nullptr, kept_blocks_out, n_keep, s->block, N, kvd, dt, kc, nullptr, st));
+        SLIM_TRY(launch_rmsnorm(x_out, w->g_attn, n, Hd, s->rms_eps, dt, h, st));
+        resid = x_out;
+        pos = pos_out;
+    } else {
+        if (kept_blocks_out) SLIM_TRY(launch_select(nullptr, p.nb, p.nb, 0, kept_blocks_out, st));
+        if (pos_out) SLIM_TRY(launch_positions(pos_in, pos_out, N, st));
+    }
+
+    // Q, V of the rows that continue; RoPE on Q at the original positions.
+    SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, n, qd, Hd, qd, dt, qc, st));
+    SLIM_TRY(launch_rope(qc, pos, 0, n, Hq, d, s->rope_theta, dt, st));
+    SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, n, kvd, Hd, kvd, dt, vc, st));
+    SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
+    // y = resid + Wo o  (into x_out);  z = y + Wdown(silu(Wgate r) * Wup r), r = RMSNorm(y)  (in place)
+    SLIM_TRY(launch_linear(o, qd, w->wo, nullptr, resid, n, Hd, qd, Hd, dt, x_out, st));
+    SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, n, Hd, s->rms_eps, dt, h, st));
+    SLIM_TRY(launch_linear(h, Hd, w->w_gate, w->w_up, nullptr, n, s->ffn, Hd, s->ffn, dt, act, st));
+    SLIM_TRY(launch_linear(act, s->ffn, w->w_down, nullptr, x_out, n, Hd, s->ffn, Hd, dt, x_out, st));
+#undef SLIM_TRY
+    return SLIM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,279 @@
+// Block-wise prompt token pruning (Section 4.2): block scores (Eq. 1-2), block selection,
+// hidden-state compaction.  All three are HBM-/latency-bound; none uses matrix cores.
+#include "slim_common.h"
+
+namespace slim {
+
+// -------------------------------------------------------------------------------------------------
+// Scores.  By linearity of Eq. (2),
+//   (1/Hq) sum_h q_l^h . k_rep^{g(h)}(j,m) = k_rep(j,m) . qt,   qt[g,:] = (1/Hq) sum_{h in group g} q_l^h,
+// so the window query is reduced once to qt[Hkv*d] and each unit needs one dot product of length
+// Hkv*d with its mean key.
+// -------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) window_query_kernel(const T* __restrict__ q_win, int w, int Hq, int Hkv,
+                                                           int d, float* __restrict__ qt) {
+    int e = blockIdx.x * blockDim.x + threadIdx.x;      // element of [Hkv, d]
+    if (e >= Hkv * d) return;
+    int g = e / d, c = e - g * d, G = Hq / Hkv;
+    float acc = 0.f;
+    for (int h = g * G; h < (g + 1) * G; ++h) {
+        float s = 0.f;
+        for (int t = 0; t < w; ++t) s += Elem<T>::ld(q_win + ((size_t)t * Hq + h) * d + c);
+        acc += s / (float)w;                            // q_l^h[c]
+    }
+    qt[e] = acc / (float)Hq;
+}
+
+// One workgroup per block j, one wave per TokenUnit (waves stride over the units).  A wave reads its
+// unit's rows in 16-byte chunks, accumulates sum_t k[t,:] . qt, divides by the unit's token count
+// (Eq. 1 then the dot of Eq. 2) and the workgroup takes the max over units.
+template <typename T>
+__global__ void __launch_bounds__(1024) block_score_kernel(const T* __restrict__ k, const float* __restrict__ qt,
+                                                            int N, int E /*Hkv*d*/, int block, int unit,
+                                                            float* __restrict__ scores) {
+    constexpr int V = Elem<T>::kVec;
+    extern __shared__ float smem[];                      // qt copy [E] + per-wave maxima [16]
+    float* qs = smem;
+    float* wmax = smem + E;
+    const int j = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) qs[e] = qt[e];
+    __syncthreads();
+    const int b0 = j * block, b1 = min(b0 + block, N);
+    const int nchunk = E / V;
+    float best = -INFINITY;
+    for (int u0 = b0 + wave * unit; u0 < b1; u0 += nw * unit) {
+        const int u1 = min(u0 + unit, b1);
+        float acc = 0.f;
+        for (int c = lane; c < nchunk; c += 64) {
+            float ksum[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) ksum[i] = 0.f;
+#pragma unroll 8
+            for (int t = u0; t < u1; ++t) {
+                uint4 raw = *reinterpret_cast<const uint4*>(k + (size_t)t * E + (size_t)c * V);
+                float f[V];
+                Elem<T>::unpack(raw, f);
+#pragma unroll
+                for (int i = 0; i < V; ++i) ksum[i] += f[i];
+            }
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc += ksum[i] * qs[c * V + i];
+        }
+        acc = wave_sum(acc) / (float)(u1 - u0);
+        best = fmaxf(best, acc);
+    }
+    if (lane == 0) wmax[wave] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float m = wmax[0];
+        for (int i = 1; i < nw; ++i) m = fmaxf(m, wmax[i]);
+        scores[j] = m;
+    }
+}
+
+int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv, int d, int block, int unit,
+                 int dtype, float* scores, float* qtilde, hipStream_t st) {
+    const int E = Hkv * d, nb = (N + block - 1) / block;
+    const int M = (block + unit - 1) / unit;
+    const int waves = M < 1 ? 1 : (M > 16 ? 16 : M);
+    const size_t smem = (size_t)(E + 16) * sizeof(float);
+    dim3 g1((E + 255) / 256);
+    if (dtype == SLIM_BF16) {
+        hipLaunchKernelGGL(window_query_kernel<bf16_t>, g1, dim3(256), 0, st, (const bf16_t*)q_win, w, Hq, Hkv, d, qtilde);
+        hipLaunchKernelGGL(block_score_kernel<bf16_t>, dim3(nb), dim3(64 * waves), smem, st, (const bf16_t*)k,
+                           qtilde, N, E, block, unit, scores);
+    } else {
+        hipLaunchKernelGGL(window_query_kernel<float>, g1, dim3(256), 0, st, (const float*)q_win, w, Hq, Hkv, d, qtilde);
+        hipLaunchKernelGGL(block_score_kernel<float>, dim3(nb), dim3(64 * waves), smem, st, (const float*)k, qtilde,
+                           N, E, block, unit, scores);
+    }
+    return check_launch();
+}
+
+// -------------------------------------------------------------------------------------------------
+// Selection: one workgroup.  An 8-bit-digit radix select over order-preserving integer keys finds
+// the score of the last block to take; equal scores are taken in ascending index order; the kept
+// set is written ascending through a prefix sum of the keep flags.  Integer work only, so the
+// result does not depend on the order in which threads run.
+// -------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t score_key(float s) {
+    uint32_t b = __builtin_bit_cast(uint32_t, s);
+    if ((b << 1) == 0) b = 0;                            // -0.0 == +0.0
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);   // ascending in the float order
+}
+
+constexpr int kSelThreads = 1024;
+
+// Exclusive prefix sum of one int per thread across the workgroup; returns the total in `total`.
+__device__ int block_exclusive_scan(int v, int* wsum /*[16]*/, int& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int t = __shfl_up(inc, o, 64);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();                                     // wsum free from the previous use
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int i = 0; i < kSelThreads / 64; ++i) {
+        int s = wsum[i];
+        if (i < wave) base += s;
+        tot += s;
+    }
+    total = tot;
+    return base + inc - v;
+}
+
+__global__ void __launch_bounds__(kSelThreads) select_blocks_kernel(const float* __restrict__ scores, int nb,
+                                                                     int n_keep, unsigned flags,
+                                                                     int* __restrict__ kept) {
+    __shared__ int hist[256];
+    __shared__ int wsum[kSelThreads / 64];
+    __shared__ uint32_t s_prefix;
+    __shared__ int s_remaining;
+    const int tid = threadIdx.x;
+    const bool f_first = flags & SLIM_FORCE_FIRST, f_last = flags & SLIM_FORCE_LAST;
+    auto forced = [&](int j) { return (f_first && j == 0) || (f_last && j == nb - 1); };
+    const int n_forced = (f_first ? 1 : 0) + ((f_last && !(f_first && nb == 1)) ? 1 : 0);
+    const int take = n_keep - n_forced;                  // > 0 slots for the non-forced blocks, < nb - n_forced
+
+    uint32_t thr = 0;                                    // key of the last block taken
+    int n_eq = 0;                                        // how many blocks with that exact key to take
+    if (take > 0) {
+        if (tid == 0) { s_prefix = 0; s_remaining = take; }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            const uint32_t himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+            const uint32_t prefix = s_prefix;
+            for (int j = tid; j < nb; j += kSelThreads) {
+                if (forced(j)) continue;
+                uint32_t key = score_key(scores[j]);
+                if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int rem = s_remaining, bin = 255;
+                for (; bin > 0; --bin) {                 // walk down from the largest digit
+                    if (hist[bin] >= rem) break;
+                    rem -= hist[bin];
+                }
+                s_prefix = prefix | ((uint32_t)bin << shift);
+                s_remaining = rem;
+            }
+            __syncthreads();
+        }
+        thr = s_prefix;
+        n_eq = s_remaining;
+    }
+
+    int eq_seen = 0, out_base = 0;
+    for (int base = 0; base < nb; base += kSelThreads) {
+        const int j = base + tid;
+        bool in = j < nb, fz = in && forced(j);
+        uint32_t key = (in && !fz && take > 0) ? score_key(scores[j]) : 0;
+        int is_eq = (in && !fz && take > 0 && key == thr) ? 1 : 0;
+        int tot_eq;
+        int eq_rank = block_exclusive_scan(is_eq, wsum, tot_eq) + eq_seen;
+        int keep = fz || (in && !fz && take > 0 && (key > thr || (is_eq && eq_rank < n_eq)));
+        int tot_keep;
+        int slot = block_exclusive_scan(keep, wsum, tot_keep) + out_base;
+        if (keep) kept[slot] = j;
+        eq_seen += tot_eq;
+        out_base += tot_keep;
+    }
+}
+
+__global__ void iota_kernel(int* out, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = i;
+}
+
+__global__ void positions_kernel(const int* __restrict__ pos_in, int* __restrict__ pos_out, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) pos_out[i] = pos_in ? pos_in[i] : i;
+}
+
+int launch_positions(const int* pos_in, int* pos_out, int n, hipStream_t st) {
+    hipLaunchKernelGGL(positions_kernel, dim3((n + 255) / 256), dim3(256), 0, st, pos_in, pos_out, n);
+    return check_launch();
+}
+
+int launch_select(const float* scores, int nb, int n_keep, unsigned flags, int* kept, hipStream_t st) {
+    if (n_keep >= nb) {
+        hipLaunchKernelGGL(iota_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, kept, nb);
+    } else {
+        hipLaunchKernelGGL(select_blocks_kernel, dim3(1), dim3(kSelThreads), 0, st, scores, nb, n_keep, flags, kept);
+    }
+    return check_launch();
+}
+
+// -------------------------------------------------------------------------------------------------
+// Compaction: a kept block is one contiguous run of block*row bytes in src and in dst, so the gather
+// is a segmented copy.  grid = (chunks per block, kept blocks); each thread moves kCopyVecs 16-byte
+// vectors, loads first, then stores.
+// -------------------------------------------------------------------------------------------------
+constexpr int kCopyThreads = 256;
+constexpr int kCopyVecs = 4;
+
+template <typename V>
+__global__ void __launch_bounds__(kCopyThreads) compact_kernel(const V* __restrict__ src, V* __restrict__ dst,
+                                                               const int* __restrict__ kept, int block, int N,
+                                                               int nb, size_t row_vecs,
+                                                               const int* __restrict__ pos_in,
+                                                               int* __restrict__ pos_out) {
+    const int i = blockIdx.y;
+    const int kb = kept[i];
+    if ((unsigned)kb >= (unsigned)nb) return;
+    const int rows = min(block, N - kb * block);
+    const size_t seg = (size_t)rows * row_vecs;
+    const V* s = src + (size_t)kb * block * row_vecs;
+    V* d = dst + (size_t)i * block * row_vecs;
+    const size_t base = (size_t)blockIdx.x * (kCopyThreads * kCopyVecs) + threadIdx.x;
+    V tmp[kCopyVecs];
+#pragma unroll
+    for (int u = 0; u < kCopyVecs; ++u) {
+        size_t o = base + (size_t)u * kCopyThreads;
+        if (o < seg) tmp[u] = __builtin_nontemporal_load(s + o);
+    }
+#pragma unroll
+    for (int u = 0; u < kCopyVecs; ++u) {
+        size_t o = base + (size_t)u * kCopyThreads;
+        if (o < seg) __builtin_nontemporal_store(tmp[u], d + o);
+    }
+    if (blockIdx.x == 0 && pos_out) {
+        for (int r = threadIdx.x; r < rows; r += kCopyThreads) {
+            int t = kb * block + r;
+            pos_out[(size_t)i * block + r] = pos_in ? pos_in[t] : t;
+        }
+    }
+}
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+int launch_compact(const void* src, const int* pos_in, const int* kept, int n_keep, int block, int N,
+                   int row_elems, int dtype, void* dst, int* pos_out, hipStream_t st) {
+    const size_t row_bytes = (size_t)row_elems * elem_size(dtype);
+    const int nb = (N + block - 1) / block;
+    const size_t per = (size_t)kCopyThreads * kCopyVecs;
+    if (row_bytes % 16 == 0 && aligned16(src) && aligned16(dst)) {
+        size_t rv = row_bytes / 16, chunks = ((size_t)block * rv + per - 1) / per;
+        hipLaunchKernelGGL(compact_kernel<u32x4>, dim3((unsigned)chunks, n_keep), dim3(kCopyThreads), 0, st,
+                           (const u32x4*)src, (u32x4*)dst, kept, block, N, nb, rv, pos_in, pos_out);
+    } else if (row_bytes % 4 == 0) {
+        size_t rv = row_bytes / 4, chunks = ((size_t)block * rv + per - 1) / per;
+        hipLaunchKernelGGL(compact_kernel<uint32_t>, dim3((unsigned)chunks, n_keep), dim3(kCopyThreads), 0, st,
+                           (const uint32_t*)src, (uint32_t*)dst, kept, block, N, nb, rv, pos_in, pos_out);
+    } else {
+        size_t rv = row_bytes / 2, chunks = ((size_t)block * rv + per - 1) / per;
+        hipLaunchKernelGGL(compact_kernel<uint16_t>, dim3((unsigned)chunks, n_keep), dim3(kCopyThreads), 0, st,
+                           (const uint16_t*)src, (uint16_t*)dst, kept, block, N, nb, rv, pos_in, pos_out);
+    }
+    return check_launch();
+}
+
+}  // namespace slim

@@ -1,0 +1,93 @@
+// Shared device/host helpers for libslim (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "slim.h"
+
+namespace slim {
+
+typedef unsigned short bf16_t;                       // storage type of a bfloat16
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+    return __builtin_bit_cast(float, (uint32_t)v << 16);
+}
+// Round-to-nearest-even (hardware v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    return __builtin_bit_cast(bf16_t, (__bf16)f);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+__device__ __forceinline__ float lo_bf16(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+__device__ __forceinline__ float hi_bf16(uint32_t w) { return __builtin_bit_cast(float, w & 0xffff0000u); }
+
+// Element access templated on the storage type (float or bf16_t).
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kVec = 4;                   // elements per 16-byte chunk
+    __device__ static float ld(const float* p) { return *p; }
+    __device__ static void st(float* p, float v) { *p = v; }
+    __device__ static void unpack(const uint4& c, float* f) {
+        f[0] = __builtin_bit_cast(float, c.x); f[1] = __builtin_bit_cast(float, c.y);
+        f[2] = __builtin_bit_cast(float, c.z); f[3] = __builtin_bit_cast(float, c.w);
+    }
+    __device__ static uint4 pack(const float* f) {
+        return make_uint4(__builtin_bit_cast(uint32_t, f[0]), __builtin_bit_cast(uint32_t, f[1]),
+                          __builtin_bit_cast(uint32_t, f[2]), __builtin_bit_cast(uint32_t, f[3]));
+    }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int kVec = 8;
+    __device__ static float ld(const bf16_t* p) { return bf16_to_f32(*p); }
+    __device__ static void st(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+    __device__ static void unpack(const uint4& c, float* f) {
+        f[0] = lo_bf16(c.x); f[1] = hi_bf16(c.x); f[2] = lo_bf16(c.y); f[3] = hi_bf16(c.y);
+        f[4] = lo_bf16(c.z); f[5] = hi_bf16(c.z); f[6] = lo_bf16(c.w); f[7] = hi_bf16(c.w);
+    }
+    __device__ static uint4 pack(const float* f) {
+        return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]),
+                          pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+    }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+int set_hip_error(hipError_t e);                      // records text, returns SLIM_HIP_ERROR
+inline int check_launch() {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? SLIM_OK : set_hip_error(e);
+}
+inline size_t elem_size(int dtype) { return dtype == SLIM_BF16 ? 2 : 4; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+// Internal launchers (each validates nothing: the C entry points do).
+int launch_rmsnorm(const void* x, const void* gain, int n, int hidden, float eps, int dtype, void* out, hipStream_t st);
+int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float theta, int dtype, hipStream_t st);
+int launch_linear(const void* a, int lda, const void* w0, const void* w1, const void* residual, int m,
+                  int n_out, int k_in, int ldo, int dtype, void* out, hipStream_t st);
+int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv, int d, int block, int unit,
+                 int dtype, float* scores, float* qtilde, hipStream_t st);
+int launch_positions(const int* pos_in, int* pos_out, int n, hipStream_t st);
+int launch_select(const float* scores, int nb, int n_keep, unsigned flags, int* kept, hipStream_t st);
+int launch_compact(const void* src, const int* pos_in, const int* kept, int n_keep, int block, int N,
+                   int row_elems, int dtype, void* dst, int* pos_out, hipStream_t st);
+int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int Hkv, int d, float scale,
+                int dtype, void* out, hipStream_t st);
+
+}  // namespace slim

@@ -1,0 +1,119 @@
+"""GPU parity of slim_pruned_layer against the CPU oracle: the fp32 workload in full, reduced bf16
+workloads in full, and the full-size bf16 workloads on sampled output rows (scores and the kept
+set are always checked in full)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slim_oracle as so
+from paper_2508_06447_amd import inputs
+from tests.helpers import (F32_MAX_ABS, MAX_ABS, MEAN_ABS, assert_selection_matches, bf16_floor, errs, f64,
+                           oracle_shape, oracle_weights)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def slim():
+    import paper_2508_06447_amd as slim
+    slim.load_library()
+    return slim
+
+
+def run_gpu(slim, wl, x, w, pos, n_keep, flags=3):
+    shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
+                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps, flags)
+    wd = {k: v.cuda() for k, v in w.items()}
+    res = slim.slim_pruned_layer(shape, wd, x.cuda(), None if pos is None else pos.cuda(), n_keep)
+    torch.cuda.synchronize()
+    return res
+
+
+def sample_rows(n, block, count=48, seed=0):
+    g = np.random.default_rng(seed)
+    fixed = [0, 1, block - 1, block, n // 2, n - block, n - 2, n - 1, 127, 128, 255, 256]
+    rows = set(r for r in fixed if 0 <= r < n)
+    rows |= set(g.integers(0, n, max(0, count - len(rows))).tolist())
+    return np.array(sorted(rows))
+
+
+def check_layer(slim, wl, np_dtype, rows_count=None, label=""):
+    """Runs the GPU layer and the oracle on one workload; returns the numbers for the log."""
+    x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
+    n_keep = wl.n_keep
+    res = run_gpu(slim, wl, x, w, pos, n_keep)
+    s, ow = oracle_shape(wl), oracle_weights(w, np_dtype)
+    xs = x.to(torch.float32).numpy().astype(np_dtype)
+    sc_ref, _ = so.layer_scores(s, ow, xs, pos.numpy())
+    sc_gpu = f64(res["scores"])
+    sc_err = float(np.abs(sc_gpu - sc_ref).max())
+    kept_gpu = res["kept"].cpu().numpy()
+    want, band, ndiff = assert_selection_matches(kept_gpu, sc_ref.astype(np.float64), n_keep)
+    n_out = slim.kept_tokens(wl.seq, wl.block, n_keep)
+    assert res["x"].shape[0] == n_out
+    # positions and (teacher-forced on the GPU's set) the layer output
+    T = so.kept_token_index(kept_gpu, wl.block, wl.seq)
+    np.testing.assert_array_equal(res["pos"].cpu().numpy(), pos.numpy()[T])
+    rows = None if rows_count is None else sample_rows(n_out, wl.block, rows_count)
+    z_ref, fl_max, fl_mean = bf16_floor(s, ow, xs, pos.numpy(), kept_gpu, rows=rows)
+    got = res["x"] if rows is None else res["x"][torch.from_numpy(rows).cuda()]
+    mx, mean = errs(got, z_ref.astype(np.float64))
+    print(f"{label}: scores max-abs {sc_err:.2e}; kept {len(kept_gpu)} blocks, {band} in the 1e-3 band, "
+          f"{ndiff} differ; z max-abs {mx:.3e} mean-abs {mean:.3e} (bf16-rounding oracle: {fl_max:.3e} / "
+          f"{fl_mean:.3e}); |z| max {np.abs(z_ref).max():.2f}", flush=True)
+    return dict(sc_err=sc_err, mx=mx, mean=mean, fl_max=fl_max, fl_mean=fl_mean)
+
+
+def test_cfg1_fp32_full(slim):
+    wl = inputs.WORKLOADS["cfg1"]
+    r = check_layer(slim, wl, np.float64, label="cfg1")
+    assert r["sc_err"] < 1e-5 and r["mx"] < F32_MAX_ABS
+
+
+def test_cfg1_keep_all_equals_unpruned_layer(slim):
+    wl = inputs.WORKLOADS["cfg1"]
+    x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
+    res = run_gpu(slim, wl, x, w, pos, wl.n_blocks)                       # Preserve layer
+    res2 = run_gpu(slim, wl, x, w, None, wl.n_blocks + 7)                 # NULL positions, n_keep > nb
+    assert torch.equal(res["x"], res2["x"]) and torch.equal(res["pos"], res2["pos"])
+    np.testing.assert_array_equal(res["kept"].cpu().numpy(), np.arange(wl.n_blocks))
+    ref = so.pruned_layer(oracle_shape(wl), oracle_weights(w), f64(x), pos.numpy(), wl.n_blocks)
+    mx, _ = errs(res["x"], ref["z"])
+    assert mx < F32_MAX_ABS
+    np.testing.assert_array_equal(res["pos"].cpu().numpy(), pos.numpy())
+
+
+@pytest.mark.parametrize("seq,block,window,keep", [(1024, 64, 64, 0.5), (1000, 64, 64, 0.3), (1536, 128, 128, 0.25)])
+def test_reduced_bf16_layer_full_output(slim, seq, block, window, keep):
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=seq, block=block, window=window, keep_ratio=keep, planted=seq // 100)
+    r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq {seq} block {block} keep {keep}")
+    assert r["sc_err"] < 2e-3
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+
+
+def test_reduced_bf16_keep_all_and_prefix_property(slim):
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=768, keep_ratio=1.0, planted=7)
+    x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
+    full = run_gpu(slim, wl, x, w, pos, wl.n_blocks)
+    s, ow = oracle_shape(wl), oracle_weights(w)
+    z_ref, fl_max, fl_mean = bf16_floor(s, ow, f64(x), pos.numpy(), np.arange(wl.n_blocks, dtype=np.int32))
+    mx, mean = errs(full["x"], z_ref)
+    print(f"keep-all: z max-abs {mx:.3e} mean-abs {mean:.3e} (floor {fl_max:.3e}/{fl_mean:.3e})", flush=True)
+    assert mx <= max(MAX_ABS, 1.5 * fl_max) and mean <= max(MEAN_ABS, 1.5 * fl_mean)
+    # Causal attention never looks right: rows of kept blocks that form a prefix equal the unpruned rows.
+    pr = run_gpu(slim, wl, x, w, pos, 5)
+    kept = pr["kept"].cpu().numpy()
+    lead = 0
+    while lead < len(kept) and kept[lead] == lead:
+        lead += 1
+    a, b = f64(pr["x"][: lead * wl.block]), f64(full["x"][: lead * wl.block])
+    assert lead >= 1 and np.abs(a - b).max() <= 2 * MAX_ABS
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4"])
+def test_full_size_workloads_sampled_rows(slim, name):
+    wl = inputs.WORKLOADS[name]
+    print(f"{name}: N={wl.seq} nb={wl.n_blocks} n_keep={wl.n_keep} n'={wl.n_kept_tokens}", flush=True)
+    r = check_layer(slim, wl, np.float32, rows_count=40, label=name)
+    assert r["sc_err"] < 2e-3
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])

@@ -1,0 +1,73 @@
+"""The C-ABI library loads and exports every symbol that include/slim.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2508_06447_amd as slim
+    if not os.path.exists(slim.LIB_PATH):
+        from paper_2508_06447_amd.build import build_lib
+        build_lib(verbose=False)
+    return slim.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "slim.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(slim_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    import paper_2508_06447_amd as slim
+    names = declared_symbols()
+    assert len(names) >= 14 and set(names) == set(slim.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings_and_host_only_helpers(lib):
+    assert lib.slim_status_string(0) == b"ok"
+    assert b"invalid" in lib.slim_status_string(-1)
+    assert b"unsupported" in lib.slim_status_string(-2)
+    assert b"workspace" in lib.slim_status_string(-3)
+    assert lib.slim_last_hip_error() == b""
+    # n' = (n_keep-1)*block + length of the last block
+    assert lib.slim_kept_tokens(512, 16, 16) == 256
+    assert lib.slim_kept_tokens(32768, 64, 154) == 9856
+    assert lib.slim_kept_tokens(131072, 128, 205) == 26240
+    assert lib.slim_kept_tokens(45, 8, 3) == 21 and lib.slim_kept_tokens(45, 8, 6) == 45
+    assert lib.slim_score_blocks_workspace_bytes(8, 128) == 4096
+
+
+def test_argument_errors_are_reported_before_anything_is_enqueued(lib):
+    import paper_2508_06447_amd as slim
+    null = ctypes.c_void_p(0)
+    assert lib.slim_score_blocks(null, null, 8, 2, 2, 1, 8, 4, 2, 1, null, null, 0, null) == -1
+    assert lib.slim_select_topk_blocks(null, 4, 2, 3, null, null) == -1
+    assert lib.slim_compact_tokens(null, null, null, 1, 4, 8, 8, 1, null, null, null) == -1
+    assert lib.slim_prefill_attn(null, null, null, 4, 2, 1, 128, 0.0, 1, null, null) == -1
+    one = ctypes.c_void_p(256)            # non-null, never dereferenced on these paths
+    assert lib.slim_prefill_attn(one, one, one, 4, 3, 2, 128, 0.0, 1, one, null) == -1      # Hq % Hkv
+    assert lib.slim_prefill_attn(one, one, one, 4, 2, 1, 96, 0.0, 1, one, null) == -2       # head_dim
+    assert lib.slim_prefill_attn(one, one, one, 4, 2, 1, 128, 0.0, 7, one, null) == -2      # dtype
+    assert lib.slim_select_topk_blocks(one, 8, 1, 3, one, null) == -1                       # fewer than forced
+    assert lib.slim_score_blocks(one, one, 8, 2, 2, 1, 8, 4, 8, 1, one, one, 4096, null) == -1   # unit > block
+    assert lib.slim_score_blocks(one, one, 8, 2, 2, 1, 8, 4, 2, 1, one, one, 0, null) == -3      # workspace
+    assert lib.slim_linear(one, 8, one, null, 4, 4, 12, 4, 1, one, null) == -1                    # lda < k
+    assert lib.slim_linear(one, 12, one, null, 4, 4, 12, 4, 1, one, null) == -2                   # k % 8
+    shape = slim.make_shape(4096, 32, 8, 128, 14336, 64, 8, 64, __import__("torch").bfloat16)
+    need = slim.pruned_layer_workspace_bytes(shape, 32768, 154)
+    assert need > 32768 * 4096 * 2
+    w = slim.LayerWeights(*([256] * 9))
+    args = (ctypes.byref(shape), ctypes.byref(w), one, null, 32768, 154, one, one, one, null, one)
+    assert lib.slim_pruned_layer(*args, need - 1, null) == -3
+    assert lib.slim_pruned_layer(ctypes.byref(shape), ctypes.byref(w), one, null, 32768, 1, one, one, one, null,
+                                 one, need, null) == -1
+    bad = slim.make_shape(4096, 32, 8, 96, 14336, 64, 8, 64, __import__("torch").bfloat16)
+    assert slim.pruned_layer_workspace_bytes(bad, 1024, 4) == 0
