@@ -5,6 +5,11 @@
 // bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The weight tile is the MFMA "A" operand
 // and the activation tile the "B" operand, so a lane ends up with 4 consecutive output features of
 // one token and stores them as one 8-byte vector.
+//
+// Main kernel (k_in a multiple of 64): 8 waves per workgroup, two waves per SIMD, 256x256 output tile
+// (128 features x 2 matrices x 256 tokens for SwiGLU).  Operand tiles go from global memory straight
+// into LDS (global_load_lds_dwordx4, no VGPR staging), double-buffered; MFMA fragments are read one
+// k-step ahead of their use.  A register-staged kernel with k predicates covers ragged k_in.
 #include "slim_common.h"
 
 namespace slim {
@@ -18,10 +23,187 @@ constexpr int BK = 64;                                   // k-depth of an LDS ti
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 __device__ __forceinline__ int lds_off(int r, int c) { return (r * 8 + (c ^ swz(r))) * 16; }   // bytes
 
+// Epilogue shared by both bf16 kernels.  acc[w][i][j][v] is out[token m][feature n] with
+//   m = mw + j*32 + l32,   n = nw + i*32 + 8*(v/4) + 4*hh + (v%4)      (mw, nw: the wave's origin)
+template <int TW, int TA, int EPI>
+__device__ __forceinline__ void store_tile(f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 : 1][TW][TA], const bf16_t* R,
+                                           bf16_t* C, int ldo, int M, int N, int mw, int nw, int l32, int hh) {
+    constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
+    const bool vec_ok = (N % 4 == 0) && (ldo % 4 == 0);
+#pragma unroll
+    for (int j = 0; j < TA; ++j) {
+        const int m = mw + j * 32 + l32;
+        if (m >= M) continue;
+#pragma unroll
+        for (int i = 0; i < TW; ++i) {
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                const int n = nw + i * 32 + 8 * vg + 4 * hh;
+                if (n >= N) continue;
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (EPI == EPI_SWIGLU) {
+                        const float g = acc[0][i][j][vg * 4 + e], u = acc[NW - 1][i][j][vg * 4 + e];
+                        o[e] = g / (1.0f + __expf(-g)) * u;
+                    } else {
+                        o[e] = acc[0][i][j][vg * 4 + e];
+                    }
+                }
+                bf16_t* dst = C + (size_t)m * ldo + n;
+                if (vec_ok) {
+                    if (EPI == EPI_RESIDUAL) {
+                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * ldo + n);
+                        o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
+                    }
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (n + e < N) {
+                            float val = o[e];
+                            if (EPI == EPI_RESIDUAL) val += bf16_to_f32(R[(size_t)m * ldo + n + e]);
+                            dst[e] = f32_to_bf16(val);
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// Workgroup -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, so each XCD gets a
+// contiguous run of logical tiles; inside the run, bands of GM token-tiles are walked feature-tile by
+// feature-tile, so the workgroups resident on one XCD share few distinct operand tiles in its L2.
+__device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int& tm, int& tn) {
+    int L = blockIdx.x;
+    const int total = tiles_m * tiles_n;
+    if (total % 8 == 0) L = (L & 7) * (total >> 3) + (L >> 3);
+    constexpr int GM = 8;
+    const int band_sz = GM * tiles_n;
+    const int band = L / band_sz;
+    const int gm = min(GM, tiles_m - band * GM);
+    const int rem = L - band * band_sz;
+    tm = band * GM + rem % gm;
+    tn = rem / gm;
+}
+
+// One 16-byte-per-lane load from global memory straight into LDS.  The LDS address of lane l is
+// (wave-uniform base) + 16*l; the base travels in M0.  The compiler does not see this as an LDS write,
+// so callers order it against LDS reads themselves: s_waitcnt vmcnt + workgroup barrier.
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_global_to_lds16(const void* g, void* lds_wave_base) {
+    const unsigned la = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
+}
+__device__ __forceinline__ void workgroup_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// Main kernel.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned rows.
+template <int TW, int TA, int WGN, int WGM, int EPI>
+__global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
+                                                        const bf16_t* __restrict__ W0,
+                                                        const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
+                                                        int ldo, int M, int N, int K, int tiles_m, int tiles_n) {
+    static_assert(WGN * WGM == 8, "8 waves");
+    constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM, WROWS = BN * NW;
+    constexpr int STAGE = (WROWS + BM) * BK * 2;
+    constexpr int WLD = WROWS / 64, ALD = BM / 64;       // wave-loads per k-tile per wave (8 rows each)
+    static_assert(WLD * 64 == WROWS && ALD * 64 == BM, "tile rows must split over 8 waves x 8 rows");
+    extern __shared__ __align__(16) unsigned char lds[];
+    int tm, tn;
+    tile_of_workgroup(tiles_m, tiles_n, tm, tn);
+    const int n0 = tn * BN, m0 = tm * BM;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave % WGN, wm = wave / WGN;
+    const int l32 = lane & 31, hh = lane >> 5;
+
+    // Wave-load i covers rows (i*8 + wave)*8 + lane/8 of the tile; lane%8 is the LDS chunk slot, which
+    // holds logical chunk slot ^ swz(row).  Row pointers are loop-invariant.
+    const bf16_t* wsrc[WLD];
+    const bf16_t* asrc[ALD];
+#pragma unroll
+    for (int i = 0; i < WLD; ++i) {
+        const int r = (i * 8 + wave) * 8 + (lane >> 3);
+        const int mat = NW == 2 ? r / BN : 0;
+        const int n = min(n0 + r - mat * BN, N - 1);
+        wsrc[i] = (mat ? W1 : W0) + (size_t)n * K + ((lane & 7) ^ swz(r)) * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < ALD; ++i) {
+        const int r = (i * 8 + wave) * 8 + (lane >> 3);
+        asrc[i] = A + (size_t)min(m0 + r, M - 1) * lda + ((lane & 7) ^ swz(r)) * 8;
+    }
+    auto issue_loads = [&](int k0, int stage) {
+        unsigned char* ws = lds + stage * STAGE;
+        unsigned char* as = ws + WROWS * BK * 2;
+#pragma unroll
+        for (int i = 0; i < WLD; ++i) load_global_to_lds16(wsrc[i] + k0, ws + (i * 8 + wave) * 1024);
+#pragma unroll
+        for (int i = 0; i < ALD; ++i) load_global_to_lds16(asrc[i] + k0, as + (i * 8 + wave) * 1024);
+    };
+
+    f32x16 acc[NW][TW][TA];
+#pragma unroll
+    for (int w = 0; w < NW; ++w)
+#pragma unroll
+        for (int i = 0; i < TW; ++i)
+#pragma unroll
+            for (int j = 0; j < TA; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[w][i][j][v] = 0.f;
+
+    const int KT = K / BK;
+    issue_loads(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
+    workgroup_barrier();
+    for (int kt = 0; kt < KT; ++kt) {
+        // The other stage was last read in iteration kt-1, which every wave has left.
+        if (kt + 1 < KT) issue_loads((kt + 1) * BK, (kt + 1) & 1);
+        const unsigned char* ws = lds + (kt & 1) * STAGE;
+        const unsigned char* as = ws + WROWS * BK * 2;
+        bf16x8 af[2][TA], wf[2][NW][TW];
+        auto load_frags = [&](int ks, int buf) {
+#pragma unroll
+            for (int j = 0; j < TA; ++j)
+                af[buf][j] = *reinterpret_cast<const bf16x8*>(as + lds_off((wm * TA + j) * 32 + l32, ks * 2 + hh));
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int i = 0; i < TW; ++i)
+                    wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(
+                        ws + lds_off(w * BN + (wn * TW + i) * 32 + l32, ks * 2 + hh));
+        };
+        load_frags(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            const int cur = ks & 1;
+            if (ks + 1 < BK / 16) load_frags(ks + 1, cur ^ 1);
+            __builtin_amdgcn_sched_barrier(0);           // keep the next step's LDS reads ahead of these MFMAs
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int i = 0; i < TW; ++i)
+#pragma unroll
+                    for (int j = 0; j < TA; ++j)
+                        acc[w][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][w][i], af[cur][j], acc[w][i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_s_waitcnt(0x0070);              // this wave's tile kt+1 has landed; its LDS reads are done
+        workgroup_barrier();
+    }
+    store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+}
+
+// Generic kernel (any k_in that is a multiple of 8): register-staged loads with k predicates.
 // TW x TA: number of 32-row MFMA tiles per wave along the weight (n) and activation (m) directions.
 // Workgroup = 4 waves arranged WGN x WGM.  SwiGLU uses two weight tiles per n (gate, up).
 template <int TW, int TA, int WGN, int WGM, int EPI>
-__global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
+__global__ void __launch_bounds__(256) gemm_bf16_generic_kernel(const bf16_t* __restrict__ A, int lda,
                                                         const bf16_t* __restrict__ W0,
                                                         const bf16_t* __restrict__ W1,
                                                         const bf16_t* R, bf16_t* C, int ldo, int M, int N, int K,
@@ -34,18 +216,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict
     constexpr int STAGE = (WROWS + BM) * BK * 2;         // bytes per LDS stage
     extern __shared__ __align__(16) unsigned char lds[];
 
-    // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so give each XCD a
-    // contiguous run of logical tiles; inside the run walk bands of GM token-tiles, feature-tile by
-    // feature-tile, so the workgroups resident on one XCD share few distinct operand tiles in its L2.
-    int L = blockIdx.x;
-    const int total = tiles_m * tiles_n;
-    if (total % 8 == 0) L = (L & 7) * (total >> 3) + (L >> 3);
-    constexpr int GM = 8;
-    const int band_sz = GM * tiles_n;
-    const int band = L / band_sz;
-    const int gm = min(GM, tiles_m - band * GM);
-    const int rem = L - band * band_sz;
-    const int tm = band * GM + rem % gm, tn = rem / gm;
+    int tm, tn;
+    tile_of_workgroup(tiles_m, tiles_n, tm, tn);
     const int n0 = tn * BN, m0 = tm * BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -124,58 +296,18 @@ __global__ void __launch_bounds__(256) gemm_bf16_kernel(const bf16_t* __restrict
         __syncthreads();
     }
 
-    // epilogue: acc[..][i][j][v] is out[token m][feature n] with
-    //   m = m0 + (wm*TA + j)*32 + l32,   n = n0 + (wn*TW + i)*32 + 8*(v/4) + 4*hh + (v%4)
-    const bool vec_ok = (N % 4 == 0) && (ldo % 4 == 0);
-#pragma unroll
-    for (int j = 0; j < TA; ++j) {
-        const int m = m0 + (wm * TA + j) * 32 + l32;
-        if (m >= M) continue;
-#pragma unroll
-        for (int i = 0; i < TW; ++i) {
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                const int n = n0 + (wn * TW + i) * 32 + 8 * vg + 4 * hh;
-                if (n >= N) continue;
-                float o[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (EPI == EPI_SWIGLU) {
-                        const float g = acc[0][i][j][vg * 4 + e], u = acc[NW - 1][i][j][vg * 4 + e];
-                        o[e] = g / (1.0f + __expf(-g)) * u;
-                    } else {
-                        o[e] = acc[0][i][j][vg * 4 + e];
-                    }
-                }
-                bf16_t* dst = C + (size_t)m * ldo + n;
-                if (vec_ok) {
-                    if (EPI == EPI_RESIDUAL) {
-                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * ldo + n);
-                        o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
-                    }
-                    *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        if (n + e < N) {
-                            float val = o[e];
-                            if (EPI == EPI_RESIDUAL) val += bf16_to_f32(R[(size_t)m * ldo + n + e]);
-                            dst[e] = f32_to_bf16(val);
-                        }
-                    }
-                }
-            }
-        }
-    }
+    store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
 }
 
-template <int TW, int TA, int WGN, int WGM, int EPI>
+template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC>
 static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                        int ldo, int M, int N, int K, hipStream_t st) {
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM;
     constexpr size_t smem = 2 * (size_t)(BN * NW + BM) * BK * 2;
-    auto kern = gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
+    void (*kern)(const bf16_t*, int, const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, int, int, int, int, int, int);
+    if constexpr (GENERIC) kern = gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>;
+    else kern = gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
     static bool attr_done = false;                       // raising the LDS limit is per function, once
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -183,9 +315,21 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
         attr_done = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), smem, st, A, lda, W0, W1, R, C, ldo, M, N, K,
-                       tiles_m, tiles_n);
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem, st, A, lda, W0, W1, R, C, ldo, M, N,
+                       K, tiles_m, tiles_n);
     return check_launch();
+}
+
+template <int EPI>
+static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
+                         int ldo, int M, int N, int K, hipStream_t st) {
+    if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    if (EPI == EPI_SWIGLU) {
+        if (M <= 128) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+        return launch_bf16<2, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    }
+    if (M <= 128) return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    return launch_bf16<4, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
@@ -254,13 +398,9 @@ int launch_linear(const void* a, int lda, const void* w0, const void* w1, const 
     }
     const bf16_t *A = (const bf16_t*)a, *W0 = (const bf16_t*)w0, *W1 = (const bf16_t*)w1, *R = (const bf16_t*)residual;
     bf16_t* C = (bf16_t*)out;
-    if (w1) return launch_bf16<2, 4, 2, 2, EPI_SWIGLU>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
-    if (m <= 128) {
-        if (residual) return launch_bf16<2, 2, 2, 2, EPI_RESIDUAL>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
-        return launch_bf16<2, 2, 2, 2, EPI_PLAIN>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
-    }
-    if (residual) return launch_bf16<4, 4, 2, 2, EPI_RESIDUAL>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
-    return launch_bf16<4, 4, 2, 2, EPI_PLAIN>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
+    if (w1) return dispatch_bf16<EPI_SWIGLU>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
+    if (residual) return dispatch_bf16<EPI_RESIDUAL>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
+    return dispatch_bf16<EPI_PLAIN>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
 }
 
 }  // namespace slim

@@ -10,19 +10,28 @@ namespace slim {
 // so the window query is reduced once to qt[Hkv*d] and each unit needs one dot product of length
 // Hkv*d with its mean key.
 // -------------------------------------------------------------------------------------------------
+// 64 elements of qt per workgroup, 16 slices of the window per element (slice s takes tokens s, s+16, ..);
+// the slices are summed in a fixed order through LDS, so the result is deterministic.
 template <typename T>
-__global__ void __launch_bounds__(256) window_query_kernel(const T* __restrict__ q_win, int w, int Hq, int Hkv,
-                                                           int d, float* __restrict__ qt) {
-    int e = blockIdx.x * blockDim.x + threadIdx.x;      // element of [Hkv, d]
-    if (e >= Hkv * d) return;
-    int g = e / d, c = e - g * d, G = Hq / Hkv;
+__global__ void __launch_bounds__(1024) window_query_kernel(const T* __restrict__ q_win, int w, int Hq, int Hkv,
+                                                            int d, float* __restrict__ qt) {
+    __shared__ float part[16][64];
+    const int le = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int e = blockIdx.x * 64 + le;                  // element of [Hkv, d]
     float acc = 0.f;
-    for (int h = g * G; h < (g + 1) * G; ++h) {
-        float s = 0.f;
-        for (int t = 0; t < w; ++t) s += Elem<T>::ld(q_win + ((size_t)t * Hq + h) * d + c);
-        acc += s / (float)w;                            // q_l^h[c]
+    if (e < Hkv * d) {
+        const int g = e / d, c = e - g * d, G = Hq / Hkv;
+        for (int t = slice; t < w; t += 16)
+            for (int h = g * G; h < (g + 1) * G; ++h) acc += Elem<T>::ld(q_win + ((size_t)t * Hq + h) * d + c);
     }
-    qt[e] = acc / (float)Hq;
+    part[slice][le] = acc;
+    __syncthreads();
+    if (slice == 0 && e < Hkv * d) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += part[i][le];
+        qt[e] = s / ((float)w * (float)Hq);              // mean over the window, then mean over heads
+    }
 }
 
 // One workgroup per block j, one wave per TokenUnit (waves stride over the units).  A wave reads its
@@ -78,13 +87,13 @@ int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv
     const int M = (block + unit - 1) / unit;
     const int waves = M < 1 ? 1 : (M > 16 ? 16 : M);
     const size_t smem = (size_t)(E + 16) * sizeof(float);
-    dim3 g1((E + 255) / 256);
+    dim3 g1((E + 63) / 64);
     if (dtype == SLIM_BF16) {
-        hipLaunchKernelGGL(window_query_kernel<bf16_t>, g1, dim3(256), 0, st, (const bf16_t*)q_win, w, Hq, Hkv, d, qtilde);
+        hipLaunchKernelGGL(window_query_kernel<bf16_t>, g1, dim3(1024), 0, st, (const bf16_t*)q_win, w, Hq, Hkv, d, qtilde);
         hipLaunchKernelGGL(block_score_kernel<bf16_t>, dim3(nb), dim3(64 * waves), smem, st, (const bf16_t*)k,
                            qtilde, N, E, block, unit, scores);
     } else {
-        hipLaunchKernelGGL(window_query_kernel<float>, g1, dim3(256), 0, st, (const float*)q_win, w, Hq, Hkv, d, qtilde);
+        hipLaunchKernelGGL(window_query_kernel<float>, g1, dim3(1024), 0, st, (const float*)q_win, w, Hq, Hkv, d, qtilde);
         hipLaunchKernelGGL(block_score_kernel<float>, dim3(nb), dim3(64 * waves), smem, st, (const float*)k, qtilde,
                            N, E, block, unit, scores);
     }
