@@ -1,12 +1,13 @@
 // Causal grouped-query prefill attention ("Attention" stage of Fig. 2) over the compacted sequence.
 //
 // bf16 path (head_dim 128): flash-style single pass with online softmax, v_mfma_f32_32x32x16_bf16.
-// A workgroup of 4 waves owns 128 queries of one head, each wave 32 of them; K/V tiles of 64 keys
-// are staged in LDS (K row-major, V transposed) and double-buffered.
+// A workgroup of 8 waves (two per SIMD) owns 256 queries of one head, each wave 32 of them.  K/V tiles
+// of 64 keys go from global memory straight into LDS (global_load_lds_dwordx4), both row-major, in a
+// ring of 3 stages; V fragments are read with the transposing LDS read (ds_read_b64_tr_b16).
 //
 // Both products are computed transposed so that no register shuffle is needed between them:
 //   S^T[key, query] = K . Q^T      (A operand = K rows from LDS, B operand = Q rows held in VGPRs)
-//   O^T[d,   query] = V^T . P^T    (A operand = V^T rows from LDS, B operand = P^T from the S^T
+//   O^T[d,   query] = V^T . P^T    (A operand = V^T from LDS, B operand = P^T from the S^T
 //                                   accumulators, converted to bf16 in place)
 // In the 32x32 accumulator layout a lane owns one query column, so the softmax statistics of a query
 // live in two lanes (l and l^32) and need a single cross-lane exchange per tile.  The accumulator's
@@ -16,20 +17,28 @@
 
 namespace slim {
 
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+#define SLIM_LDS_PTR(T, addr) ((__attribute__((address_space(3))) T*)(uintptr_t)(addr))
+
 constexpr int AD = 128;          // head_dim of the MFMA path
-constexpr int BQ = 128;          // queries per workgroup
+constexpr int ANW = 8;           // waves per workgroup
+constexpr int BQ = 32 * ANW;     // queries per workgroup
 constexpr int BKV = 64;          // keys per tile
-constexpr int K_TILE_BYTES = BKV * AD * 2;
-constexpr int KV_STAGE_BYTES = 2 * K_TILE_BYTES;
+constexpr int NSTAGE = 3;        // K/V tiles resident in LDS
+constexpr int TILE_BYTES = BKV * AD * 2;
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;             // K tile, then V tile
 
-// K tile: row = key, 16 chunks of 16 B per row; chunk c of row r stored at slot c ^ (r & 15).
+// Both tiles: row = key, 256 B = 16 chunks of 16 B.  K: chunk c of row r sits at slot c ^ (r & 15), so
+// the 128-bit fragment reads (32 rows, one chunk column) are conflict-free.  V: slot c ^ (4 * (r & 3)),
+// which spreads the 4 key rows x 4 chunks that one transposing read touches over all banks.
 __device__ __forceinline__ int k_off(int r, int c) { return (r * 16 + (c ^ (r & 15))) * 16; }
-// V^T tile: row = d index, 16 units of 8 B (4 keys) per row; unit u of row r at slot u ^ ((r >> 1) & 15).
-__device__ __forceinline__ int vt_off(int r, int u) { return (r * 16 + (u ^ ((r >> 1) & 15))) * 8; }
+__device__ __forceinline__ int v_off(int r, int c) { return (r * 16 + (c ^ ((r & 3) << 2))) * 16; }
 
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) attn_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kg,
-                                                        const bf16_t* __restrict__ Vg, bf16_t* __restrict__ O,
-                                                        int n, int Hq, int Hkv, float scale_log2e, int n_qt) {
+__global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kg,
+                                                             const bf16_t* __restrict__ Vg, bf16_t* __restrict__ O,
+                                                             int n, int Hq, int Hkv, float scale_log2e, int n_qt) {
     extern __shared__ __align__(16) unsigned char lds[];
     // Workgroup -> (head, query tile).  Ids are dealt round-robin to the 8 XCDs; give each XCD a
     // contiguous range of heads so the query heads sharing a kv head meet in one L2, and start the
@@ -37,15 +46,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
     int L = blockIdx.x;
     const int total = n_qt * Hq;
     if (total % 8 == 0) L = (L & 7) * (total >> 3) + (L >> 3);
-    const int h = L / n_qt, qt = n_qt - 1 - (L - h * n_qt);
+    const int h = L / n_qt, qt_idx = n_qt - 1 - (L - h * n_qt);
     const int g = h / (Hq / Hkv);
-    const int q0 = qt * BQ;
-
+    const int q0 = qt_idx * BQ;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hh = lane >> 5;
     const int qw0 = q0 + wave * 32;                       // first query of this wave
     const int qi = qw0 + l32;                             // this lane's query
     const size_t qstride = (size_t)Hq * AD, kvstride = (size_t)Hkv * AD;
+    const unsigned lds_base = (unsigned)(uintptr_t)lds;
 
     // Q fragments (B operand): 8 k-steps x 8 bf16 of row qi, d = ks*16 + hh*8 ..
     bf16x8 qf[8];
@@ -55,48 +64,39 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
         for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
     }
 
-    // staging registers for the next K/V tile
-    uint4 kreg[4];
-    uint2 vreg[2][4];
+    // Tile t -> stage t % NSTAGE.  A wave-load moves 4 key rows x 256 B; each tile is 16 wave-loads for
+    // K and 16 for V, two of each per wave.  Lane l lands at LDS slot l%16 of row l/16, so it fetches the
+    // global chunk that the swizzle assigns to that slot.  Tiles past the end re-read the last tile into
+    // a stage nobody reads, which keeps the count of loads in flight the same in every iteration.
     const bf16_t* kbase = Kg + (size_t)g * AD;
     const bf16_t* vbase = Vg + (size_t)g * AD;
-    // K: thread owns chunk (tid & 15) of rows (tid >> 4) + 16*i.
-    // V: thread owns d-group dg = tid & 31 (d = 4*dg..+3) and key-groups kg = (tid >> 5) + 8*i (keys 4*kg..+3).
-    auto load_kv = [&](int k0) {
+    const int n_kt_all = (n + BKV - 1) / BKV;
+    auto issue_tile = [&](int t) {
+        const int k0 = min(t, n_kt_all - 1) * BKV;
+        unsigned char* stage = lds + (t % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = min(k0 + (tid >> 4) + 16 * i, n - 1);
-            kreg[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)r * kvstride + (tid & 15) * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const int r = min(k0 + 4 * ((tid >> 5) + 8 * i) + kk, n - 1);
-                vreg[i][kk] = *reinterpret_cast<const uint2*>(vbase + (size_t)r * kvstride + (tid & 31) * 4);
-            }
-    };
-    auto store_kv = [&](int stage) {
-        unsigned char* ks = lds + stage * KV_STAGE_BYTES;
-        unsigned char* vs = ks + K_TILE_BYTES;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(ks + k_off((tid >> 4) + 16 * i, tid & 15)) = kreg[i];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int kg = (tid >> 5) + 8 * i, dg = tid & 31;
-            // 4 keys x 4 d  ->  4 d-rows x 4 keys
-            const uint32_t a0 = vreg[i][0].x, a1 = vreg[i][0].y, b0 = vreg[i][1].x, b1 = vreg[i][1].y;
-            const uint32_t c0 = vreg[i][2].x, c1 = vreg[i][2].y, e0 = vreg[i][3].x, e1 = vreg[i][3].y;
-            uint2 r0 = make_uint2((a0 & 0xffffu) | (b0 << 16), (c0 & 0xffffu) | (e0 << 16));          // d + 0
-            uint2 r1 = make_uint2((a0 >> 16) | (b0 & 0xffff0000u), (c0 >> 16) | (e0 & 0xffff0000u));  // d + 1
-            uint2 r2 = make_uint2((a1 & 0xffffu) | (b1 << 16), (c1 & 0xffffu) | (e1 << 16));          // d + 2
-            uint2 r3 = make_uint2((a1 >> 16) | (b1 & 0xffff0000u), (c1 >> 16) | (e1 & 0xffff0000u));  // d + 3
-            *reinterpret_cast<uint2*>(vs + vt_off(4 * dg + 0, kg)) = r0;
-            *reinterpret_cast<uint2*>(vs + vt_off(4 * dg + 1, kg)) = r1;
-            *reinterpret_cast<uint2*>(vs + vt_off(4 * dg + 2, kg)) = r2;
-            *reinterpret_cast<uint2*>(vs + vt_off(4 * dg + 3, kg)) = r3;
+        for (int i = 0; i < 16 / ANW; ++i) {
+            const int rg = i * ANW + wave, r = rg * 4 + (lane >> 4), slot = lane & 15;
+            const size_t row = (size_t)min(k0 + r, n - 1) * kvstride;
+            load_global_to_lds16(kbase + row + (slot ^ (r & 15)) * 8, stage + rg * 1024);
+            load_global_to_lds16(vbase + row + (slot ^ ((r & 3) << 2)) * 8, stage + TILE_BYTES + rg * 1024);
         }
     };
+
+    // Per-lane LDS byte offsets inside a stage (loop-invariant); tile rows are added as immediates.
+    unsigned koff[8], voff[4];
+#pragma unroll
+    for (int st = 0; st < 8; ++st) koff[st] = k_off(l32, st * 2 + hh);
+    {
+        // Transposing read: in each group of 16 lanes, lane s supplies the address of 4 consecutive d of
+        // key (s/4) and receives, for d = D0 + s, the 4 consecutive keys.  Lane groups 0/1 cover d 0-15 /
+        // 16-31 of the fragment, groups 2/3 the keys 4-7 (the accumulator rows owned by lanes 32-63).
+        const int G = lane >> 4, sl = lane & 15;
+        const int key_lane = 4 * (G >> 1) + (sl >> 2);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+            voff[dt] = TILE_BYTES + v_off(key_lane, dt * 4 + 2 * (G & 1) + ((sl & 3) >> 1)) + (sl & 1) * 8;
+    }
 
     f32x16 oacc[4];
 #pragma unroll
@@ -107,15 +107,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
 
     const int last_q = min(q0 + BQ, n) - 1;
     const int n_kt = last_q / BKV + 1;                    // causal: tiles up to the last query's diagonal
-    load_kv(0);
-    store_kv(0);
-    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < NSTAGE - 1; ++t) issue_tile(t);
+    __builtin_amdgcn_s_waitcnt(0x0070);                   // vmcnt(0) lgkmcnt(0)
+    workgroup_barrier();
+
     for (int kt = 0; kt < n_kt; ++kt) {
         const int k0 = kt * BKV;
-        if (kt + 1 < n_kt) load_kv(k0 + BKV);
+        issue_tile(kt + NSTAGE - 1);                      // its stage held tile kt-1, which every wave has left
         if (k0 <= qw0 + 31) {                             // some key of the tile is visible to this wave
-            const unsigned char* ks = lds + (kt & 1) * KV_STAGE_BYTES;
-            const unsigned char* vs = ks + K_TILE_BYTES;
+            const unsigned sb = lds_base + (kt % NSTAGE) * STAGE_BYTES;
             // ---- S^T = K Q^T : two 32-key sub-tiles
             f32x16 s[2];
 #pragma unroll
@@ -124,68 +125,77 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))
                 for (int v = 0; v < 16; ++v) s[jt][v] = 0.f;
 #pragma unroll
                 for (int st = 0; st < 8; ++st) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + k_off(jt * 32 + l32, st * 2 + hh));
+                    const bf16x8 kf = *(SLIM_LDS_PTR(const bf16x8, sb + koff[st]) + jt * (32 * 256 / 16));
                     s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[jt], 0, 0, 0);
                 }
             }
-            // ---- mask + running max (log2 domain)
-            const bool need_mask = (k0 + BKV - 1 > qw0) || (k0 + BKV > n);
+            // ---- causal / ragged mask (selects only; the branch is wave-uniform)
+            if ((k0 + BKV - 1 > qw0) || (k0 + BKV > n)) {
+                const int lim = min(qi, n - 1) - k0 - 4 * hh;     // visible: key offset in the tile <= lim
+#pragma unroll
+                for (int jt = 0; jt < 2; ++jt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        s[jt][v] = (jt * 32 + 8 * (v >> 2) + (v & 3)) > lim ? -INFINITY : s[jt][v];
+            }
+            // ---- running max in the log2 domain (softmax_scale > 0, so the max commutes with it)
             float tmax = -INFINITY;
 #pragma unroll
             for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float x = s[jt][v] * scale_log2e;
-                    if (need_mask) {
-                        const int key = k0 + jt * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-                        if (key > qi || key >= n) x = -INFINITY;
-                    }
-                    s[jt][v] = x;
-                    tmax = fmaxf(tmax, x);
-                }
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+                for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[jt][v]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * scale_log2e;
             const float m_new = fmaxf(m_run, tmax);       // finite: key 0 is visible to every query
+            const bool changed = m_new > m_run;
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
+            // ---- P = exp2(S*c - m), rounded to bf16 for the MFMA; the row sum adds the rounded values
+            uint32_t pb[2][8];
             float psum = 0.f;
-            uint32_t pb[2][8];                            // P^T as bf16 pairs: [sub-tile][v/2]
+            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
             for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                 for (int v = 0; v < 16; v += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(s[jt][v] - m_new);
-                    const float p1 = __builtin_amdgcn_exp2f(s[jt][v + 1] - m_new);
-                    psum += p0 + p1;
-                    pb[jt][v >> 1] = pack_bf16x2(p0, p1);
+                    const f32x2 p = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[jt][v], scale_log2e, -m_new)),
+                                     __builtin_amdgcn_exp2f(__builtin_fmaf(s[jt][v + 1], scale_log2e, -m_new))};
+                    const bf16x2 p2 = __builtin_convertvector(p, bf16x2);
+                    psum = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, psum, false);
+                    pb[jt][v >> 1] = __builtin_bit_cast(uint32_t, p2);
                 }
             l_run = l_run * alpha + psum;
+            if (__any(changed)) {                         // rescale only when some row's max moved
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
+                for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+            }
             // ---- O^T += V^T P^T : 4 k-steps of 16 keys; step (jt, half) uses accumulator values
             //      v = half*8 .. half*8+7 of sub-tile jt, i.e. keys jt*32 + half*16 + {4*hh+0..3, 8+4*hh+0..3}
+            constexpr int ROW = 256 / 8;                  // one key row in units of 8 bytes
 #pragma unroll
             for (int jt = 0; jt < 2; ++jt)
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
-                    const uint4 pw = make_uint4(pb[jt][half * 4 + 0], pb[jt][half * 4 + 1], pb[jt][half * 4 + 2],
-                                                pb[jt][half * 4 + 3]);
-                    const bf16x8 pf = __builtin_bit_cast(bf16x8, pw);
-                    const int u0 = jt * 8 + half * 4 + hh;       // 4-key unit of keys 4*hh.. ; second unit is +2
+                    const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pb[jt][half * 4 + 0], pb[jt][half * 4 + 1],
+                                                                            pb[jt][half * 4 + 2], pb[jt][half * 4 + 3]));
+                    const int r0 = (jt * 32 + half * 16) * ROW;
 #pragma unroll
                     for (int dt = 0; dt < 4; ++dt) {
-                        const int r = dt * 32 + l32;
-                        const uint2 lo = *reinterpret_cast<const uint2*>(vs + vt_off(r, u0));
-                        const uint2 hi = *reinterpret_cast<const uint2*>(vs + vt_off(r, u0 + 2));
-                        const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+                        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SLIM_LDS_PTR(i16x4, sb + voff[dt]) + r0);
+                        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SLIM_LDS_PTR(i16x4, sb + voff[dt]) + r0 + 8 * ROW);
+                        const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
+                        const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
                         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
                     }
                 }
         }
-        if (kt + 1 < n_kt) store_kv((kt + 1) & 1);
-        __syncthreads();
+        // Tile kt+1 has landed for this wave (the newer tile's loads may stay in flight); its own LDS
+        // reads are done; after the barrier that holds for every wave.
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((32 / ANW) * (NSTAGE - 2)));
+        workgroup_barrier();
     }
+    __builtin_amdgcn_s_waitcnt(0x0070);                   // drain the trailing loads before the wave ends
 
     // ---- normalise and store: lane holds O[qi][h][dt*32 + 8*(v/4) + 4*hh + v%4]
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -245,7 +255,7 @@ int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int 
     if (scale == 0.f) scale = 1.0f / sqrtf((float)d);
     if (dtype == SLIM_BF16) {
         static bool attr_done = false;
-        const int smem = 2 * KV_STAGE_BYTES;
+        const int smem = NSTAGE * STAGE_BYTES;
         if (!attr_done) {
             hipError_t e = hipFuncSetAttribute((const void*)attn_bf16_kernel,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -253,7 +263,7 @@ int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int 
             attr_done = true;
         }
         const int n_qt = (n + BQ - 1) / BQ;
-        hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_qt * Hq), dim3(256), smem, st, (const bf16_t*)q, (const bf16_t*)k,
+        hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_qt * Hq), dim3(64 * ANW), smem, st, (const bf16_t*)q, (const bf16_t*)k,
                            (const bf16_t*)v, (bf16_t*)out, n, Hq, Hkv, scale * 1.4426950408889634f, n_qt);
         return check_launch();
     }

@@ -88,20 +88,6 @@ __device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int&
     tn = rem / gm;
 }
 
-// One 16-byte-per-lane load from global memory straight into LDS.  The LDS address of lane l is
-// (wave-uniform base) + 16*l; the base travels in M0.  The compiler does not see this as an LDS write,
-// so callers order it against LDS reads themselves: s_waitcnt vmcnt + workgroup barrier.
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void load_global_to_lds16(const void* g, void* lds_wave_base) {
-    const unsigned la = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_wave_base);
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
-}
-__device__ __forceinline__ void workgroup_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 // Main kernel.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned rows.
 template <int TW, int TA, int WGN, int WGM, int EPI>
 __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,

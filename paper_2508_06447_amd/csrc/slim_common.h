@@ -66,6 +66,20 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// One 16-byte-per-lane load from global memory straight into LDS.  The LDS address of lane l is
+// (wave-uniform base) + 16*l; the base travels in M0.  The compiler does not see this as an LDS write,
+// so callers order it against LDS reads themselves: s_waitcnt vmcnt + workgroup barrier.
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void load_global_to_lds16(const void* g, void* lds_wave_base) {
+    const unsigned la = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_wave_base);
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
+}
+__device__ __forceinline__ void workgroup_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // ---- host side ---------------------------------------------------------------------------------
 int set_hip_error(hipError_t e);                      // records text, returns SLIM_HIP_ERROR
 inline int check_launch() {
