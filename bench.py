@@ -131,6 +131,68 @@ def cpu_baseline(wl_full, sample_tokens=8192):
                       f"{wl.n_blocks} blocks); attention per token is cheaper at this length than at full length"}
 
 
+def bench_model(args, slim, inputs, wl, dev):
+    """Multi-layer workload (cfg5): one step = the whole Preserve/Slim schedule through slim_prefill_model."""
+    import torch
+    x = inputs.hidden_states(wl).to(dev)
+    pos = inputs.positions(wl).to(dev)
+    w_gpu = [{k: v.to(dev) for k, v in w.items()} for _, w in inputs.model_weights(wl, workers=16)]
+    shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
+                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps)
+    keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, wl.schedule)
+    out = slim.slim_prefill_model(shape, w_gpu, x, pos, keeps)           # allocates outputs once
+    lib = slim.load_library()
+    import ctypes as C
+    arr = (C.c_int * len(keeps))(*keeps)
+    ws = torch.empty(lib.slim_prefill_model_workspace_bytes(C.byref(shape), len(keeps), arr, wl.seq),
+                     dtype=torch.uint8, device=dev)
+
+    def step():
+        slim.slim_prefill_model(shape, w_gpu, x, pos, keeps, workspace=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    Hd, Hq, Hkv, d, F = wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn
+    flops, n, per_layer = 0.0, wl.seq, []
+    for l, k in enumerate(keeps):
+        N = n
+        if k:
+            n = slim.kept_tokens(n, wl.block, k)
+        f = (2 * N * Hd * Hkv * d + (2 * wl.window * Hd * Hq * d if k else 0) + 2 * n * Hd * (Hq + Hkv) * d
+             + 2 * n * n * d * Hq + 2 * n * Hd * Hq * d + 6 * n * Hd * F)
+        flops += f
+        per_layer.append(n)
+    rec = {
+        "metric": "pruned-prefill tokens/s", "value": round(wl.seq / (ms * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: 32-layer LLaMA-3.1-8B-shaped prefill, seq {wl.seq}, pruning at layers "
+                               f"8/16/24 to 50/25/12.5 % of the incoming blocks (block {wl.block}, window {wl.window})",
+                   "n_tokens": wl.seq, "n_keep_blocks": [k for k in keeps if k], "tokens_after_layer": per_layer[::8],
+                   "seed": wl.seed},
+        "prefill_ms": round(ms, 3), "model_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+        "model_mfma_frac": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "unpruned_flops_ratio": None,
+    }
+    n0 = wl.seq
+    rec["unpruned_flops_ratio"] = round(wl.n_layers * (2 * n0 * Hd * (Hq + 2 * Hkv) * d + 2 * n0 * n0 * d * Hq
+                                                       + 2 * n0 * Hd * Hq * d + 6 * n0 * Hd * F) / flops, 3)
+    h = torch.randn(n0, Hd, device=dev).to(torch.bfloat16)
+    act = torch.empty(n0, F, device=dev, dtype=torch.bfloat16)
+    med, mean = time_gpu(lambda: slim.slim_swiglu_linear(h, w_gpu[0]["w_gate"], w_gpu[0]["w_up"], out=act), 10)
+    tf = 4 * n0 * Hd * F / (mean * 1e-3) / 1e12
+    rec["roofline"] = {"kernel": "gemm_bf16_kernel (SwiGLU gate/up projection, 32768 tokens)", "bound": "mfma",
+                       "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                       "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None, "avg_ms": round(mean, 4)}
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,7 +217,8 @@ def main():
     slim.load_library()
     dev = torch.device("cuda:0")
     wl = inputs.WORKLOADS[args.workload]
-    assert wl.n_layers == 1, "bench.py times single-layer workloads"
+    if wl.n_layers > 1:
+        return bench_model(args, slim, inputs, wl, dev)
     x = inputs.hidden_states(wl).to(dev)
     wd = {k: v.to(dev) for k, v in inputs.layer_weights(wl).items()}
     pos = inputs.positions(wl).to(dev)

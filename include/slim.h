@@ -155,6 +155,29 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
                       int* kept_blocks_out, float* scores_out, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Preserve/Slim schedule -- Section 4.1: the layers run in order; a layer whose n_keep[l] is smaller
+ * than its incoming block count prunes its incoming sequence to n_keep[l] blocks (forced blocks
+ * included), and the surviving set then propagates unchanged until the next pruning layer.
+ * Because whole blocks are kept in order, the compacted sequence is re-blocked by `block` and its
+ * blocks are the surviving original ones.
+ *   layers   host array [n_layers] of slim_layer_weights (device pointers inside)
+ *   n_keep   host array [n_layers]; 0 or >= incoming blocks = Preserve layer
+ *   x_in [N, hidden], pos_in [N] int32 or NULL (= 0..N-1)
+ *   x_out [n_final, hidden], pos_out [n_final] int32 (NULL allowed), n_final = slim_prefill_model_tokens(...)
+ *   kept_blocks_out: int32, the kept sets of the pruning layers one after another (each in the block
+ *                    numbering of that layer's incoming sequence), or NULL
+ *   workspace >= slim_prefill_model_workspace_bytes(...), 256-byte aligned
+ * Output = residual stream after the last layer (no final norm).  Errors as slim_pruned_layer.
+ */
+int slim_prefill_model_tokens(const slim_layer_shape* s, int n_layers, const int* n_keep, int n_tokens);
+size_t slim_prefill_model_workspace_bytes(const slim_layer_shape* s, int n_layers, const int* n_keep,
+                                          int n_tokens);
+int slim_prefill_model(const slim_layer_shape* s, const slim_layer_weights* layers, int n_layers,
+                       const int* n_keep, const void* x_in, const int* pos_in, int n_tokens, void* x_out,
+                       int* pos_out, int* kept_blocks_out, void* workspace, size_t workspace_bytes,
+                       void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
-    "slim_pruned_layer",
+    "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
 )
 
 
@@ -75,6 +75,12 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_pruned_layer_workspace_bytes.argtypes = [C.POINTER(LayerShape), i, i]
     lib.slim_pruned_layer.argtypes = [C.POINTER(LayerShape), C.POINTER(LayerWeights), vp, vp, i, i, vp, vp, vp, vp,
                                       vp, sz, vp]
+    ip = C.POINTER(C.c_int)
+    lib.slim_prefill_model_tokens.argtypes = [C.POINTER(LayerShape), i, ip, i]
+    lib.slim_prefill_model_workspace_bytes.restype = sz
+    lib.slim_prefill_model_workspace_bytes.argtypes = [C.POINTER(LayerShape), i, ip, i]
+    lib.slim_prefill_model.argtypes = [C.POINTER(LayerShape), C.POINTER(LayerWeights), i, ip, vp, vp, i, vp, vp, vp,
+                                       vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name)                      # every declared symbol must resolve
     if path is None:
@@ -267,4 +273,49 @@ def slim_pruned_layer(shape: LayerShape, weights: dict, x: torch.Tensor, pos: to
                                  _dev(out["x"], "x_out"), _dev(out["pos"], "pos_out"), _dev(out["kept"], "kept"),
                                  _dev(out["scores"], "scores"), _dev(workspace, "workspace"), workspace.numel(),
                                  _stream()), "slim_pruned_layer")
+    return out
+
+
+def schedule_keep_counts(n_tokens: int, block: int, n_layers: int, schedule: dict) -> list:
+    """Per-layer n_keep for a {layer: keep ratio of the incoming blocks} schedule (0 = Preserve layer):
+    ceil(ratio * incoming blocks), at least the two forced blocks."""
+    import math
+    out, n = [], n_tokens
+    for l in range(n_layers):
+        nb = n_blocks(n, block)
+        if l in schedule:
+            keep = int(min(nb, max(min(2, nb), math.ceil(schedule[l] * nb - 1e-12))))
+            out.append(keep)
+            n = load_library().slim_kept_tokens(n, block, keep)
+        else:
+            out.append(0)
+    return out
+
+
+def slim_prefill_model(shape: LayerShape, layer_weights: list, x: torch.Tensor, pos: torch.Tensor | None,
+                       n_keep: list, workspace: torch.Tensor | None = None, out: dict | None = None):
+    """All layers in order (Preserve layers where n_keep[l] == 0).  `layer_weights` is a list of dicts of GPU
+    tensors.  Returns dict(x=[n_final, hidden], pos=[n_final], kept=concatenated kept sets of the pruning layers)."""
+    lib = load_library()
+    L = len(layer_weights)
+    N = x.shape[0]
+    keep_arr = (C.c_int * L)(*[int(k) for k in n_keep])
+    n_final = lib.slim_prefill_model_tokens(C.byref(shape), L, keep_arr, N)
+    if n_final <= 0:
+        raise SlimError(-1, "slim_prefill_model", "invalid schedule")
+    warr = (LayerWeights * L)(*[make_weights(w) for w in layer_weights])
+    dev = x.device
+    out = dict(out) if out else {}
+    if "x" not in out:
+        out["x"] = torch.empty((n_final, shape.hidden), dtype=x.dtype, device=dev)
+    if "pos" not in out:
+        out["pos"] = torch.empty(n_final, dtype=torch.int32, device=dev)
+    if "kept" not in out:
+        out["kept"] = torch.empty(max(1, sum(int(k) for k in n_keep)), dtype=torch.int32, device=dev)
+    need = lib.slim_prefill_model_workspace_bytes(C.byref(shape), L, keep_arr, N)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check(lib.slim_prefill_model(C.byref(shape), warr, L, keep_arr, _dev(x, "x"), _dev(pos, "pos"), N,
+                                  _dev(out["x"], "x_out"), _dev(out["pos"], "pos_out"), _dev(out["kept"], "kept"),
+                                  _dev(workspace, "workspace"), workspace.numel(), _stream()), "slim_prefill_model")
     return out

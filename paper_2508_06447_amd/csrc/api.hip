@@ -249,4 +249,82 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     return SLIM_OK;
 }
 
+// Walks the schedule on the host: tokens entering each layer, the largest layer workspace, and the
+// number of kept-block indices the pruning layers emit.  Returns the final token count, 0 on bad input.
+static int walk_schedule(const slim_layer_shape* s, int n_layers, const int* n_keep, int n_tokens,
+                         size_t* max_layer_ws, size_t* kept_total) {
+    if (check_shape(s) != SLIM_OK || n_layers < 1 || !n_keep || n_tokens < 1) return 0;
+    int n = n_tokens;
+    size_t ws = 0, kept = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int nb = (n + s->block - 1) / s->block;
+        const bool prune = n_keep[l] > 0 && n_keep[l] < nb;
+        const int keep = prune ? n_keep[l] : nb;
+        if (prune && (keep < forced_count(s->flags, nb) || (!(s->flags & SLIM_FORCE_LAST) && n % s->block != 0)))
+            return 0;
+        const size_t need = plan_layer(s, n, keep).total;
+        if (need > ws) ws = need;
+        if (prune) { kept += (size_t)keep; n = slim_kept_tokens(n, s->block, keep); }
+    }
+    if (max_layer_ws) *max_layer_ws = ws;
+    if (kept_total) *kept_total = kept;
+    return n;
+}
+
+int slim_prefill_model_tokens(const slim_layer_shape* s, int n_layers, const int* n_keep, int n_tokens) {
+    return walk_schedule(s, n_layers, n_keep, n_tokens, nullptr, nullptr);
+}
+
+// Workspace: [layer workspace | hidden A | hidden B | pos A | pos B | kept scratch]
+size_t slim_prefill_model_workspace_bytes(const slim_layer_shape* s, int n_layers, const int* n_keep, int n_tokens) {
+    size_t lw = 0;
+    if (!walk_schedule(s, n_layers, n_keep, n_tokens, &lw, nullptr)) return 0;
+    const size_t hid = align_up((size_t)n_tokens * s->hidden * elem_size(s->dtype), 256);
+    const size_t ints = align_up((size_t)n_tokens * sizeof(int), 256);
+    return align_up(lw, 256) + 2 * hid + 3 * ints;
+}
+
+int slim_prefill_model(const slim_layer_shape* s, const slim_layer_weights* layers, int n_layers, const int* n_keep,
+                       const void* x_in, const int* pos_in, int n_tokens, void* x_out, int* pos_out,
+                       int* kept_blocks_out, void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(s);
+    if (rc) return rc;
+    if (!layers || !n_keep || !x_in || !x_out || !workspace || n_layers < 1 || n_tokens < 1) return SLIM_INVALID_ARG;
+    size_t lw = 0;
+    if (!walk_schedule(s, n_layers, n_keep, n_tokens, &lw, nullptr)) return SLIM_INVALID_ARG;
+    if (workspace_bytes < slim_prefill_model_workspace_bytes(s, n_layers, n_keep, n_tokens)) return SLIM_WORKSPACE_TOO_SMALL;
+    if ((uintptr_t)workspace & 255u) return SLIM_UNSUPPORTED;
+    lw = align_up(lw, 256);
+    const size_t hid = align_up((size_t)n_tokens * s->hidden * elem_size(s->dtype), 256);
+    const size_t ints = align_up((size_t)n_tokens * sizeof(int), 256);
+    unsigned char* ws = (unsigned char*)workspace;
+    void* hbuf[2] = {ws + lw, ws + lw + hid};
+    int* pbuf[2] = {(int*)(ws + lw + 2 * hid), (int*)(ws + lw + 2 * hid + ints)};
+    int* kept_scratch = (int*)(ws + lw + 2 * hid + 2 * ints);
+
+    const void* x = x_in;
+    const int* pos = pos_in;
+    int n = n_tokens, hsel = 0, psel = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const int nb = (n + s->block - 1) / s->block;
+        const bool prune = n_keep[l] > 0 && n_keep[l] < nb;
+        const int keep = prune ? n_keep[l] : nb;
+        void* y = (l == n_layers - 1) ? x_out : hbuf[hsel];
+        int* kept = kept_blocks_out ? kept_blocks_out : kept_scratch;
+        rc = slim_pruned_layer(s, &layers[l], x, pos, n, keep, y, prune ? pbuf[psel] : nullptr, prune ? kept : nullptr,
+                               nullptr, workspace, lw, stream);
+        if (rc) return rc;
+        if (prune) {
+            if (kept_blocks_out) kept_blocks_out += keep;
+            pos = pbuf[psel];
+            psel ^= 1;
+            n = slim_kept_tokens(n, s->block, keep);
+        }
+        x = y;
+        hsel ^= 1;
+    }
+    if (pos_out) return launch_positions(pos, pos_out, n, (hipStream_t)stream);
+    return SLIM_OK;
+}
+
 }  // extern "C"

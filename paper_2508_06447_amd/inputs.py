@@ -6,8 +6,8 @@ checker can be fed from it.  Everything is generated on the host with NumPy's PC
 bf16 workloads, rounded to bfloat16 once, so every consumer reads the same bits.
 
 Draw order per workload (fixed): hidden states x, planted-token indices or block ranks, then for a
-layer Wq, Wk, Wv, Wo, Wgate, Wup, Wdown.  Multi-layer workloads draw each layer's weights from the
-generator seeded with (seed, layer) so no process ever has to hold all layers on the host.
+layer Wq, Wk, Wv, Wo, Wgate, Wup, Wdown, each from its own generator seeded with (seed, 1000 + layer,
+index), so a process never has to hold all layers on the host and matrices can be drawn in parallel.
 Weights are N(0, 0.02^2); RMSNorm gains are exactly 1; there are no biases.
 """
 from __future__ import annotations
@@ -116,16 +116,33 @@ def weight_shapes(wl: Workload) -> dict:
                 w_gate=(wl.ffn, wl.hidden), w_up=(wl.ffn, wl.hidden), w_down=(wl.hidden, wl.ffn))
 
 
-def layer_weights(wl: Workload, layer: int = 0) -> dict:
-    """Dict of [out, in] weight tensors plus unit gains, stored in the workload's dtype."""
-    rng = np.random.default_rng([wl.seed, 1000 + layer])
-    out = {}
-    for name, shp in weight_shapes(wl).items():
-        out[name] = _store(0.02 * rng.standard_normal(shp, dtype=np.float32), wl.dtype)
+def _one_weight(args):
+    seed, layer, idx, shp, dtype = args
+    rng = np.random.default_rng([seed, 1000 + layer, idx])
+    return _store(0.02 * rng.standard_normal(shp, dtype=np.float32), dtype)
+
+
+def layer_weights(wl: Workload, layer: int = 0, pool=None) -> dict:
+    """Dict of [out, in] weight tensors plus unit gains, stored in the workload's dtype.  Each matrix has
+    its own generator seeded with (seed, 1000 + layer, index in WEIGHT_NAMES), so matrices can be drawn
+    concurrently (`pool`: a concurrent.futures executor) without changing their values."""
+    jobs = [(wl.seed, layer, i, shp, wl.dtype) for i, shp in enumerate(weight_shapes(wl).values())]
+    mats = list(pool.map(_one_weight, jobs)) if pool is not None else [_one_weight(j) for j in jobs]
+    out = dict(zip(weight_shapes(wl).keys(), mats))
     ones = np.ones(wl.hidden, dtype=np.float32)
     out["g_attn"] = _store(ones, wl.dtype)
     out["g_ffn"] = _store(ones.copy(), wl.dtype)
     return out
+
+
+def model_weights(wl: Workload, layers=None, workers: int = 8):
+    """Yields (layer, weights dict) for the chosen layers of a multi-layer workload, drawing the
+    matrices on a thread pool (NumPy's generators release the GIL while they fill an array)."""
+    from concurrent.futures import ThreadPoolExecutor
+    layers = range(wl.n_layers) if layers is None else layers
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        for l in layers:
+            yield l, layer_weights(wl, l, pool)
 
 
 def positions(wl: Workload) -> torch.Tensor:
