@@ -72,6 +72,66 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 :
     }
 }
 
+// Epilogue of the main kernel: the wave's tile goes through a wave-private LDS region so that global
+// traffic is 16 bytes per lane and whole rows of the tile are contiguous (a lane of the accumulator
+// layout owns only 4 consecutive features of one token).  Steps, all inside one wave (LDS operations
+// of a wave complete in program order, so no barrier is needed):
+//   residual only: rows of R are loaded coalesced and parked in the region;
+//   each lane takes its accumulators, applies SiLU(gate)*up or adds its 4 residual values in fp32,
+//   rounds once to bf16 and writes 8 bytes into the region;
+//   rows are read back 16 bytes per lane and stored.
+// Region layout: row = token (TA*32 rows of TW*64 bytes), 16-byte chunk c of row r at slot
+// c ^ (r & (chunks per row - 1)).  Needs N % 8 == 0, ldo % 8 == 0 and 16-byte aligned out / residual.
+template <int TW, int TA, int EPI>
+__device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 : 1][TW][TA], const bf16_t* R,
+                                                   bf16_t* C, int ldo, int M, int N, int mw, int nw, int lane,
+                                                   unsigned char* region) {
+    constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr int CPR = TW * 4, RB = TW * 64, ROWS = TA * 32, RPI = 64 / CPR;
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int rrow = lane / CPR, rchunk = lane % CPR;     // coalesced phases: lane -> (row in group, chunk)
+    auto slot = [&](int row, int chunk) { return row * RB + ((chunk ^ (row & (CPR - 1))) << 4); };
+    if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+        for (int it = 0; it < ROWS / RPI; ++it) {
+            const int row = it * RPI + rrow, m = mw + row, n = nw + rchunk * 8;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (m < M && n < N) v = *reinterpret_cast<const uint4*>(R + (size_t)m * ldo + n);
+            *reinterpret_cast<uint4*>(region + slot(row, rchunk)) = v;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < TA; ++j)
+#pragma unroll
+        for (int i = 0; i < TW; ++i)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                const int row = j * 32 + l32;
+                uint2* cell = reinterpret_cast<uint2*>(region + slot(row, i * 4 + vg) + hh * 8);
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (EPI == EPI_SWIGLU) {
+                        const float g = acc[0][i][j][vg * 4 + e], u = acc[NW - 1][i][j][vg * 4 + e];
+                        o[e] = g / (1.0f + __expf(-g)) * u;
+                    } else {
+                        o[e] = acc[0][i][j][vg * 4 + e];
+                    }
+                }
+                if (EPI == EPI_RESIDUAL) {
+                    const uint2 r = *cell;
+                    o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
+                }
+                *cell = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
+            }
+#pragma unroll
+    for (int it = 0; it < ROWS / RPI; ++it) {
+        const int row = it * RPI + rrow, m = mw + row, n = nw + rchunk * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(region + slot(row, rchunk));
+        if (m < M && n < N) *reinterpret_cast<uint4*>(C + (size_t)m * ldo + n) = v;
+    }
+}
+
 // Workgroup -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, so each XCD gets a
 // contiguous run of logical tiles; inside the run, bands of GM token-tiles are walked feature-tile by
 // feature-tile, so the workgroups resident on one XCD share few distinct operand tiles in its L2.
@@ -182,7 +242,14 @@ __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict
         __builtin_amdgcn_s_waitcnt(0x0070);              // this wave's tile kt+1 has landed; its LDS reads are done
         workgroup_barrier();
     }
-    store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+    // Every wave has left the k-loop (barrier above), so the stage buffers are free for the epilogue.
+    const bool wide = (N % 8 == 0) && (ldo % 8 == 0) && (((uintptr_t)C & 15) == 0) &&
+                      (EPI != EPI_RESIDUAL || ((uintptr_t)R & 15) == 0);
+    if (wide)
+        store_tile_via_lds<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+                                        lds + wave * (TA * 32 * TW * 64));
+    else
+        store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
 }
 
 // Generic kernel (any k_in that is a multiple of 8): register-staged loads with k predicates.
@@ -310,12 +377,13 @@ template <int EPI>
 static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                          int ldo, int M, int N, int K, hipStream_t st) {
     if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-    if (EPI == EPI_SWIGLU) {
+    if constexpr (EPI == EPI_SWIGLU) {
         if (M <= 128) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
         return launch_bf16<2, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    } else {
+        if (M <= 128) return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+        return launch_bf16<4, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
     }
-    if (M <= 128) return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-    return launch_bf16<4, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
