@@ -104,6 +104,25 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     return table
 
 
+def measured_ceilings(slim, dev):
+    """What this chip sustains in this run: a register-only MFMA loop and a plain 1 GiB copy."""
+    import torch
+    sink = torch.zeros(1, device=dev)
+    flops = [0.0]
+
+    def mfma():
+        flops[0] = slim.probe_mfma(2048, 4096, sink)
+
+    _, ms = time_gpu(mfma, 5, warmup=2)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    _, ms_c = time_gpu(lambda: slim.probe_copy(src, dst), 5, warmup=2)
+    return {"mfma_loop_tflops": round(flops[0] / (ms * 1e-3) / 1e12, 1),
+            "copy_gbs": round(2 * src.numel() / (ms_c * 1e-3) / 1e9, 1),
+            "note": "register-only v_mfma_f32_32x32x16_bf16 loop (2048 workgroups x 8 waves); 1 GiB device copy, "
+                    "read + write bytes"}
+
+
 def cpu_baseline(wl_full, sample_tokens=8192):
     """The oracle, as it is, on the host cores: the same layer on the first `sample_tokens` tokens."""
     import numpy as np
@@ -272,6 +291,8 @@ def main():
         rec["roofline"] = {"kernel": "gemm_bf16_kernel (SwiGLU gate/up projection)", "bound": "mfma",
                            "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                            "frac": dom["frac"], "traffic": None, "avg_ms": dom["ms"]}
+    if not args.no_stages:
+        rec["measured_ceilings"] = measured_ceilings(slim, dev)
     if not args.no_cpu:
         rec["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(rec))

@@ -23,6 +23,7 @@ EXPORTS = (
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
+    "slim_probe_mfma_flops", "slim_probe_mfma", "slim_probe_copy",
 )
 
 
@@ -81,6 +82,10 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_prefill_model_workspace_bytes.argtypes = [C.POINTER(LayerShape), i, ip, i]
     lib.slim_prefill_model.argtypes = [C.POINTER(LayerShape), C.POINTER(LayerWeights), i, ip, vp, vp, i, vp, vp, vp,
                                        vp, sz, vp]
+    lib.slim_probe_mfma_flops.restype = C.c_double
+    lib.slim_probe_mfma_flops.argtypes = [i, i]
+    lib.slim_probe_mfma.argtypes = [i, i, vp, vp]
+    lib.slim_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name)                      # every declared symbol must resolve
     if path is None:
@@ -319,3 +324,17 @@ def slim_prefill_model(shape: LayerShape, layer_weights: list, x: torch.Tensor, 
                                   _dev(out["x"], "x_out"), _dev(out["pos"], "pos_out"), _dev(out["kept"], "kept"),
                                   _dev(workspace, "workspace"), workspace.numel(), _stream()), "slim_prefill_model")
     return out
+
+
+def probe_mfma(n_workgroups: int, iters: int, sink: torch.Tensor) -> float:
+    """Enqueue the register-only MFMA loop; returns its flop count."""
+    lib = load_library()
+    _check(lib.slim_probe_mfma(n_workgroups, iters, _dev(sink, "sink"), _stream()), "slim_probe_mfma")
+    return lib.slim_probe_mfma_flops(n_workgroups, iters)
+
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
+    """Enqueue a plain device copy of src into dst; returns the bytes copied."""
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().slim_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "slim_probe_copy")
+    return nbytes

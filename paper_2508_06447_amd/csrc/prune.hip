@@ -165,14 +165,28 @@ __global__ void __launch_bounds__(kSelThreads) select_blocks_kernel(const float*
                 if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1);
             }
             __syncthreads();
-            if (tid == 0) {
-                int rem = s_remaining, bin = 255;
-                for (; bin > 0; --bin) {                 // walk down from the largest digit
-                    if (hist[bin] >= rem) break;
-                    rem -= hist[bin];
+            if (tid < 64) {
+                // Find the digit that holds the rem-th largest candidate: lane l owns the digits
+                // 255-4l .. 252-4l (descending); a wave scan gives the count of larger digits.
+                const int rem = s_remaining;
+                int c[4], tot = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) { c[k] = hist[255 - (4 * tid + k)]; tot += c[k]; }
+                int inc = tot;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const int t = __shfl_up(inc, o, 64);
+                    if (tid >= o) inc += t;
                 }
-                s_prefix = prefix | ((uint32_t)bin << shift);
-                s_remaining = rem;
+                int above = inc - tot;                   // candidates with a larger digit than this lane's first
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (above < rem && rem <= above + c[k]) {          // true for exactly one (lane, k)
+                        s_prefix = prefix | ((uint32_t)(255 - (4 * tid + k)) << shift);
+                        s_remaining = rem - above;
+                    }
+                    above += c[k];
+                }
             }
             __syncthreads();
         }
