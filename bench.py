@@ -104,6 +104,20 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     return table
 
 
+def profiled_traffic(kernel_prefix):
+    """HBM-side bytes per launch of a kernel as last measured with rocprofv3 counters (see profiles/);
+    None if no measurement is on file.  bench.py itself cannot read hardware counters."""
+    path = os.path.join(ROOT, "profiles", "pruned_layer_cfg3_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith(kernel_prefix):
+                _, rd, wr = line.rstrip("\n").split("\t")
+                return int(rd) + int(wr)
+    except OSError:
+        pass
+    return None
+
+
 def measured_ceilings(slim, dev):
     """What this chip sustains in this run: a register-only MFMA loop and a plain 1 GiB copy."""
     import torch
@@ -123,7 +137,7 @@ def measured_ceilings(slim, dev):
                     "read + write bytes"}
 
 
-def cpu_baseline(wl_full, sample_tokens=8192):
+def cpu_baseline(wl_full, sample_tokens=32768):
     """The oracle, as it is, on the host cores: the same layer on the first `sample_tokens` tokens."""
     import numpy as np
     from oracle import slim_oracle as so
@@ -147,7 +161,8 @@ def cpu_baseline(wl_full, sample_tokens=8192):
             "seconds": round(dt, 2),
             "sample": f"float32 oracle pruned layer on the first {wl.seq} of {wl_full.seq} tokens of {wl_full.name} "
                       f"(same layer shapes, block {wl.block}, keep ratio {wl.keep_ratio}: {wl.n_keep} of "
-                      f"{wl.n_blocks} blocks); attention per token is cheaper at this length than at full length"}
+                      f"{wl.n_blocks} blocks)" + ("" if wl.seq == wl_full.seq else
+                                                  "; attention per token is cheaper at this length than at full length")}
 
 
 def bench_model(args, slim, inputs, wl, dev):
@@ -290,7 +305,9 @@ def main():
         dom = table["ffn_gate_up_swiglu"]
         rec["roofline"] = {"kernel": "gemm_bf16_kernel (SwiGLU gate/up projection)", "bound": "mfma",
                            "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": dom["frac"], "traffic": None, "avg_ms": dom["ms"]}
+                           "frac": dom["frac"], "traffic": profiled_traffic("gemm_bf16_kernel<2, 2, 2, 4, 2>"),
+                           "traffic_unit": "bytes per launch, rocprofv3 FETCH_SIZE x2 + WRITE_SIZE (profiles/)",
+                           "algorithmic_bytes": 2 * (n * Hd + 2 * F * Hd + n * F), "avg_ms": dom["ms"]}
     if not args.no_stages:
         rec["measured_ceilings"] = measured_ceilings(slim, dev)
     if not args.no_cpu:

@@ -1,0 +1,69 @@
+"""Host-side logic that needs no GPU: keep counts, kept-token counts, the schedule walk, workspace sizes."""
+import ctypes as C
+
+import pytest
+import torch
+
+import paper_2508_06447_amd as slim
+from paper_2508_06447_amd import inputs
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import os
+    if not os.path.exists(slim.LIB_PATH):
+        from paper_2508_06447_amd.build import build_lib
+        build_lib(verbose=False)
+    return slim.load_library()
+
+
+def test_workload_table_matches_the_stated_shapes():
+    w = inputs.WORKLOADS
+    assert [(w[k].n_blocks, w[k].n_keep, w[k].n_kept_tokens) for k in ("cfg1", "cfg2", "cfg3", "cfg4")] == \
+        [(32, 16, 256), (128, 64, 4096), (512, 154, 9856), (1024, 205, 26240)]
+    assert inputs.keep_count(0.0, 10) == 2 and inputs.keep_count(1.0, 10) == 10 and inputs.keep_count(0.5, 1) == 1
+    assert inputs.kept_tokens(45, 8, 3) == 21 and inputs.kept_tokens(45, 8, 9) == 45
+
+
+def test_schedule_keep_counts_and_model_token_walk(lib):
+    wl = inputs.WORKLOADS["cfg5"]
+    keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, wl.schedule)
+    assert len(keeps) == 32 and keeps[8] == 256 and keeps[16] == 64 and keeps[24] == 8 and sum(1 for k in keeps if k) == 3
+    shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit, wl.window,
+                            torch.bfloat16)
+    arr = (C.c_int * 32)(*keeps)
+    assert lib.slim_prefill_model_tokens(C.byref(shape), 32, arr, wl.seq) == 512
+    need = lib.slim_prefill_model_workspace_bytes(C.byref(shape), 32, arr, wl.seq)
+    layer0 = slim.pruned_layer_workspace_bytes(shape, wl.seq, wl.n_blocks)
+    assert need >= layer0 + 2 * wl.seq * wl.hidden * 2
+    # a schedule that asks for fewer blocks than are forced is rejected on the host
+    bad = (C.c_int * 32)(*([0] * 8 + [1] + [0] * 23))
+    assert lib.slim_prefill_model_tokens(C.byref(shape), 32, bad, wl.seq) == 0
+    assert lib.slim_prefill_model_workspace_bytes(C.byref(shape), 32, bad, wl.seq) == 0
+    # ragged sequence: whole blocks survive plus the short last block
+    keeps2 = slim.schedule_keep_counts(2085, 64, 5, {1: 0.5, 3: 0.25})
+    assert keeps2 == [0, 17, 0, 5, 0]
+    arr2 = (C.c_int * 5)(*keeps2)
+    assert lib.slim_prefill_model_tokens(C.byref(shape), 5, arr2, 2085) == 4 * 64 + 37
+
+
+def test_layer_workspace_grows_with_tokens_and_is_aligned(lib):
+    shape = slim.make_shape(4096, 32, 8, 128, 14336, 64, 8, 64, torch.bfloat16)
+    a = slim.pruned_layer_workspace_bytes(shape, 8192, 64)
+    b = slim.pruned_layer_workspace_bytes(shape, 32768, 154)
+    assert 0 < a < b and a % 256 == 0 and b % 256 == 0
+    assert lib.slim_probe_mfma_flops(2, 3) == 2 * 8 * 3 * 8 * 2.0 * 32 * 32 * 16
+
+
+def test_generators_are_seeded_and_per_matrix():
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=64, hidden=64, ffn=128, n_q_heads=2, n_kv_heads=1, head_dim=32)
+    a, b = inputs.layer_weights(wl, 3), inputs.layer_weights(wl, 3)
+    assert all(torch.equal(a[k], b[k]) for k in a)
+    c = inputs.layer_weights(wl, 4)
+    assert not torch.equal(a["wq"], c["wq"])
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(4) as pool:
+        d = inputs.layer_weights(wl, 3, pool)
+    assert all(torch.equal(a[k], d[k]) for k in a)
+    x1, x2 = inputs.hidden_states(wl), inputs.hidden_states(wl)
+    assert torch.equal(x1, x2) and x1.dtype == torch.bfloat16 and float(a["g_attn"].float().min()) == 1.0
