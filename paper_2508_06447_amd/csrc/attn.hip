@@ -2,8 +2,8 @@
 //
 // bf16 path (head_dim 128): flash-style single pass with online softmax, v_mfma_f32_32x32x16_bf16.
 // A workgroup of 8 waves (two per SIMD) owns 256 queries of one head, each wave 32 of them.  K/V tiles
-// of 64 keys go from global memory straight into LDS (global_load_lds_dwordx4), both row-major, in a
-// ring of 3 stages; V fragments are read with the transposing LDS read (ds_read_b64_tr_b16).
+// of 128 keys go from global memory straight into LDS (global_load_lds_dwordx4), both row-major, double-
+// buffered (2 x 64 KB); V fragments are read with the transposing LDS read (ds_read_b64_tr_b16).
 //
 // Both products are computed transposed so that no register shuffle is needed between them:
 //   S^T[key, query] = K . Q^T      (A operand = K rows from LDS, B operand = Q rows held in VGPRs)
@@ -25,8 +25,9 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 constexpr int AD = 128;          // head_dim of the MFMA path
 constexpr int ANW = 8;           // waves per workgroup
 constexpr int BQ = 32 * ANW;     // queries per workgroup
-constexpr int BKV = 64;          // keys per tile
-constexpr int NSTAGE = 3;        // K/V tiles resident in LDS
+constexpr int BKV = 128;         // keys per tile
+constexpr int NJ = BKV / 32;      // 32-key sub-tiles per tile
+constexpr int NSTAGE = 2;        // K/V tiles resident in LDS
 constexpr int TILE_BYTES = BKV * AD * 2;
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;             // K tile, then V tile
 
@@ -64,7 +65,7 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
         for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
     }
 
-    // Tile t -> stage t % NSTAGE.  A wave-load moves 4 key rows x 256 B; each tile is 16 wave-loads for
+    // Tile t -> stage t % NSTAGE.  A wave-load moves 4 key rows x 256 B; each tile is BKV/4 wave-loads for
     // K and 16 for V, two of each per wave.  Lane l lands at LDS slot l%16 of row l/16, so it fetches the
     // global chunk that the swizzle assigns to that slot.  Tiles past the end re-read the last tile into
     // a stage nobody reads, which keeps the count of loads in flight the same in every iteration.
@@ -75,7 +76,7 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
         const int k0 = min(t, n_kt_all - 1) * BKV;
         unsigned char* stage = lds + (t % NSTAGE) * STAGE_BYTES;
 #pragma unroll
-        for (int i = 0; i < 16 / ANW; ++i) {
+        for (int i = 0; i < BKV / 4 / ANW; ++i) {
             const int rg = i * ANW + wave, r = rg * 4 + (lane >> 4), slot = lane & 15;
             const size_t row = (size_t)min(k0 + r, n - 1) * kvstride;
             load_global_to_lds16(kbase + row + (slot ^ (r & 15)) * 8, stage + rg * 1024);
@@ -117,10 +118,10 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
         issue_tile(kt + NSTAGE - 1);                      // its stage held tile kt-1, which every wave has left
         if (k0 <= qw0 + 31) {                             // some key of the tile is visible to this wave
             const unsigned sb = lds_base + (kt % NSTAGE) * STAGE_BYTES;
-            // ---- S^T = K Q^T : two 32-key sub-tiles
-            f32x16 s[2];
+            // ---- S^T = K Q^T : NJ 32-key sub-tiles
+            f32x16 s[NJ];
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt) {
+            for (int jt = 0; jt < NJ; ++jt) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[jt][v] = 0.f;
 #pragma unroll
@@ -133,7 +134,7 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
             if ((k0 + BKV - 1 > qw0) || (k0 + BKV > n)) {
                 const int lim = min(qi, n - 1) - k0 - 4 * hh;     // visible: key offset in the tile <= lim
 #pragma unroll
-                for (int jt = 0; jt < 2; ++jt)
+                for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                     for (int v = 0; v < 16; ++v)
                         s[jt][v] = (jt * 32 + 8 * (v >> 2) + (v & 3)) > lim ? -INFINITY : s[jt][v];
@@ -141,7 +142,7 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
             // ---- running max in the log2 domain (softmax_scale > 0, so the max commutes with it)
             float tmax = -INFINITY;
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
+            for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[jt][v]);
             tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * scale_log2e;
@@ -150,11 +151,11 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
             const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
             m_run = m_new;
             // ---- P = exp2(S*c - m), rounded to bf16 for the MFMA; the row sum adds the rounded values
-            uint32_t pb[2][8];
+            uint32_t pb[NJ][8];
             float psum = 0.f;
             const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
+            for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                 for (int v = 0; v < 16; v += 2) {
                     const f32x2 p = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[jt][v], scale_log2e, -m_new)),
@@ -170,11 +171,11 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
 #pragma unroll
                     for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
             }
-            // ---- O^T += V^T P^T : 4 k-steps of 16 keys; step (jt, half) uses accumulator values
+            // ---- O^T += V^T P^T : 2*NJ k-steps of 16 keys; step (jt, half) uses accumulator values
             //      v = half*8 .. half*8+7 of sub-tile jt, i.e. keys jt*32 + half*16 + {4*hh+0..3, 8+4*hh+0..3}
             constexpr int ROW = 256 / 8;                  // one key row in units of 8 bytes
 #pragma unroll
-            for (int jt = 0; jt < 2; ++jt)
+            for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
                     const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pb[jt][half * 4 + 0], pb[jt][half * 4 + 1],
@@ -192,7 +193,7 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
         }
         // Tile kt+1 has landed for this wave (the newer tile's loads may stay in flight); its own LDS
         // reads are done; after the barrier that holds for every wave.
-        __builtin_amdgcn_s_waitcnt(0x0070 | ((32 / ANW) * (NSTAGE - 2)));
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((BKV / 2 / ANW) * (NSTAGE - 2)));
         workgroup_barrier();
     }
     __builtin_amdgcn_s_waitcnt(0x0070);                   // drain the trailing loads before the wave ends
