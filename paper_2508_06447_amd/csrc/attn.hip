@@ -66,7 +66,7 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
     }
 
     // Tile t -> stage t % NSTAGE.  A wave-load moves 4 key rows x 256 B; each tile is BKV/4 wave-loads for
-    // K and 16 for V, two of each per wave.  Lane l lands at LDS slot l%16 of row l/16, so it fetches the
+    // K and as many for V, spread evenly over the waves.  Lane l lands at LDS slot l%16 of row l/16, so it fetches the
     // global chunk that the swizzle assigns to that slot.  Tiles past the end re-read the last tile into
     // a stage nobody reads, which keeps the count of loads in flight the same in every iteration.
     const bf16_t* kbase = Kg + (size_t)g * AD;
