@@ -12,6 +12,12 @@
 // k-step ahead of their use.  A register-staged kernel with k predicates covers ragged k_in.
 #include "slim_common.h"
 
+#include <map>
+#include <mutex>
+#include <queue>
+#include <tuple>
+#include <vector>
+
 namespace slim {
 
 enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
@@ -135,10 +141,11 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
 // Workgroup -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, so each XCD gets a
 // contiguous run of logical tiles; inside the run, bands of GM token-tiles are walked feature-tile by
 // feature-tile, so the workgroups resident on one XCD share few distinct operand tiles in its L2.
-__device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int& tm, int& tn) {
-    int L = blockIdx.x;
+// L is the workgroup's index inside a region of tiles_m x tiles_n tiles that starts at a workgroup id
+// divisible by 8 when xcd_runs is set.
+__device__ __forceinline__ void tile_of_workgroup(int L, bool xcd_runs, int tiles_m, int tiles_n, int& tm, int& tn) {
     const int total = tiles_m * tiles_n;
-    if (total % 8 == 0) L = (L & 7) * (total >> 3) + (L >> 3);
+    if (xcd_runs && total % 8 == 0) L = (L & 7) * (total >> 3) + (L >> 3);
     constexpr int GM = 8;
     const int band_sz = GM * tiles_n;
     const int band = L / band_sz;
@@ -148,22 +155,18 @@ __device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int&
     tn = rem / gm;
 }
 
-// Main kernel.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned rows.
+// One output tile of the main path.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned
+// rows.  The tile starts at token m0, feature n0; M and N bound the loads (clamped) and the stores.
 template <int TW, int TA, int WGN, int WGM, int EPI>
-__global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
-                                                        const bf16_t* __restrict__ W0,
-                                                        const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
-                                                        int ldo, int M, int N, int K, int tiles_m, int tiles_n) {
+__device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
+                                          const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
+                                          int N, int K, int m0, int n0, unsigned char* lds) {
     static_assert(WGN * WGM == 8, "8 waves");
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM, WROWS = BN * NW;
     constexpr int STAGE = (WROWS + BM) * BK * 2;
     constexpr int WLD = WROWS / 64, ALD = BM / 64;       // wave-loads per k-tile per wave (8 rows each)
     static_assert(WLD * 64 == WROWS && ALD * 64 == BM, "tile rows must split over 8 waves x 8 rows");
-    extern __shared__ __align__(16) unsigned char lds[];
-    int tm, tn;
-    tile_of_workgroup(tiles_m, tiles_n, tm, tn);
-    const int n0 = tn * BN, m0 = tm * BM;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wn = wave % WGN, wm = wave / WGN;
     const int l32 = lane & 31, hh = lane >> 5;
@@ -252,6 +255,50 @@ __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict
         store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
 }
 
+// Main kernel: every workgroup computes one tile of the same shape.
+template <int TW, int TA, int WGN, int WGM, int EPI>
+__global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
+                                                        const bf16_t* __restrict__ W0,
+                                                        const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
+                                                        int ldo, int M, int N, int K, int tiles_m, int tiles_n) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    int tm, tn;
+    tile_of_workgroup(blockIdx.x, true, tiles_m, tiles_n, tm, tn);
+    gemm_tile<TW, TA, WGN, WGM, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds);
+}
+
+// Shapes of the two-size launch: 256-token tiles for the first big_tiles_m token-tiles, 128-token tiles
+// (same feature width) for the rest.  Wave tiles: plain 64 tokens x 128 features (big), 64 x 64 (small);
+// SwiGLU 64 tokens x 64 gate + 64 up features (big), 64 x 32 + 32 (small).
+template <int EPI> struct TileShapes {
+    static constexpr int TW_BIG = EPI == EPI_SWIGLU ? 2 : 4, TW_SMALL = EPI == EPI_SWIGLU ? 1 : 2;
+    static constexpr int BN = 32 * TW_BIG * 2;           // = 32 * TW_SMALL * 4
+    static constexpr int BM_BIG = 256, BM_SMALL = 128;
+};
+
+// Two tile sizes in one launch.  Workgroups are started in id order, so the 256-token tiles run first
+// and the 128-token tiles fill the last, partly empty round of workgroups: the tail of the launch costs
+// about half a tile time instead of a whole one, and a ragged last token-tile wastes no MFMA work.
+template <int EPI>
+__global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* __restrict__ A, int lda,
+                                                                 const bf16_t* __restrict__ W0,
+                                                                 const bf16_t* __restrict__ W1, const bf16_t* R,
+                                                                 bf16_t* C, int ldo, int M, int N, int K,
+                                                                 int big_tiles_m, int small_tiles_m, int tiles_n) {
+    using S = TileShapes<EPI>;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int n_big = big_tiles_m * tiles_n;
+    int tm, tn;
+    if ((int)blockIdx.x < n_big) {
+        tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
+        gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds);
+    } else {
+        tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
+        gemm_tile<S::TW_SMALL, 2, 4, 2, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K,
+                                             big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds);
+    }
+}
+
 // Generic kernel (any k_in that is a multiple of 8): register-staged loads with k predicates.
 // TW x TA: number of 32-row MFMA tiles per wave along the weight (n) and activation (m) directions.
 // Workgroup = 4 waves arranged WGN x WGM.  SwiGLU uses two weight tiles per n (gate, up).
@@ -270,7 +317,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_generic_kernel(const bf16_t* __
     extern __shared__ __align__(16) unsigned char lds[];
 
     int tm, tn;
-    tile_of_workgroup(tiles_m, tiles_n, tm, tn);
+    tile_of_workgroup(blockIdx.x, true, tiles_m, tiles_n, tm, tn);
     const int n0 = tn * BN, m0 = tm * BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -373,17 +420,96 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
     return check_launch();
 }
 
+// How many 256-token tiles to run before the 128-token tiles.  Workgroups are handed to free CUs in id
+// order, which is list scheduling; it is simulated for each candidate and the shortest makespan wins.
+// The model, fitted to sweeps of the split on the layer's shapes:
+//   a 128-token tile costs small_cost of a 256-token one (0.5 plain, 0.6 SwiGLU);
+//   CU speeds are spread over +-8 % (tiles do not run equally fast on all CUs, which is what makes a
+//   fine-grained tail pay even when the large tiles fill whole rounds);
+//   +1 % / +3 % when the per-XCD run of large tiles is not a multiple of 8 / of 4 tiles (the run then
+//   straddles columns of the band walk and shares fewer operand panels in that XCD's L2);
+//   +5 % for fewer than 4 token-tiles of small tiles (too few rows to share a weight panel between the
+//   workgroups that run together).
+static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
+    static std::mutex mu;
+    static std::map<std::tuple<int, int, int>, int> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    const auto key = std::make_tuple(M, tiles_n, (int)(small_cost * 1000));
+    const auto hit = cache.find(key);
+    if (hit != cache.end()) return hit->second;
+    std::vector<double> speed(n_cu);
+    for (int c = 0; c < n_cu; ++c) speed[c] = 1.0 + 0.08 * ((double)((c * 97) % n_cu) / (n_cu - 1) * 2.0 - 1.0);
+    const int mb_max = M / 256;
+    int best_mb = mb_max;
+    double best = 1e300;
+    typedef std::pair<double, int> Slot;                 // (time the CU becomes free, CU)
+    for (int mb = mb_max; mb >= 0 && mb >= mb_max - 24; --mb) {
+        const int small_tiles_m = (M - mb * 256 + 127) / 128;
+        const long nb = (long)mb * tiles_n, ns = (long)small_tiles_m * tiles_n;
+        std::priority_queue<Slot, std::vector<Slot>, std::greater<Slot>> free_at;
+        for (int c = 0; c < n_cu; ++c) free_at.push(Slot(0.0, c));
+        double makespan = 0.0;
+        for (long i = 0; i < nb + ns; ++i) {
+            Slot s = free_at.top();
+            free_at.pop();
+            s.first += speed[s.second] * (i < nb ? 1.0 : small_cost);
+            if (s.first > makespan) makespan = s.first;
+            free_at.push(s);
+        }
+        if (nb > 0 && nb % 8 == 0) {
+            const long run = nb / 8;
+            if (run % 8 != 0) makespan *= 1.01;
+            if (run % 4 != 0) makespan *= 1.03;
+        }
+        if (small_tiles_m > 0 && small_tiles_m < 4 && mb > 0) makespan *= 1.05;
+        if (makespan < best) { best = makespan; best_mb = mb; }
+    }
+    cache[key] = best_mb;
+    return best_mb;
+}
+
+template <int EPI>
+static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
+                           int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st) {
+    using S = TileShapes<EPI>;
+    constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
+    auto kern = gemm_bf16_two_size_kernel<EPI>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return set_hip_error(e);
+        attr_done = true;
+    }
+    const int tiles_n = (N + S::BN - 1) / S::BN;
+    const int small_tiles_m = (M - big_tiles_m * S::BM_BIG + S::BM_SMALL - 1) / S::BM_SMALL;
+    hipLaunchKernelGGL(kern, dim3((big_tiles_m + small_tiles_m) * tiles_n), dim3(512), smem, st, A, lda, W0, W1, R, C,
+                       ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n);
+    return check_launch();
+}
+
+static int cu_count() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
 template <int EPI>
 static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                          int ldo, int M, int N, int K, hipStream_t st) {
     if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-    if constexpr (EPI == EPI_SWIGLU) {
-        if (M <= 128) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-        return launch_bf16<2, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-    } else {
-        if (M <= 128) return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-        return launch_bf16<4, 2, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    if (M <= 128) {
+        if constexpr (EPI == EPI_SWIGLU) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+        else return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
     }
+    const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;
+    return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.6 : 0.5), st);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
