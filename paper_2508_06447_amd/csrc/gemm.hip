@@ -9,7 +9,8 @@
 // Main kernel (k_in a multiple of 64): 8 waves per workgroup, two waves per SIMD, 256x256 output tile
 // (128 features x 2 matrices x 256 tokens for SwiGLU).  Operand tiles go from global memory straight
 // into LDS (global_load_lds_dwordx4, no VGPR staging), double-buffered; MFMA fragments are read one
-// k-step ahead of their use.  A register-staged kernel with k predicates covers ragged k_in.
+// k-step ahead of their use, across k-tiles too.  A register-staged kernel with k predicates covers
+// ragged k_in.
 #include "slim_common.h"
 
 #include <map>
@@ -207,45 +208,59 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
                 for (int v = 0; v < 16; ++v) acc[w][i][j][v] = 0.f;
 
     const int KT = K / BK;
+    bf16x8 af[2][TA], wf[2][NW][TW];
+    auto load_frags = [&](int stage, int ks, int buf) {
+        const unsigned char* ws = lds + stage * STAGE;
+        const unsigned char* as = ws + WROWS * BK * 2;
+#pragma unroll
+        for (int j = 0; j < TA; ++j)
+            af[buf][j] = *reinterpret_cast<const bf16x8*>(as + lds_off((wm * TA + j) * 32 + l32, ks * 2 + hh));
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+#pragma unroll
+            for (int i = 0; i < TW; ++i)
+                wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(
+                    ws + lds_off(w * BN + (wn * TW + i) * 32 + l32, ks * 2 + hh));
+    };
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int w = 0; w < NW; ++w)
+#pragma unroll
+            for (int i = 0; i < TW; ++i)
+#pragma unroll
+                for (int j = 0; j < TA; ++j)
+                    acc[w][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][w][i], af[buf][j], acc[w][i][j], 0, 0, 0);
+    };
+    // Two LDS stages.  Fragments are read one k-step ahead of their MFMAs, also across k-tiles: the
+    // workgroup barrier of a k-tile sits before its last k-step, when every wave has pulled that step's
+    // fragments into registers.  Past the barrier the stage is free, so tile kt+2 is sent into it, tile
+    // kt+1 (sent one iteration earlier, waited for just before the barrier) is visible to all waves, and
+    // its first fragments are read while the last k-step's MFMAs run.
     issue_loads(0, 0);
+    if (KT > 1) issue_loads(BK, 1);
     __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
     workgroup_barrier();
+    load_frags(0, 0, 0);
     for (int kt = 0; kt < KT; ++kt) {
-        // The other stage was last read in iteration kt-1, which every wave has left.
-        if (kt + 1 < KT) issue_loads((kt + 1) * BK, (kt + 1) & 1);
-        const unsigned char* ws = lds + (kt & 1) * STAGE;
-        const unsigned char* as = ws + WROWS * BK * 2;
-        bf16x8 af[2][TA], wf[2][NW][TW];
-        auto load_frags = [&](int ks, int buf) {
+        const int stage = kt & 1;
 #pragma unroll
-            for (int j = 0; j < TA; ++j)
-                af[buf][j] = *reinterpret_cast<const bf16x8*>(as + lds_off((wm * TA + j) * 32 + l32, ks * 2 + hh));
-#pragma unroll
-            for (int w = 0; w < NW; ++w)
-#pragma unroll
-                for (int i = 0; i < TW; ++i)
-                    wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(
-                        ws + lds_off(w * BN + (wn * TW + i) * 32 + l32, ks * 2 + hh));
-        };
-        load_frags(0, 0);
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            const int cur = ks & 1;
-            if (ks + 1 < BK / 16) load_frags(ks + 1, cur ^ 1);
+        for (int ks = 0; ks < BK / 16 - 1; ++ks) {
+            load_frags(stage, ks + 1, (ks + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);           // keep the next step's LDS reads ahead of these MFMAs
-#pragma unroll
-            for (int w = 0; w < NW; ++w)
-#pragma unroll
-                for (int i = 0; i < TW; ++i)
-#pragma unroll
-                    for (int j = 0; j < TA; ++j)
-                        acc[w][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[cur][w][i], af[cur][j], acc[w][i][j], 0, 0, 0);
+            mfmas(ks & 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_s_waitcnt(0x0070);              // this wave's tile kt+1 has landed; its LDS reads are done
+        __builtin_amdgcn_s_waitcnt(0x0070);              // own reads of this stage and own part of tile kt+1 done
         workgroup_barrier();
+        if (kt + 2 < KT) issue_loads((kt + 2) * BK, stage);
+        if (kt + 1 < KT) load_frags(stage ^ 1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas((BK / 16 - 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    // Every wave has left the k-loop (barrier above), so the stage buffers are free for the epilogue.
+    // The epilogue reuses the stage buffers: every wave must be past its last fragment reads.
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    workgroup_barrier();
     const bool wide = (N % 8 == 0) && (ldo % 8 == 0) && (((uintptr_t)C & 15) == 0) &&
                       (EPI != EPI_RESIDUAL || ((uintptr_t)R & 15) == 0);
     if (wide)
