@@ -57,12 +57,19 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
     const size_t qstride = (size_t)Hq * AD, kvstride = (size_t)Hkv * AD;
     const unsigned lds_base = (unsigned)(uintptr_t)lds;
 
-    // Q fragments (B operand): 8 k-steps x 8 bf16 of row qi, d = ks*16 + hh*8 ..
+    // Q fragments (B operand): 8 k-steps x 8 bf16 of row qi, d = ks*16 + hh*8 .., multiplied by
+    // softmax_scale * log2(e) once (rounded to bf16 again), so the MFMA result is the logit in the
+    // base-2 domain and the softmax needs no multiply per element.
     bf16x8 qf[8];
     {
         const bf16_t* qrow = Q + (size_t)min(qi, n - 1) * qstride + (size_t)h * AD + hh * 8;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+        for (int ks = 0; ks < 8; ++ks) {
+            bf16x8 raw = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) raw[e] = (__bf16)((float)raw[e] * scale_log2e);
+            qf[ks] = raw;
+        }
     }
 
     // Tile t -> stage t % NSTAGE.  A wave-load moves 4 key rows x 256 B; each tile is BKV/4 wave-loads for
@@ -104,7 +111,16 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    // Softmax state.  Logits are kept relative to a reference r per query: the S^T accumulators start
+    // from -r (negr, one value splat over the tile), so the MFMAs deliver s - r and P = exp2(s - r)
+    // needs no subtraction.  r is the row maximum of the first tile and moves only when a later logit
+    // exceeds it by more than REF_SLACK (then O and l are rescaled), so P <= 2^REF_SLACK; the final
+    // O / l does not depend on r.
+    constexpr float REF_SLACK = 8.0f;
+    float ref = 0.f, l_run = 0.f;
+    f32x16 negr;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) negr[v] = 0.f;
 
     const int last_q = min(q0 + BQ, n) - 1;
     const int n_kt = last_q / BKV + 1;                    // causal: tiles up to the last query's diagonal
@@ -118,16 +134,14 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
         issue_tile(kt + NSTAGE - 1);                      // its stage held tile kt-1, which every wave has left
         if (k0 <= qw0 + 31) {                             // some key of the tile is visible to this wave
             const unsigned sb = lds_base + (kt % NSTAGE) * STAGE_BYTES;
-            // ---- S^T = K Q^T : NJ 32-key sub-tiles
+            // ---- S^T - r = K Q^T - r : NJ 32-key sub-tiles
             f32x16 s[NJ];
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) s[jt][v] = 0.f;
-#pragma unroll
                 for (int st = 0; st < 8; ++st) {
                     const bf16x8 kf = *(SLIM_LDS_PTR(const bf16x8, sb + koff[st]) + jt * (32 * 256 / 16));
-                    s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], s[jt], 0, 0, 0);
+                    s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], st == 0 ? negr : s[jt], 0, 0, 0);
                 }
             }
             // ---- causal / ragged mask (selects only; the branch is wave-uniform)
@@ -139,38 +153,44 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
                     for (int v = 0; v < 16; ++v)
                         s[jt][v] = (jt * 32 + 8 * (v >> 2) + (v & 3)) > lim ? -INFINITY : s[jt][v];
             }
-            // ---- running max in the log2 domain (softmax_scale > 0, so the max commutes with it)
+            // ---- row maximum relative to the reference; move the reference if it is exceeded by too much
             float tmax = -INFINITY;
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) tmax = fmaxf(tmax, s[jt][v]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64)) * scale_log2e;
-            const float m_new = fmaxf(m_run, tmax);       // finite: key 0 is visible to every query
-            const bool changed = m_new > m_run;
-            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-            m_run = m_new;
-            // ---- P = exp2(S*c - m), rounded to bf16 for the MFMA; the row sum adds the rounded values
+                for (int v = 0; v < 16; v += 2) tmax = fmaxf(fmaxf(tmax, s[jt][v]), s[jt][v + 1]);
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+            const bool first = kt == 0;                   // every wave computes tile 0, where key 0 is visible
+            if (first || __any(tmax > REF_SLACK)) {
+                const float delta = first ? tmax : fmaxf(tmax, 0.f);
+                ref += delta;
+#pragma unroll
+                for (int jt = 0; jt < NJ; ++jt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s[jt][v] -= delta;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) negr[v] = -ref;
+                if (!first) {
+                    const float alpha = __builtin_amdgcn_exp2f(-delta);
+                    l_run *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
+                }
+            }
+            // ---- P = exp2(s - r), rounded to bf16 for the MFMA; the row sum adds the rounded values
             uint32_t pb[NJ][8];
-            float psum = 0.f;
             const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
             for (int jt = 0; jt < NJ; ++jt)
 #pragma unroll
                 for (int v = 0; v < 16; v += 2) {
-                    const f32x2 p = {__builtin_amdgcn_exp2f(__builtin_fmaf(s[jt][v], scale_log2e, -m_new)),
-                                     __builtin_amdgcn_exp2f(__builtin_fmaf(s[jt][v + 1], scale_log2e, -m_new))};
+                    const f32x2 p = {__builtin_amdgcn_exp2f(s[jt][v]), __builtin_amdgcn_exp2f(s[jt][v + 1])};
                     const bf16x2 p2 = __builtin_convertvector(p, bf16x2);
-                    psum = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, psum, false);
+                    l_run = __builtin_amdgcn_fdot2_f32_bf16(p2, ones, l_run, false);
                     pb[jt][v >> 1] = __builtin_bit_cast(uint32_t, p2);
                 }
-            l_run = l_run * alpha + psum;
-            if (__any(changed)) {                         // rescale only when some row's max moved
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) oacc[dt][v] *= alpha;
-            }
             // ---- O^T += V^T P^T : 2*NJ k-steps of 16 keys; step (jt, half) uses accumulator values
             //      v = half*8 .. half*8+7 of sub-tile jt, i.e. keys jt*32 + half*16 + {4*hh+0..3, 8+4*hh+0..3}
             constexpr int ROW = 256 / 8;                  // one key row in units of 8 bytes
