@@ -127,14 +127,20 @@ def measured_ceilings(slim, dev):
     def mfma():
         flops[0] = slim.probe_mfma(2048, 4096, sink)
 
+    def mfma_random():
+        flops[0] = slim.probe_mfma(2048, 4096, sink, random_operands=True)
+
     _, ms = time_gpu(mfma, 5, warmup=2)
+    _, ms_r = time_gpu(mfma_random, 5, warmup=2)
     src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     dst = torch.empty_like(src)
     _, ms_c = time_gpu(lambda: slim.probe_copy(src, dst), 5, warmup=2)
     return {"mfma_loop_tflops": round(flops[0] / (ms * 1e-3) / 1e12, 1),
+            "mfma_loop_random_operands_tflops": round(flops[0] / (ms_r * 1e-3) / 1e12, 1),
             "copy_gbs": round(2 * src.numel() / (ms_c * 1e-3) / 1e9, 1),
-            "note": "register-only v_mfma_f32_32x32x16_bf16 loop (2048 workgroups x 8 waves); 1 GiB device copy, "
-                    "read + write bytes"}
+            "note": "register-only v_mfma_f32_32x32x16_bf16 loop (2048 workgroups x 8 waves) with constant and "
+                    "with pseudo-random operands (the chip clocks lower when operand bits toggle); 1 GiB device "
+                    "copy, read + write bytes"}
 
 
 def cpu_baseline(wl_full, sample_tokens=32768):

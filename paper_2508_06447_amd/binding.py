@@ -84,7 +84,7 @@ def load_library(path: str | None = None) -> C.CDLL:
                                        vp, sz, vp]
     lib.slim_probe_mfma_flops.restype = C.c_double
     lib.slim_probe_mfma_flops.argtypes = [i, i]
-    lib.slim_probe_mfma.argtypes = [i, i, vp, vp]
+    lib.slim_probe_mfma.argtypes = [i, i, i, vp, vp]
     lib.slim_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name)                      # every declared symbol must resolve
@@ -326,10 +326,11 @@ def slim_prefill_model(shape: LayerShape, layer_weights: list, x: torch.Tensor, 
     return out
 
 
-def probe_mfma(n_workgroups: int, iters: int, sink: torch.Tensor) -> float:
+def probe_mfma(n_workgroups: int, iters: int, sink: torch.Tensor, random_operands: bool = False) -> float:
     """Enqueue the register-only MFMA loop; returns its flop count."""
     lib = load_library()
-    _check(lib.slim_probe_mfma(n_workgroups, iters, _dev(sink, "sink"), _stream()), "slim_probe_mfma")
+    _check(lib.slim_probe_mfma(n_workgroups, iters, int(random_operands), _dev(sink, "sink"), _stream()),
+           "slim_probe_mfma")
     return lib.slim_probe_mfma_flops(n_workgroups, iters)
 
 

@@ -134,14 +134,25 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
         issue_tile(kt + NSTAGE - 1);                      // its stage held tile kt-1, which every wave has left
         if (k0 <= qw0 + 31) {                             // some key of the tile is visible to this wave
             const unsigned sb = lds_base + (kt % NSTAGE) * STAGE_BYTES;
-            // ---- S^T - r = K Q^T - r : NJ 32-key sub-tiles
+            // ---- S^T - r = K Q^T - r : NJ 32-key sub-tiles.  Fragment f = (k-step st, sub-tile jt) is
+            //      read KAHEAD MFMAs before its use (the compiler, left alone, reads each fragment right
+            //      before its MFMA and waits for it); consecutive MFMAs go to different accumulators.
             f32x16 s[NJ];
+            {
+                constexpr int NF = 8 * NJ, KAHEAD = 3;
+                bf16x8 kf[KAHEAD + 1];
+                auto ldk = [&](int f) {
+                    return *(SLIM_LDS_PTR(const bf16x8, sb + koff[f / NJ]) + (f % NJ) * (32 * 256 / 16));
+                };
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt) {
+                for (int f = 0; f < KAHEAD; ++f) kf[f] = ldk(f);
 #pragma unroll
-                for (int st = 0; st < 8; ++st) {
-                    const bf16x8 kf = *(SLIM_LDS_PTR(const bf16x8, sb + koff[st]) + jt * (32 * 256 / 16));
-                    s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[st], st == 0 ? negr : s[jt], 0, 0, 0);
+                for (int f = 0; f < NF; ++f) {
+                    const int st = f / NJ, jt = f % NJ;
+                    if (f + KAHEAD < NF) kf[(f + KAHEAD) % (KAHEAD + 1)] = ldk(f + KAHEAD);
+                    __builtin_amdgcn_sched_barrier(0);
+                    s[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[f % (KAHEAD + 1)], qf[st], st == 0 ? negr : s[jt], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
             // ---- causal / ragged mask (selects only; the branch is wave-uniform)
@@ -193,23 +204,32 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
                 }
             // ---- O^T += V^T P^T : 2*NJ k-steps of 16 keys; step (jt, half) uses accumulator values
             //      v = half*8 .. half*8+7 of sub-tile jt, i.e. keys jt*32 + half*16 + {4*hh+0..3, 8+4*hh+0..3}
-            constexpr int ROW = 256 / 8;                  // one key row in units of 8 bytes
+            //      Fragment g = (step, dt) is read VAHEAD MFMAs ahead, like the K fragments.
+            {
+                constexpr int ROW = 256 / 8;              // one key row in units of 8 bytes
+                constexpr int NG = 8 * NJ, VAHEAD = 3;
+                i16x4 vlo[VAHEAD + 1], vhi[VAHEAD + 1];
+                auto ldv = [&](int g) {
+                    const int r0 = (g >> 2) * 16 * ROW, b = g % (VAHEAD + 1);
+                    vlo[b] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SLIM_LDS_PTR(i16x4, sb + voff[g & 3]) + r0);
+                    vhi[b] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SLIM_LDS_PTR(i16x4, sb + voff[g & 3]) + r0 + 8 * ROW);
+                };
 #pragma unroll
-            for (int jt = 0; jt < NJ; ++jt)
+                for (int g = 0; g < VAHEAD; ++g) ldv(g);
 #pragma unroll
-                for (int half = 0; half < 2; ++half) {
+                for (int g = 0; g < NG; ++g) {
+                    const int step = g >> 2, jt = step >> 1, half = step & 1, dt = g & 3;
+                    if (g + VAHEAD < NG) ldv(g + VAHEAD);
+                    __builtin_amdgcn_sched_barrier(0);
                     const bf16x8 pf = __builtin_bit_cast(bf16x8, make_uint4(pb[jt][half * 4 + 0], pb[jt][half * 4 + 1],
                                                                             pb[jt][half * 4 + 2], pb[jt][half * 4 + 3]));
-                    const int r0 = (jt * 32 + half * 16) * ROW;
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) {
-                        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SLIM_LDS_PTR(i16x4, sb + voff[dt]) + r0);
-                        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(SLIM_LDS_PTR(i16x4, sb + voff[dt]) + r0 + 8 * ROW);
-                        const uint2 lo2 = __builtin_bit_cast(uint2, lo), hi2 = __builtin_bit_cast(uint2, hi);
-                        const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
-                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
-                    }
+                    const uint2 lo2 = __builtin_bit_cast(uint2, vlo[g % (VAHEAD + 1)]);
+                    const uint2 hi2 = __builtin_bit_cast(uint2, vhi[g % (VAHEAD + 1)]);
+                    const bf16x8 vf = __builtin_bit_cast(bf16x8, make_uint4(lo2.x, lo2.y, hi2.x, hi2.y));
+                    oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+            }
         }
         // Tile kt+1 has landed for this wave (the newer tile's loads may stay in flight); its own LDS
         // reads are done; after the barrier that holds for every wave.
