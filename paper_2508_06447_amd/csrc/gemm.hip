@@ -167,34 +167,41 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
     constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM, WROWS = BN * NW;
     constexpr int STAGE = (WROWS + BM) * BK * 2;
     constexpr int WLD = WROWS / 64, ALD = BM / 64;       // wave-loads per k-tile per wave (8 rows each)
-    static_assert(WLD * 64 == WROWS && ALD * 64 == BM, "tile rows must split over 8 waves x 8 rows");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    static_assert(WLD * 64 == WROWS && ALD * 64 == BM && BN % 64 == 0, "tile rows must split over 8 waves x 8 rows");
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave % WGN, wm = wave / WGN;
     const int l32 = lane & 31, hh = lane >> 5;
 
     // Wave-load i covers rows (i*8 + wave)*8 + lane/8 of the tile; lane%8 is the LDS chunk slot, which
-    // holds logical chunk slot ^ swz(row).  Row pointers are loop-invariant.
-    const bf16_t* wsrc[WLD];
-    const bf16_t* asrc[ALD];
+    // holds logical chunk slot ^ swz(row).  A load's address is a wave-uniform base (start of the tile's
+    // rows + k offset, scalar registers) plus a loop-invariant per-lane byte offset inside the tile, so
+    // the k-loop spends no vector instruction on addresses (a tile spans at most 256 rows: 32 bits do).
+    unsigned woff[WLD], aoff[ALD];
 #pragma unroll
     for (int i = 0; i < WLD; ++i) {
         const int r = (i * 8 + wave) * 8 + (lane >> 3);
         const int mat = NW == 2 ? r / BN : 0;
-        const int n = min(n0 + r - mat * BN, N - 1);
-        wsrc[i] = (mat ? W1 : W0) + (size_t)n * K + ((lane & 7) ^ swz(r)) * 8;
+        const int n = min(n0 + r - mat * BN, N - 1) - n0;
+        woff[i] = (unsigned)(((size_t)n * K + ((lane & 7) ^ swz(r)) * 8) * 2);
     }
 #pragma unroll
     for (int i = 0; i < ALD; ++i) {
         const int r = (i * 8 + wave) * 8 + (lane >> 3);
-        asrc[i] = A + (size_t)min(m0 + r, M - 1) * lda + ((lane & 7) ^ swz(r)) * 8;
+        aoff[i] = (unsigned)(((size_t)(min(m0 + r, M - 1) - m0) * lda + ((lane & 7) ^ swz(r)) * 8) * 2);
     }
+    const bf16_t* w0base = W0 + (size_t)n0 * K;
+    const bf16_t* w1base = NW == 2 ? W1 + (size_t)n0 * K : W0;
+    const bf16_t* abase = A + (size_t)m0 * lda;
+    const unsigned lds_wave = (unsigned)(uintptr_t)lds + wave * 1024;
     auto issue_loads = [&](int k0, int stage) {
-        unsigned char* ws = lds + stage * STAGE;
-        unsigned char* as = ws + WROWS * BK * 2;
+        const unsigned ws = lds_wave + stage * STAGE, as = ws + WROWS * BK * 2;
 #pragma unroll
-        for (int i = 0; i < WLD; ++i) load_global_to_lds16(wsrc[i] + k0, ws + (i * 8 + wave) * 1024);
+        for (int i = 0; i < WLD; ++i) {
+            const bool second = NW == 2 && (i * 8 * 8 >= BN);   // rows of wave-load i lie in one matrix (BN % 64 == 0)
+            load_global_to_lds16((second ? w1base : w0base) + k0, woff[i], ws + i * 8 * 1024);
+        }
 #pragma unroll
-        for (int i = 0; i < ALD; ++i) load_global_to_lds16(asrc[i] + k0, as + (i * 8 + wave) * 1024);
+        for (int i = 0; i < ALD; ++i) load_global_to_lds16(abase + k0, aoff[i], as + i * 8 * 1024);
     };
 
     f32x16 acc[NW][TW][TA];

@@ -74,6 +74,13 @@ __device__ __forceinline__ void load_global_to_lds16(const void* g, void* lds_wa
     const unsigned la = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)lds_wave_base);
     asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
 }
+// Same, with the global address split into a wave-uniform 64-bit base (scalar registers) and a per-lane
+// 32-bit byte offset: a load whose base moves every iteration then costs scalar instructions only.
+__device__ __forceinline__ void load_global_to_lds16(const void* uniform_base, unsigned lane_byte_offset,
+                                                     unsigned lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 ::"v"(lane_byte_offset), "s"(uniform_base), "s"(lds_wave_base) : "memory", "m0");
+}
 __device__ __forceinline__ void workgroup_barrier() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
