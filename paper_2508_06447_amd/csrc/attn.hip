@@ -73,21 +73,44 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
     }
 
     // Tile t -> stage t % NSTAGE.  A wave-load moves 4 key rows x 256 B; each tile is BKV/4 wave-loads for
-    // K and as many for V, spread evenly over the waves.  Lane l lands at LDS slot l%16 of row l/16, so it fetches the
-    // global chunk that the swizzle assigns to that slot.  Tiles past the end re-read the last tile into
-    // a stage nobody reads, which keeps the count of loads in flight the same in every iteration.
+    // K and as many for V, spread evenly over the waves.  Lane l lands at LDS slot l%16 of row l/16, so it
+    // fetches the global chunk that the swizzle assigns to that slot.  A load's address is a wave-uniform
+    // base (first row of the tile, scalar registers) plus a loop-invariant per-lane byte offset; only the
+    // last, ragged tile recomputes the offsets with its rows clamped to n-1.  Tiles past the end re-read
+    // the last tile into a stage nobody reads, which keeps the count of loads in flight the same in
+    // every iteration.
     const bf16_t* kbase = Kg + (size_t)g * AD;
     const bf16_t* vbase = Vg + (size_t)g * AD;
     const int n_kt_all = (n + BKV - 1) / BKV;
+    constexpr int NLD = BKV / 4 / ANW;                    // wave-loads per wave per tile and operand
+    const int uwave = __builtin_amdgcn_readfirstlane(wave);
+    unsigned kofs[NLD], vofs[NLD];
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+        const int r = (i * ANW + uwave) * 4 + (lane >> 4), slot = lane & 15;
+        kofs[i] = (unsigned)(((size_t)r * kvstride + (slot ^ (r & 15)) * 8) * 2);
+        vofs[i] = (unsigned)(((size_t)r * kvstride + (slot ^ ((r & 3) << 2)) * 8) * 2);
+    }
     auto issue_tile = [&](int t) {
         const int k0 = min(t, n_kt_all - 1) * BKV;
-        unsigned char* stage = lds + (t % NSTAGE) * STAGE_BYTES;
+        const unsigned stage = lds_base + (t % NSTAGE) * STAGE_BYTES + uwave * 1024;
+        const bf16_t* kt0 = kbase + (size_t)k0 * kvstride;
+        const bf16_t* vt0 = vbase + (size_t)k0 * kvstride;
+        if (k0 + BKV <= n) {
 #pragma unroll
-        for (int i = 0; i < BKV / 4 / ANW; ++i) {
-            const int rg = i * ANW + wave, r = rg * 4 + (lane >> 4), slot = lane & 15;
-            const size_t row = (size_t)min(k0 + r, n - 1) * kvstride;
-            load_global_to_lds16(kbase + row + (slot ^ (r & 15)) * 8, stage + rg * 1024);
-            load_global_to_lds16(vbase + row + (slot ^ ((r & 3) << 2)) * 8, stage + TILE_BYTES + rg * 1024);
+            for (int i = 0; i < NLD; ++i) {
+                load_global_to_lds16(kt0, kofs[i], stage + i * ANW * 1024);
+                load_global_to_lds16(vt0, vofs[i], stage + TILE_BYTES + i * ANW * 1024);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int r = (i * ANW + uwave) * 4 + (lane >> 4), slot = lane & 15;
+                const size_t row = (size_t)(min(k0 + r, n - 1) - k0) * kvstride;
+                load_global_to_lds16(kt0, (unsigned)((row + (slot ^ (r & 15)) * 8) * 2), stage + i * ANW * 1024);
+                load_global_to_lds16(vt0, (unsigned)((row + (slot ^ ((r & 3) << 2)) * 8) * 2),
+                                     stage + TILE_BYTES + i * ANW * 1024);
+            }
         }
     };
 
