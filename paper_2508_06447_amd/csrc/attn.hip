@@ -41,13 +41,19 @@ __global__ void __launch_bounds__(64 * ANW) attn_bf16_kernel(const bf16_t* __res
                                                              const bf16_t* __restrict__ Vg, bf16_t* __restrict__ O,
                                                              int n, int Hq, int Hkv, float scale_log2e, int n_qt) {
     extern __shared__ __align__(16) unsigned char lds[];
-    // Workgroup -> (head, query tile).  Ids are dealt round-robin to the 8 XCDs; give each XCD a
-    // contiguous range of heads so the query heads sharing a kv head meet in one L2, and start the
-    // query tiles with the most keys first.
-    int L = blockIdx.x;
-    const int total = n_qt * Hq;
-    if (total % 8 == 0) L = (L & 7) * (total >> 3) + (L >> 3);
-    const int h = L / n_qt, qt_idx = n_qt - 1 - (L - h * n_qt);
+    // Workgroup -> (head, query tile).  Ids are dealt round-robin to the 8 XCDs and each XCD hands its
+    // workgroups to its CUs in id order.  Give each XCD a contiguous range of heads, so the query heads
+    // sharing a kv head meet in one L2, and walk that range's query tiles from the one with the most keys
+    // down, all heads of the range at each size: longest-first order per XCD keeps its CUs evenly loaded.
+    int h, qt_idx;
+    if (Hq % 8 == 0) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, hpx = Hq >> 3;
+        h = xcd * hpx + j % hpx;
+        qt_idx = n_qt - 1 - j / hpx;
+    } else {
+        h = blockIdx.x % Hq;
+        qt_idx = n_qt - 1 - blockIdx.x / Hq;
+    }
     const int g = h / (Hq / Hkv);
     const int q0 = qt_idx * BQ;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
