@@ -17,6 +17,7 @@
 #include <mutex>
 #include <queue>
 #include <tuple>
+#include <type_traits>
 #include <vector>
 
 namespace slim {
@@ -216,18 +217,29 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
 
     const int KT = K / BK;
     bf16x8 af[2][TA], wf[2][NW][TW];
-    auto load_frags = [&](int stage, int ks, int buf) {
-        const unsigned char* ws = lds + stage * STAGE;
-        const unsigned char* as = ws + WROWS * BK * 2;
+    // Fragment addresses: one per-lane base per (operand, stage, k-step), computed once; the MFMA tile
+    // (i, j) and the matrix (gate/up) are immediate offsets of the LDS reads, so the k-loop spends no
+    // vector instruction on them.  The swizzle term (row >> 1) & 7 depends only on lane % 32 because the
+    // tile rows of a wave start at multiples of 32.
+    const unsigned char* wfrag[2][BK / 16];
+    const unsigned char* afrag[2][BK / 16];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            wfrag[st][ks] = lds + st * STAGE + lds_off(wn * TW * 32 + l32, ks * 2 + hh);
+            afrag[st][ks] = lds + st * STAGE + WROWS * BK * 2 + lds_off(wm * TA * 32 + l32, ks * 2 + hh);
+        }
+    auto load_frags = [&](auto stage_c, int ks, int buf) {
+        constexpr int stage = decltype(stage_c)::value;
 #pragma unroll
         for (int j = 0; j < TA; ++j)
-            af[buf][j] = *reinterpret_cast<const bf16x8*>(as + lds_off((wm * TA + j) * 32 + l32, ks * 2 + hh));
+            af[buf][j] = *reinterpret_cast<const bf16x8*>(afrag[stage][ks] + j * 32 * BK * 2);
 #pragma unroll
         for (int w = 0; w < NW; ++w)
 #pragma unroll
             for (int i = 0; i < TW; ++i)
-                wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(
-                    ws + lds_off(w * BN + (wn * TW + i) * 32 + l32, ks * 2 + hh));
+                wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(wfrag[stage][ks] + (w * BN + i * 32) * BK * 2);
     };
     auto mfmas = [&](int buf) {
 #pragma unroll
@@ -242,17 +254,15 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
     // workgroup barrier of a k-tile sits before its last k-step, when every wave has pulled that step's
     // fragments into registers.  Past the barrier the stage is free, so tile kt+2 is sent into it, tile
     // kt+1 (sent one iteration earlier, waited for just before the barrier) is visible to all waves, and
-    // its first fragments are read while the last k-step's MFMAs run.
-    issue_loads(0, 0);
-    if (KT > 1) issue_loads(BK, 1);
-    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
-    workgroup_barrier();
-    load_frags(0, 0, 0);
-    for (int kt = 0; kt < KT; ++kt) {
-        const int stage = kt & 1;
+    // its first fragments are read while the last k-step's MFMAs run.  The loop is unrolled by two so the
+    // stage of every read is a compile-time constant.
+    using Stage0 = std::integral_constant<int, 0>;
+    using Stage1 = std::integral_constant<int, 1>;
+    auto k_tile = [&](int kt, auto stage_c, auto other_c) {
+        constexpr int stage = decltype(stage_c)::value;
 #pragma unroll
         for (int ks = 0; ks < BK / 16 - 1; ++ks) {
-            load_frags(stage, ks + 1, (ks + 1) & 1);
+            load_frags(stage_c, ks + 1, (ks + 1) & 1);
             __builtin_amdgcn_sched_barrier(0);           // keep the next step's LDS reads ahead of these MFMAs
             mfmas(ks & 1);
             __builtin_amdgcn_sched_barrier(0);
@@ -260,10 +270,19 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
         __builtin_amdgcn_s_waitcnt(0x0070);              // own reads of this stage and own part of tile kt+1 done
         workgroup_barrier();
         if (kt + 2 < KT) issue_loads((kt + 2) * BK, stage);
-        if (kt + 1 < KT) load_frags(stage ^ 1, 0, 0);
+        if (kt + 1 < KT) load_frags(other_c, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfmas((BK / 16 - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
+    };
+    issue_loads(0, 0);
+    if (KT > 1) issue_loads(BK, 1);
+    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
+    workgroup_barrier();
+    load_frags(Stage0{}, 0, 0);
+    for (int kt = 0; kt < KT; kt += 2) {
+        k_tile(kt, Stage0{}, Stage1{});
+        if (kt + 1 < KT) k_tile(kt + 1, Stage1{}, Stage0{});
     }
     // The epilogue reuses the stage buffers: every wave must be past its last fragment reads.
     __builtin_amdgcn_s_waitcnt(0x0070);
