@@ -464,7 +464,7 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
 // How many 256-token tiles to run before the 128-token tiles.  Workgroups are handed to free CUs in id
 // order, which is list scheduling; it is simulated for each candidate and the shortest makespan wins.
 // The model, fitted to sweeps of the split on the layer's shapes:
-//   a 128-token tile costs small_cost of a 256-token one (0.5 plain, 0.6 SwiGLU);
+//   a 128-token tile costs small_cost of a 256-token one (0.5 plain, 0.55 SwiGLU);
 //   CU speeds are spread over +-8 % (tiles do not run equally fast on all CUs, which is what makes a
 //   fine-grained tail pay even when the large tiles fill whole rounds);
 //   +1 % / +3 % when the per-XCD run of large tiles is not a multiple of 8 / of 4 tiles (the run then
@@ -550,7 +550,7 @@ static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_
         else return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
     }
     const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;
-    return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.6 : 0.5), st);
+    return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.55 : 0.5), st);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
