@@ -227,7 +227,7 @@ def bench_model(args, slim, inputs, wl, dev):
     act = torch.empty(n0, F, device=dev, dtype=torch.bfloat16)
     med, mean = time_gpu(lambda: slim.slim_swiglu_linear(h, w_gpu[0]["w_gate"], w_gpu[0]["w_up"], out=act), 10)
     tf = 4 * n0 * Hd * F / (mean * 1e-3) / 1e12
-    rec["roofline"] = {"kernel": "gemm_bf16_kernel (SwiGLU gate/up projection, 32768 tokens)", "bound": "mfma",
+    rec["roofline"] = {"kernel": "gemm_bf16_two_size_kernel (SwiGLU gate/up projection, 32768 tokens)", "bound": "mfma",
                        "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                        "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None, "avg_ms": round(mean, 4)}
     print(json.dumps(rec))
@@ -309,9 +309,9 @@ def main():
         table = stage_table(slim, wl, wd, x, pos, n_keep, reps=max(5, args.steps))
         rec["kernels"] = table
         dom = table["ffn_gate_up_swiglu"]
-        rec["roofline"] = {"kernel": "gemm_bf16_kernel (SwiGLU gate/up projection)", "bound": "mfma",
+        rec["roofline"] = {"kernel": "gemm_bf16_two_size_kernel (SwiGLU gate/up projection)", "bound": "mfma",
                            "achieved": dom["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": dom["frac"], "traffic": profiled_traffic("gemm_bf16_kernel<2, 2, 2, 4, 2>"),
+                           "frac": dom["frac"], "traffic": profiled_traffic("gemm_bf16_two_size_kernel<2>"),
                            "traffic_unit": "bytes per launch, rocprofv3 FETCH_SIZE x2 + WRITE_SIZE (profiles/)",
                            "algorithmic_bytes": 2 * (n * Hd + 2 * F * Hd + n * F), "avg_ms": dom["ms"]}
     if not args.no_stages:
