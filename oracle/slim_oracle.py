@@ -125,6 +125,25 @@ def block_scores(q_win: np.ndarray, k: np.ndarray, block: int, unit: int) -> np.
     return out
 
 
+def block_scores_pooled(q_win: np.ndarray, k: np.ndarray, block: int, pooling: str) -> np.ndarray:
+    """The two baselines of the block-scoring ablation (Table 3, "Block Importance Scoring Algorithm"):
+    one representative key per block, either the average of the block's token key states ("avg") or
+    their element-wise maximum ("max"), scored against the window query as in Eq. (2):
+    r_j = (1/H) sum_h q_l^h . k_pool^h(j).  A short last block pools the tokens it has."""
+    assert pooling in ("avg", "max")
+    Hq, Hkv = q_win.shape[1], k.shape[1]
+    G = Hq // Hkv
+    q_l = window_query(q_win)                                   # [Hq, d]
+    N = k.shape[0]
+    out = np.empty(n_blocks(N, block), dtype=k.dtype)
+    for j in range(out.shape[0]):
+        kb = k[j * block:min((j + 1) * block, N)]               # [len, Hkv, d]
+        k_pool = kb.mean(axis=0) if pooling == "avg" else kb.max(axis=0)
+        k_pool_h = np.repeat(k_pool, G, axis=0)                 # [Hq, d]: head h -> kv head h//G
+        out[j] = np.einsum("hd,hd->h", q_l, k_pool_h).mean()
+    return out
+
+
 def select_blocks(scores: np.ndarray, n_keep: int, force_first: bool = True,
                   force_last: bool = True) -> np.ndarray:
     """Forced blocks (first = attention sink; last) are always kept; the remaining
@@ -223,6 +242,7 @@ class LayerShape:
     window: int
     rope_theta: float = 500000.0
     rms_eps: float = 1e-5
+    scoring: str = "unit"          # "unit": Eq. (1)-(2); "avg" / "max": the pooled baselines of Table 3
 
 
 @dataclass
@@ -260,6 +280,8 @@ def layer_scores(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
     w_eff = min(s.window, N)
     q_win = project_heads(h[N - w_eff:], w.wq, s.n_q_heads, s.head_dim, pos[N - w_eff:],
                           s.rope_theta, True, rounding)
+    if s.scoring != "unit":
+        return block_scores_pooled(q_win, k, s.block, s.scoring), k
     return block_scores(q_win, k, s.block, s.unit), k
 
 

@@ -245,6 +245,66 @@ def test_scores_head_mapping_is_grouped_not_interleaved():
     np.testing.assert_allclose(so.block_scores(q, k, 2, 1), [1.0], rtol=1e-15)   # 4 / Hq
 
 
+def brute_pooled(q_win, k, block, pooling):
+    """Scalar loops from the description of the two baselines (Table 3): one pooled key per block."""
+    w, Hq, d = q_win.shape
+    N, Hkv, _ = k.shape
+    G = Hq // Hkv
+    out = []
+    for b0 in range(0, N, block):
+        b1 = min(b0 + block, N)
+        acc = 0.0
+        for h in range(Hq):
+            for c in range(d):
+                ql = sum(q_win[i, h, c] for i in range(w)) / w
+                vals = [k[t, h // G, c] for t in range(b0, b1)]
+                acc += ql * (sum(vals) / len(vals) if pooling == "avg" else max(vals))
+        out.append(acc / Hq)
+    return np.array(out)
+
+
+@pytest.mark.parametrize("pooling", ["avg", "max"])
+@pytest.mark.parametrize("N,block,w,Hq,Hkv,d", [(24, 8, 3, 4, 2, 4), (29, 8, 5, 6, 2, 2), (10, 4, 4, 2, 1, 6)])
+def test_pooled_scores_match_scalar_brute_force_incl_ragged(pooling, N, block, w, Hq, Hkv, d):
+    q, k = rng.standard_normal((w, Hq, d)), rng.standard_normal((N, Hkv, d))
+    np.testing.assert_allclose(so.block_scores_pooled(q, k, block, pooling), brute_pooled(q, k, block, pooling),
+                               rtol=1e-11, atol=1e-12)
+
+
+def test_pooled_scores_special_cases():
+    w, Hq, Hkv, d, B, nb = 3, 4, 2, 8, 8, 5
+    q = rng.standard_normal((w, Hq, d))
+    k = rng.standard_normal((nb * B, Hkv, d))
+    # average pooling is Eq. (1)-(2) with a single TokenUnit per block
+    np.testing.assert_allclose(so.block_scores_pooled(q, k, B, "avg"), so.block_scores(q, k, B, B), rtol=1e-12)
+    # keys constant inside each block: every pooling and every unit size agree
+    kc = np.repeat(rng.standard_normal((nb, Hkv, d)), B, axis=0)
+    ref = so.block_scores(q, kc, B, 1)
+    np.testing.assert_allclose(so.block_scores_pooled(q, kc, B, "max"), ref, rtol=1e-12)
+    np.testing.assert_allclose(so.block_scores_pooled(q, kc, B, "avg"), ref, rtol=1e-12)
+    # d = 1, one head, positive query: max pooling is q times the largest key of the block; with a negative
+    # query it still takes the element-wise maximum (the pooled key does not depend on the query)
+    k1 = rng.standard_normal((4 * B, 1, 1))
+    q1 = np.full((2, 1, 1), 0.7)
+    np.testing.assert_allclose(so.block_scores_pooled(q1, k1, B, "max"), 0.7 * k1.reshape(4, B).max(1), rtol=1e-12)
+    np.testing.assert_allclose(so.block_scores_pooled(-q1, k1, B, "max"), -0.7 * k1.reshape(4, B).max(1), rtol=1e-12)
+    # the order of the tokens inside a block does not matter; raising a key element never lowers the score
+    # where the query element is positive
+    perm = np.concatenate([j * B + rng.permutation(B) for j in range(nb)])
+    for pooling in ("avg", "max"):
+        np.testing.assert_allclose(so.block_scores_pooled(q, k[perm], B, pooling),
+                                   so.block_scores_pooled(q, k, B, pooling), rtol=1e-12)
+    qpos = np.abs(q)
+    k2 = k.copy()
+    k2[5, 1, 3] += 10.0
+    assert (so.block_scores_pooled(qpos, k2, B, "max") >= so.block_scores_pooled(qpos, k, B, "max") - 1e-12).all()
+    # grouped head mapping, as in Eq. (2)
+    qh = np.zeros((1, 4, 2)); qh[0, 1] = [1.0, 0.0]
+    kh = np.zeros((2, 2, 2)); kh[:, 0] = [[4.0, 0.0], [2.0, 0.0]]; kh[:, 1] = [-100.0, 0.0]
+    np.testing.assert_allclose(so.block_scores_pooled(qh, kh, 2, "max"), [1.0], rtol=1e-15)
+    np.testing.assert_allclose(so.block_scores_pooled(qh, kh, 2, "avg"), [0.75], rtol=1e-15)
+
+
 # ----------------------------------------------------------------------------- selection
 def valid_selection(scores, kept, n_keep, ff, fl):
     nb = len(scores)
