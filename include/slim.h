@@ -64,6 +64,19 @@ int slim_score_blocks(const void* q_win, const void* k, int n_tokens, int window
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Pooled block scores -- the two baselines of the scoring ablation (Table 3, "Block Importance
+ * Scoring Algorithm"): one representative key per block, the average of its token Key states
+ * (SLIM_POOL_AVG, which is Eq. 1-2 with a single TokenUnit per block) or their element-wise maximum
+ * (SLIM_POOL_MAX), scored like Eq. (2):  scores[j] = (1/Hq) sum_h q_l^h . k_pool^{h/(Hq/Hkv)}(j).
+ * Arguments, layouts, workspace and errors as slim_score_blocks (no unit); INVALID_ARG for another
+ * pooling value.
+ */
+enum { SLIM_POOL_AVG = 1, SLIM_POOL_MAX = 2 };
+int slim_score_blocks_pooled(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads,
+                             int n_kv_heads, int head_dim, int block, int pooling, int dtype,
+                             float* scores, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Block selection -- last paragraph of Section 4.2: the first block (attention sink) is always
  * kept; here the last block can be forced as well.  The remaining n_keep - #forced slots go to the
  * other blocks by (score descending, block index ascending).  n_keep counts the forced blocks.
@@ -127,6 +140,7 @@ typedef struct slim_layer_shape {
     float rope_theta, rms_eps;
     int dtype;
     unsigned flags;               /* SLIM_FORCE_FIRST | SLIM_FORCE_LAST */
+    int scoring;                  /* 0 = TokenUnits (Eq. 1-2), SLIM_POOL_AVG, SLIM_POOL_MAX (Table 3) */
 } slim_layer_shape;
 
 typedef struct slim_layer_weights {   /* device pointers, [out_features, in_features] row-major */

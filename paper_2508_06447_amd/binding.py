@@ -16,10 +16,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libslim.so")
 
 F32, BF16 = 0, 1
+POOL_AVG, POOL_MAX = 1, 2
 FORCE_FIRST, FORCE_LAST = 1, 2
 
 EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
+    "slim_score_blocks_pooled",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
@@ -36,7 +38,8 @@ class SlimError(RuntimeError):
 class LayerShape(C.Structure):
     _fields_ = [("hidden", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
                 ("ffn", C.c_int), ("block", C.c_int), ("unit", C.c_int), ("window", C.c_int),
-                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int), ("flags", C.c_uint)]
+                ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int), ("flags", C.c_uint),
+                ("scoring", C.c_int)]
 
 
 class LayerWeights(C.Structure):
@@ -64,6 +67,7 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_score_blocks_workspace_bytes.restype = sz
     lib.slim_score_blocks_workspace_bytes.argtypes = [i, i]
     lib.slim_score_blocks.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
+    lib.slim_score_blocks_pooled.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
     lib.slim_select_topk_blocks.argtypes = [vp, i, i, u, vp, vp]
     lib.slim_compact_tokens.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp, vp]
     lib.slim_prefill_attn.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp, vp]
@@ -146,6 +150,23 @@ def slim_score_blocks(q_win: torch.Tensor, k: torch.Tensor, block: int, unit: in
     _check(lib.slim_score_blocks(_dev(q_win, "q_win"), _dev(k, "k"), N, w, Hq, Hkv, d, block, unit, _dtype_code(k),
                                  _dev(scores, "scores"), _dev(workspace, "workspace"), workspace.numel(), _stream()),
            "slim_score_blocks")
+    return scores
+
+
+def slim_score_blocks_pooled(q_win: torch.Tensor, k: torch.Tensor, block: int, pooling: int,
+                             scores: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q_win[w,Hq,d], k[N,Hkv,d] -> scores[nb] float32 with one average- or max-pooled key per block (Table 3)."""
+    lib = load_library()
+    w, Hq, d = q_win.shape
+    N, Hkv, _ = k.shape
+    if scores is None:
+        scores = torch.empty(n_blocks(N, block), dtype=torch.float32, device=k.device)
+    need = lib.slim_score_blocks_workspace_bytes(Hkv, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=k.device)
+    _check(lib.slim_score_blocks_pooled(_dev(q_win, "q_win"), _dev(k, "k"), N, w, Hq, Hkv, d, block, pooling,
+                                        _dtype_code(k), _dev(scores, "scores"), _dev(workspace, "workspace"),
+                                        workspace.numel(), _stream()), "slim_score_blocks_pooled")
     return scores
 
 
@@ -236,10 +257,11 @@ def slim_swiglu_linear(a: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor
 
 
 def make_shape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window, dtype: torch.dtype,
-               rope_theta=500000.0, rms_eps=1e-5, flags=FORCE_FIRST | FORCE_LAST) -> LayerShape:
+               rope_theta=500000.0, rms_eps=1e-5, flags=FORCE_FIRST | FORCE_LAST, scoring=0) -> LayerShape:
+    """scoring: 0 = TokenUnits (Eq. 1-2), POOL_AVG, POOL_MAX (the pooled baselines of Table 3)."""
     code = BF16 if dtype == torch.bfloat16 else F32
     return LayerShape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window, rope_theta, rms_eps, code,
-                      flags)
+                      flags, scoring)
 
 
 def make_weights(w: dict) -> LayerWeights:

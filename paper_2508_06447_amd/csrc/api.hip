@@ -54,7 +54,7 @@ static int check_shape(const slim_layer_shape* s) {
     if (!s) return SLIM_INVALID_ARG;
     if (s->hidden < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 1 || s->ffn < 1 || s->block < 1 ||
         s->unit < 1 || s->window < 1 || s->unit > s->block || s->n_q_heads % s->n_kv_heads != 0 ||
-        !(s->rope_theta > 0.f) || !(s->rms_eps >= 0.f))
+        !(s->rope_theta > 0.f) || !(s->rms_eps >= 0.f) || s->scoring < 0 || s->scoring > SLIM_POOL_MAX)
         return SLIM_INVALID_ARG;
     if (!dtype_ok(s->dtype)) return SLIM_UNSUPPORTED;
     if (s->dtype == SLIM_BF16 && (s->head_dim != 128 || s->hidden % 8 != 0 || s->ffn % 8 != 0)) return SLIM_UNSUPPORTED;
@@ -96,8 +96,22 @@ int slim_score_blocks(const void* q_win, const void* k, int n_tokens, int window
     const int E = n_kv_heads * head_dim;
     if (E % (dtype == SLIM_BF16 ? 8 : 4) != 0 || E > 8192 || !aligned16(k)) return SLIM_UNSUPPORTED;
     if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
-    return launch_score(q_win, k, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit, dtype, scores,
+    return launch_score(q_win, k, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit, 0, dtype, scores,
                         (float*)workspace, (hipStream_t)stream);
+}
+
+int slim_score_blocks_pooled(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads,
+                             int n_kv_heads, int head_dim, int block, int pooling, int dtype, float* scores,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q_win || !k || !scores || !workspace || n_tokens < 1 || window < 1 || n_q_heads < 1 || n_kv_heads < 1 ||
+        head_dim < 1 || block < 1 || n_q_heads % n_kv_heads != 0 || (pooling != SLIM_POOL_AVG && pooling != SLIM_POOL_MAX))
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const int E = n_kv_heads * head_dim;
+    if (E % (dtype == SLIM_BF16 ? 8 : 4) != 0 || E > 8192 || !aligned16(k)) return SLIM_UNSUPPORTED;
+    if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
+    return launch_score(q_win, k, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, block, pooling, dtype,
+                        scores, (float*)workspace, (hipStream_t)stream);
 }
 
 int slim_select_topk_blocks(const float* scores, int n_blocks, int n_keep, unsigned force_flags, int* kept_blocks,
@@ -222,7 +236,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         SLIM_TRY(launch_linear(h_win, Hd, w->wq, nullptr, nullptr, w_eff, qd, Hd, qd, dt, q_win, st));
         SLIM_TRY(launch_rope(q_win, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, d, s->rope_theta, dt, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
-        SLIM_TRY(launch_score(q_win, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, dt, scores, qt, st));
+        SLIM_TRY(launch_score(q_win, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st));
         SLIM_TRY(launch_select(scores, p.nb, n_keep, s->flags, kept_blocks_out, st));
         // Hidden rows + positions into x_out / pos_out, keys into kc.
         SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));

@@ -81,8 +81,74 @@ __global__ void __launch_bounds__(1024) block_score_kernel(const T* __restrict__
     }
 }
 
+// Pooled scoring, the two baselines of the scoring ablation (Table 3): one representative key per block,
+// the average or the element-wise maximum of its token keys, then the same dot with qt.  One workgroup
+// of 512 threads per block: thread = (token slice s, 16-byte chunk c); slices are combined through LDS in
+// a fixed order, then the chunks' partial dots are summed over the workgroup.
+template <typename T, bool MAXPOOL>
+__global__ void __launch_bounds__(512) block_pool_score_kernel(const T* __restrict__ k, const float* __restrict__ qt,
+                                                               int N, int E /*Hkv*d*/, int block,
+                                                               float* __restrict__ scores) {
+    constexpr int V = Elem<T>::kVec;
+    extern __shared__ float smem[];                      // qt copy [E] + slice partials [512*V] + wave sums [8]
+    float* qs = smem;
+    float* part = smem + E;
+    float* wsum = part + 512 * V;
+    const int j = blockIdx.x, tid = threadIdx.x;
+    for (int e = tid; e < E; e += 512) qs[e] = qt[e];
+    const int b0 = j * block, b1 = min(b0 + block, N);
+    const int nchunk = E / V;
+    int C = 512;
+    while (C > nchunk) C >>= 1;                          // chunks handled side by side: power of two <= nchunk
+    const int S = 512 / C, c0 = tid % C, sl = tid / C;   // S token slices: slice sl takes tokens sl, sl+S, ..
+    float dot = 0.f;
+    __syncthreads();
+    for (int base = 0; base < nchunk; base += C) {
+        const int c = base + c0;
+        float p[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) p[i] = MAXPOOL ? -INFINITY : 0.f;
+        if (c < nchunk) {
+            for (int t = b0 + sl; t < b1; t += S) {
+                uint4 raw = *reinterpret_cast<const uint4*>(k + (size_t)t * E + (size_t)c * V);
+                float f[V];
+                Elem<T>::unpack(raw, f);
+#pragma unroll
+                for (int i = 0; i < V; ++i) p[i] = MAXPOOL ? fmaxf(p[i], f[i]) : p[i] + f[i];
+            }
+        }
+        if (S > 1) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) part[(sl * C + c0) * V + i] = p[i];
+            __syncthreads();
+            if (sl == 0) {
+                for (int o = 1; o < S; ++o)
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        const float x = part[(o * C + c0) * V + i];
+                        p[i] = MAXPOOL ? fmaxf(p[i], x) : p[i] + x;
+                    }
+            }
+            __syncthreads();
+        }
+        if (sl == 0 && c < nchunk) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) dot += p[i] * qs[c * V + i];
+        }
+    }
+    dot = wave_sum(dot);
+    if ((tid & 63) == 0) wsum[tid >> 6] = dot;
+    __syncthreads();
+    if (tid == 0) {
+        float m = 0.f;
+        for (int i = 0; i < 8; ++i) m += wsum[i];
+        scores[j] = MAXPOOL ? m : m / (float)(b1 - b0);
+    }
+}
+
+// pooling: 0 = TokenUnits (Eq. 1-2), 1 = average pooling, 2 = max pooling
 int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv, int d, int block, int unit,
-                 int dtype, float* scores, float* qtilde, hipStream_t st) {
+                 int pooling, int dtype, float* scores, float* qtilde, hipStream_t st) {
     const int E = Hkv * d, nb = (N + block - 1) / block;
     const int M = (block + unit - 1) / unit;
     const int waves = M < 1 ? 1 : (M > 16 ? 16 : M);
@@ -90,12 +156,28 @@ int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv
     dim3 g1((E + 63) / 64);
     if (dtype == SLIM_BF16) {
         hipLaunchKernelGGL(window_query_kernel<bf16_t>, g1, dim3(1024), 0, st, (const bf16_t*)q_win, w, Hq, Hkv, d, qtilde);
-        hipLaunchKernelGGL(block_score_kernel<bf16_t>, dim3(nb), dim3(64 * waves), smem, st, (const bf16_t*)k,
-                           qtilde, N, E, block, unit, scores);
+        const size_t smem_p = (size_t)(E + 512 * Elem<bf16_t>::kVec + 8) * sizeof(float);
+        if (pooling == 1)
+            hipLaunchKernelGGL((block_pool_score_kernel<bf16_t, false>), dim3(nb), dim3(512), smem_p, st, (const bf16_t*)k,
+                               qtilde, N, E, block, scores);
+        else if (pooling == 2)
+            hipLaunchKernelGGL((block_pool_score_kernel<bf16_t, true>), dim3(nb), dim3(512), smem_p, st, (const bf16_t*)k,
+                               qtilde, N, E, block, scores);
+        else
+            hipLaunchKernelGGL(block_score_kernel<bf16_t>, dim3(nb), dim3(64 * waves), smem, st, (const bf16_t*)k,
+                               qtilde, N, E, block, unit, scores);
     } else {
         hipLaunchKernelGGL(window_query_kernel<float>, g1, dim3(1024), 0, st, (const float*)q_win, w, Hq, Hkv, d, qtilde);
-        hipLaunchKernelGGL(block_score_kernel<float>, dim3(nb), dim3(64 * waves), smem, st, (const float*)k, qtilde,
-                           N, E, block, unit, scores);
+        const size_t smem_p = (size_t)(E + 512 * Elem<float>::kVec + 8) * sizeof(float);
+        if (pooling == 1)
+            hipLaunchKernelGGL((block_pool_score_kernel<float, false>), dim3(nb), dim3(512), smem_p, st, (const float*)k,
+                               qtilde, N, E, block, scores);
+        else if (pooling == 2)
+            hipLaunchKernelGGL((block_pool_score_kernel<float, true>), dim3(nb), dim3(512), smem_p, st, (const float*)k,
+                               qtilde, N, E, block, scores);
+        else
+            hipLaunchKernelGGL(block_score_kernel<float>, dim3(nb), dim3(64 * waves), smem, st, (const float*)k, qtilde,
+                               N, E, block, unit, scores);
     }
     return check_launch();
 }

@@ -103,7 +103,7 @@ int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float th
 int launch_linear(const void* a, int lda, const void* w0, const void* w1, const void* residual, int m,
                   int n_out, int k_in, int ldo, int dtype, void* out, hipStream_t st);
 int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv, int d, int block, int unit,
-                 int dtype, float* scores, float* qtilde, hipStream_t st);
+                 int pooling, int dtype, float* scores, float* qtilde, hipStream_t st);
 int launch_positions(const int* pos_in, int* pos_out, int n, hipStream_t st);
 int launch_select(const float* scores, int nb, int n_keep, unsigned flags, int* kept, hipStream_t st);
 int launch_compact(const void* src, const int* pos_in, const int* kept, int n_keep, int block, int N,

@@ -20,9 +20,9 @@ def f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().to(torch.float64).numpy()
 
 
-def oracle_shape(wl) -> so.LayerShape:
+def oracle_shape(wl, scoring: str = "unit") -> so.LayerShape:
     return so.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit, wl.window,
-                         wl.rope_theta, wl.rms_eps)
+                         wl.rope_theta, wl.rms_eps, scoring)
 
 
 def oracle_weights(w: dict, dtype=np.float64) -> so.LayerWeights:

@@ -20,9 +20,12 @@ def slim():
     return slim
 
 
-def run_gpu(slim, wl, x, w, pos, n_keep, flags=3):
+SCORING_CODE = {"unit": 0, "avg": 1, "max": 2}
+
+
+def run_gpu(slim, wl, x, w, pos, n_keep, flags=3, scoring="unit"):
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
-                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps, flags)
+                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps, flags, SCORING_CODE[scoring])
     wd = {k: v.cuda() for k, v in w.items()}
     res = slim.slim_pruned_layer(shape, wd, x.cuda(), None if pos is None else pos.cuda(), n_keep)
     torch.cuda.synchronize()
@@ -37,12 +40,12 @@ def sample_rows(n, block, count=48, seed=0):
     return np.array(sorted(rows))
 
 
-def check_layer(slim, wl, np_dtype, rows_count=None, label=""):
+def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit"):
     """Runs the GPU layer and the oracle on one workload; returns the numbers for the log."""
     x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
     n_keep = wl.n_keep
-    res = run_gpu(slim, wl, x, w, pos, n_keep)
-    s, ow = oracle_shape(wl), oracle_weights(w, np_dtype)
+    res = run_gpu(slim, wl, x, w, pos, n_keep, scoring=scoring)
+    s, ow = oracle_shape(wl, scoring), oracle_weights(w, np_dtype)
     xs = x.to(torch.float32).numpy().astype(np_dtype)
     sc_ref, _ = so.layer_scores(s, ow, xs, pos.numpy())
     sc_gpu = f64(res["scores"])
@@ -61,7 +64,7 @@ def check_layer(slim, wl, np_dtype, rows_count=None, label=""):
     print(f"{label}: scores max-abs {sc_err:.2e}; kept {len(kept_gpu)} blocks, {band} in the 1e-3 band, "
           f"{ndiff} differ; z max-abs {mx:.3e} mean-abs {mean:.3e} (bf16-rounding oracle: {fl_max:.3e} / "
           f"{fl_mean:.3e}); |z| max {np.abs(z_ref).max():.2f}", flush=True)
-    return dict(sc_err=sc_err, mx=mx, mean=mean, fl_max=fl_max, fl_mean=fl_mean)
+    return dict(sc_err=sc_err, sc_scale=float(np.abs(sc_ref).max()), mx=mx, mean=mean, fl_max=fl_max, fl_mean=fl_mean)
 
 
 def test_cfg1_fp32_full(slim):
@@ -88,6 +91,26 @@ def test_reduced_bf16_layer_full_output(slim, seq, block, window, keep):
     wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=seq, block=block, window=window, keep_ratio=keep, planted=seq // 100)
     r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq {seq} block {block} keep {keep}")
     assert r["sc_err"] < 2e-3
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+
+
+@pytest.mark.parametrize("scoring", ["avg", "max"])
+def test_layer_with_pooled_scoring(slim, scoring):
+    """The pooled scoring baselines of Table 3 inside the layer: fp32 workload and a reduced bf16 one."""
+    r = check_layer(slim, inputs.WORKLOADS["cfg1"], np.float64, label=f"cfg1 {scoring}-pool", scoring=scoring)
+    assert r["sc_err"] < 1e-5 and r["mx"] < F32_MAX_ABS
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=1000, keep_ratio=0.3, planted=10)
+    r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq 1000 {scoring}-pool", scoring=scoring)
+    # bf16 Key states against the float64 oracle: a maximum over 64 tokens does not average the rounding of
+    # the keys out the way a mean does.  Gate on what rounding the oracle's own h, K and window Q to bf16
+    # does to its scores (one draw of that noise, hence the factor 3).
+    sc_plain, _ = so.layer_scores(oracle_shape(wl, scoring), oracle_weights(inputs.layer_weights(wl)),
+                                  f64(inputs.hidden_states(wl)), inputs.positions(wl).numpy())
+    sc_rounded, _ = so.layer_scores(oracle_shape(wl, scoring), oracle_weights(inputs.layer_weights(wl)),
+                                    f64(inputs.hidden_states(wl)), inputs.positions(wl).numpy(), rounding="bf16")
+    sc_floor = float(np.abs(sc_rounded - sc_plain).max())
+    print(f"score scale {r['sc_scale']:.3f}, bf16-rounding oracle moves the scores by {sc_floor:.2e}", flush=True)
+    assert r["sc_err"] <= max(2e-3, 3.0 * sc_floor)
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
 
 

@@ -108,6 +108,28 @@ def test_scores_match_oracle(slim, N, block, unit, w, Hq, Hkv, d, dtype):
     np.testing.assert_allclose(f64(got), want, atol=2e-5 * max(scale, 1.0), rtol=1e-4)
 
 
+@pytest.mark.parametrize("pooling", ["avg", "max"])
+@pytest.mark.parametrize("N,block,w,Hq,Hkv,d,dtype", [
+    (4096, 64, 64, 32, 8, 128, torch.bfloat16),
+    (1000, 64, 4, 32, 8, 128, torch.bfloat16),           # ragged last block
+    (777, 128, 9, 64, 64, 128, torch.bfloat16),          # Hkv*d = 8192: one token slice, chunks in two rounds
+    (300, 50, 7, 8, 8, 32, torch.bfloat16),
+    (130, 32, 3, 4, 1, 16, torch.float32),
+    (700, 100, 5, 6, 3, 8, torch.float32),               # 6 chunks: not a power of two
+    (5, 8, 2, 2, 2, 64, torch.float32),                  # one short block, fewer tokens than slices
+])
+def test_pooled_scores_match_oracle(slim, pooling, N, block, w, Hq, Hkv, d, dtype):
+    print(f"pooled score {pooling} N={N} B={block} w={w} H={Hq}/{Hkv} d={d} {dtype}", flush=True)
+    q, k = rand((w, Hq, d), dtype, seed=N), rand((N, Hkv, d), dtype, seed=N + 1)
+    got = slim.slim_score_blocks_pooled(dev(q), dev(k), block, slim.POOL_AVG if pooling == "avg" else slim.POOL_MAX)
+    want = so.block_scores_pooled(f64(q), f64(k), block, pooling)
+    scale = np.abs(want).max()
+    np.testing.assert_allclose(f64(got), want, atol=2e-5 * max(scale, 1.0), rtol=1e-4)
+    if pooling == "avg":                                 # the single-TokenUnit special case of Eq. (1)-(2)
+        same = slim.slim_score_blocks(dev(q), dev(k), block, block)
+        np.testing.assert_allclose(f64(got), f64(same), atol=2e-5 * max(scale, 1.0), rtol=1e-4)
+
+
 def test_scores_skewed_stage_input_and_selection(slim):
     wl = inputs.scaled(inputs.WORKLOADS["cfg3"], seq=4096)
     q, k = inputs.stage_qk(wl, skew=True)
