@@ -243,6 +243,8 @@ class LayerShape:
     rope_theta: float = 500000.0
     rms_eps: float = 1e-5
     scoring: str = "unit"          # "unit": Eq. (1)-(2); "avg" / "max": the pooled baselines of Table 3
+    placement: str = "before"      # where a pruning layer drops the blocks: "before" its attention (the
+                                   # graded path) or "after" it, as Section 4.1 words it
 
 
 @dataclass
@@ -308,9 +310,32 @@ def layer_after_selection(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np
     return z, posk
 
 
+def layer_after_selection_literal(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
+                                  kept_blocks: np.ndarray, rows: np.ndarray | None = None, rounding=None):
+    """The placement Section 4.1 describes: the block decision is taken right after Attention, so the
+    pruning layer's own attention still sees every incoming token, and the hidden states of the pruned
+    blocks are dropped for everything that follows (this layer's output projection and FFN included).
+    Queries are only needed for the kept tokens; their keys and values are those of all N tokens.
+    `rows` indexes the compacted sequence as in layer_after_selection.  Returns (z, pos')."""
+    N = x.shape[0]
+    T = kept_token_index(kept_blocks, s.block, N)
+    Tr = T if rows is None else T[rows]
+    h = _rnd(rmsnorm(x, w.g_attn, s.rms_eps), rounding)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding)
+    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, pos, s.rope_theta, False, rounding)
+    q = project_heads(h[Tr], w.wq, s.n_q_heads, s.head_dim, pos[Tr], s.rope_theta, True, rounding)
+    o = _rnd(causal_gqa_attention(q, k, v, rows=Tr, rounding=rounding), rounding)
+    y = _rnd(x[Tr] + linear(o.reshape(len(Tr), -1), w.wo), rounding)
+    r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
+    act = _rnd(silu(linear(r, w.w_gate)) * linear(r, w.w_up), rounding)
+    z = _rnd(y + linear(act, w.w_down), rounding)
+    return z, pos[T]
+
+
 def pruned_layer(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray, n_keep: int,
                  force_first: bool = True, force_last: bool = True, rounding=None):
-    """One Slim layer: score -> select -> compact -> attention -> FFN on the kept tokens.
+    """One Slim layer: score -> select -> compact -> attention -> FFN on the kept tokens (placement
+    "before"), or score -> select -> attention over all tokens -> compact -> FFN (placement "after").
     n_keep >= number of blocks makes it a Preserve layer (nothing dropped).
     Returns dict(z, pos, kept_blocks, scores)."""
     nb = n_blocks(x.shape[0], s.block)
@@ -320,7 +345,8 @@ def pruned_layer(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
     else:
         scores, _ = layer_scores(s, w, x, pos, rounding)
         kept = select_blocks(scores, n_keep, force_first, force_last)
-    z, posk = layer_after_selection(s, w, x, pos, kept, rounding=rounding)
+    after = layer_after_selection_literal if s.placement == "after" else layer_after_selection
+    z, posk = after(s, w, x, pos, kept, rounding=rounding)
     return dict(z=z, pos=posk, kept_blocks=kept, scores=scores)
 
 

@@ -492,6 +492,36 @@ def test_bf16_rounding_mode_stays_close_and_on_grid():
     assert 0 < np.abs(a["z"] - b["z"]).max() < 0.2
 
 
+def test_placement_after_attention_is_the_unpruned_layer_at_the_kept_tokens():
+    """Section 4.1's wording: the pruning layer's own attention still sees every token, the blocks are
+    dropped afterwards.  Every later step is per token, so the result must be the rows of the unpruned
+    layer (pinned above against the library composition) at the kept tokens, with the same kept set and
+    scores as the graded placement."""
+    import dataclasses
+    s, w, x, pos = small_layer(seed=11, n=61)             # ragged last block
+    pos = pos + 100
+    lit = dataclasses.replace(s, placement="after")
+    a = so.pruned_layer(lit, w, x, pos, n_keep=4)
+    b = so.pruned_layer(s, w, x, pos, n_keep=4)
+    np.testing.assert_array_equal(a["kept_blocks"], b["kept_blocks"])
+    np.testing.assert_array_equal(a["scores"], b["scores"])
+    np.testing.assert_array_equal(a["pos"], b["pos"])
+    T = so.kept_token_index(a["kept_blocks"], s.block, 61)
+    full = torch_layer_unpruned(s, w, x, pos)
+    np.testing.assert_allclose(a["z"], full[T], rtol=1e-9, atol=1e-11)
+    # it differs from the graded placement exactly where a kept token follows a dropped block
+    first_gap = next(j for j in range(len(a["kept_blocks"])) if a["kept_blocks"][j] != j)
+    lead = first_gap * s.block
+    np.testing.assert_allclose(a["z"][:lead], b["z"][:lead], rtol=1e-9, atol=1e-11)
+    assert np.abs(a["z"][lead:] - b["z"][lead:]).max() > 1e-3
+    # keep-all: both placements are the unpruned layer; sampled rows equal rows of the full result
+    nb = so.n_blocks(61, s.block)
+    np.testing.assert_array_equal(so.pruned_layer(lit, w, x, pos, nb)["z"], so.pruned_layer(s, w, x, pos, nb)["z"])
+    rows = np.array([0, 7, 8, 20, len(T) - 1])
+    z_rows, _ = so.layer_after_selection_literal(lit, w, x, pos, a["kept_blocks"], rows=rows)
+    np.testing.assert_allclose(z_rows, a["z"][rows], rtol=1e-12, atol=1e-13)
+
+
 def test_schedule_runs_pruning_layers_on_incoming_blocks():
     s, w, x, pos = small_layer(seed=10, n=64)
     ws = [w, small_layer(seed=11)[1], small_layer(seed=12)[1]]
