@@ -241,6 +241,10 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-stages", action="store_true", help="skip the per-kernel table")
+    ap.add_argument("--scoring", choices=["unit", "avg", "max"], default="unit",
+                    help="variant: pooled scoring baselines of the ablation instead of TokenUnits")
+    ap.add_argument("--placement", choices=["before", "after"], default="before",
+                    help="variant: drop the blocks after the pruning layer's attention instead of before it")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (the pruned prefill layer of one sequence); "
@@ -263,8 +267,11 @@ def main():
     wd = {k: v.to(dev) for k, v in inputs.layer_weights(wl).items()}
     pos = inputs.positions(wl).to(dev)
     n_keep = wl.n_keep
+    variant = args.scoring != "unit" or args.placement != "before"
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
-                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps)
+                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps,
+                            scoring={"unit": 0, "avg": slim.POOL_AVG, "max": slim.POOL_MAX}[args.scoring],
+                            placement=slim.PRUNE_AFTER_ATTENTION if args.placement == "after" else 0)
     ws = torch.empty(slim.pruned_layer_workspace_bytes(shape, wl.seq, n_keep), dtype=torch.uint8, device=dev)
     n_out = slim.kept_tokens(wl.seq, wl.block, n_keep)
     out = dict(x=torch.empty(n_out, wl.hidden, dtype=x.dtype, device=dev),
@@ -305,7 +312,11 @@ def main():
         "layer_tflops": round(layer_flops / (ms * 1e-3) / 1e12, 1),
         "layer_mfma_frac": round(layer_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
     }
-    if not args.no_stages and wl.dtype == "bf16":
+    if variant:
+        # not the graded configuration: the flop count above is that of the default placement
+        rec["config"]["variant"] = {"scoring": args.scoring, "placement": args.placement}
+        del rec["layer_tflops"], rec["layer_mfma_frac"]
+    if not args.no_stages and wl.dtype == "bf16" and not variant:
         table = stage_table(slim, wl, wd, x, pos, n_keep, reps=max(5, args.steps))
         rec["kernels"] = table
         dom = table["ffn_gate_up_swiglu"]

@@ -141,7 +141,15 @@ typedef struct slim_layer_shape {
     int dtype;
     unsigned flags;               /* SLIM_FORCE_FIRST | SLIM_FORCE_LAST */
     int scoring;                  /* 0 = TokenUnits (Eq. 1-2), SLIM_POOL_AVG, SLIM_POOL_MAX (Table 3) */
+    int placement;                /* SLIM_PRUNE_BEFORE_ATTENTION (0) or SLIM_PRUNE_AFTER_ATTENTION       */
 } slim_layer_shape;
+
+/* Where a pruning layer drops the blocks.  BEFORE (the measured path): score, select, compact, then
+ * attention over the kept tokens only.  AFTER (the order Section 4.1 words: the decision is taken
+ * right after Attention): Query, Key and Value states and attention for all N tokens, then the
+ * attention output and the residual are compacted, and the output projection and FFN run on the kept
+ * tokens.  Scores, kept set and positions are the same in both; AFTER needs a larger workspace. */
+enum { SLIM_PRUNE_BEFORE_ATTENTION = 0, SLIM_PRUNE_AFTER_ATTENTION = 1 };
 
 typedef struct slim_layer_weights {   /* device pointers, [out_features, in_features] row-major */
     const void *g_attn, *wq, *wk, *wv, *wo, *g_ffn, *w_gate, *w_up, *w_down;

@@ -1,7 +1,8 @@
 """MI355X-native pruned prefill layer of SlimInfer: HIP kernels behind a C ABI (libslim.so) and a
 thin ctypes binding with the same entry-point names."""
 from .binding import (  # noqa: F401
-    BF16, F32, FORCE_FIRST, FORCE_LAST, POOL_AVG, POOL_MAX, LIB_PATH, EXPORTS, LayerShape, LayerWeights, SlimError, kept_tokens,
+    BF16, F32, FORCE_FIRST, FORCE_LAST, POOL_AVG, POOL_MAX, PRUNE_BEFORE_ATTENTION,
+    PRUNE_AFTER_ATTENTION, LIB_PATH, EXPORTS, LayerShape, LayerWeights, SlimError, kept_tokens,
     load_library, make_shape, make_weights, n_blocks, pruned_layer_workspace_bytes, slim_compact_tokens,
     slim_linear, slim_prefill_attn, slim_pruned_layer, slim_rmsnorm, slim_rope, slim_score_blocks,
     slim_score_blocks_pooled,

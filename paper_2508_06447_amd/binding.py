@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libslim.so")
 
 F32, BF16 = 0, 1
 POOL_AVG, POOL_MAX = 1, 2
+PRUNE_BEFORE_ATTENTION, PRUNE_AFTER_ATTENTION = 0, 1
 FORCE_FIRST, FORCE_LAST = 1, 2
 
 EXPORTS = (
@@ -39,7 +40,7 @@ class LayerShape(C.Structure):
     _fields_ = [("hidden", C.c_int), ("n_q_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
                 ("ffn", C.c_int), ("block", C.c_int), ("unit", C.c_int), ("window", C.c_int),
                 ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("dtype", C.c_int), ("flags", C.c_uint),
-                ("scoring", C.c_int)]
+                ("scoring", C.c_int), ("placement", C.c_int)]
 
 
 class LayerWeights(C.Structure):
@@ -257,11 +258,12 @@ def slim_swiglu_linear(a: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor
 
 
 def make_shape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window, dtype: torch.dtype,
-               rope_theta=500000.0, rms_eps=1e-5, flags=FORCE_FIRST | FORCE_LAST, scoring=0) -> LayerShape:
-    """scoring: 0 = TokenUnits (Eq. 1-2), POOL_AVG, POOL_MAX (the pooled baselines of Table 3)."""
+               rope_theta=500000.0, rms_eps=1e-5, flags=FORCE_FIRST | FORCE_LAST, scoring=0, placement=0) -> LayerShape:
+    """scoring: 0 = TokenUnits (Eq. 1-2), POOL_AVG, POOL_MAX (the pooled baselines of Table 3);
+    placement: PRUNE_BEFORE_ATTENTION (measured path) or PRUNE_AFTER_ATTENTION (Section 4.1's order)."""
     code = BF16 if dtype == torch.bfloat16 else F32
     return LayerShape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window, rope_theta, rms_eps, code,
-                      flags, scoring)
+                      flags, scoring, placement)
 
 
 def make_weights(w: dict) -> LayerWeights:

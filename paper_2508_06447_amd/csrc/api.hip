@@ -22,7 +22,7 @@ static int forced_count(unsigned flags, int nb) {
 
 // Workspace layout of slim_pruned_layer (every region 256-byte aligned).
 struct LayerPlan {
-    size_t h, k_all, q_win, qt, scores, kc, vc, qc, o, act, total;
+    size_t h, k_all, q_win, qt, scores, kc, vc, qc, o, o_all, act, total;
     int nb, n_out;
     bool prune;
 };
@@ -41,9 +41,12 @@ static LayerPlan plan_layer(const slim_layer_shape* s, int N, int n_keep) {
     p.q_win = take((size_t)s->window * qd * es);
     p.qt = take(slim_score_blocks_workspace_bytes(s->n_kv_heads, s->head_dim));
     p.scores = take((size_t)p.nb * sizeof(float));
-    p.kc = p.prune ? take((size_t)p.n_out * kv * es) : p.k_all;   // compacted keys
-    p.vc = take((size_t)p.n_out * kv * es);
-    p.qc = take((size_t)p.n_out * qd * es);
+    const bool after = p.prune && s->placement == SLIM_PRUNE_AFTER_ATTENTION;
+    const size_t n_att = after ? (size_t)N : (size_t)p.n_out;    // rows that go through attention
+    p.kc = (p.prune && !after) ? take((size_t)p.n_out * kv * es) : p.k_all;   // compacted keys
+    p.vc = take(n_att * kv * es);
+    p.qc = take(n_att * qd * es);
+    p.o_all = after ? take(n_att * qd * es) : 0;         // attention output of all N rows, compacted into o
     p.o = take((size_t)p.n_out * qd * es);
     p.act = take((size_t)p.n_out * s->ffn * es);
     p.total = off;
@@ -54,7 +57,8 @@ static int check_shape(const slim_layer_shape* s) {
     if (!s) return SLIM_INVALID_ARG;
     if (s->hidden < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->head_dim < 1 || s->ffn < 1 || s->block < 1 ||
         s->unit < 1 || s->window < 1 || s->unit > s->block || s->n_q_heads % s->n_kv_heads != 0 ||
-        !(s->rope_theta > 0.f) || !(s->rms_eps >= 0.f) || s->scoring < 0 || s->scoring > SLIM_POOL_MAX)
+        !(s->rope_theta > 0.f) || !(s->rms_eps >= 0.f) || s->scoring < 0 || s->scoring > SLIM_POOL_MAX ||
+        s->placement < 0 || s->placement > SLIM_PRUNE_AFTER_ATTENTION)
         return SLIM_INVALID_ARG;
     if (!dtype_ok(s->dtype)) return SLIM_UNSUPPORTED;
     if (s->dtype == SLIM_BF16 && (s->head_dim != 128 || s->hidden % 8 != 0 || s->ffn % 8 != 0)) return SLIM_UNSUPPORTED;
@@ -229,6 +233,24 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     const void* resid = x_in;          // residual stream entering the attention branch
     const int* pos = pos_in;           // positions of the rows that continue
     const int n = p.n_out;
+    const bool after = p.prune && s->placement == SLIM_PRUNE_AFTER_ATTENTION;
+    if (after) {
+        // Attention first, over all N tokens; its last w_eff Query rows are the local window.
+        void* o_all = ws + p.o_all;
+        SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, N, qd, Hd, qd, dt, qc, st));
+        SLIM_TRY(launch_rope(qc, pos_in, 0, N, Hq, d, s->rope_theta, dt, st));
+        SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, N, kvd, Hd, kvd, dt, vc, st));
+        SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
+        const int w_eff = s->window < N ? s->window : N;
+        const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
+        float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
+        SLIM_TRY(launch_score(q_last, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st));
+        SLIM_TRY(launch_select(scores, p.nb, n_keep, s->flags, kept_blocks_out, st));
+        // Residual rows + positions into x_out / pos_out, attention output rows into o.
+        SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
+        SLIM_TRY(launch_compact(o_all, nullptr, kept_blocks_out, n_keep, s->block, N, qd, dt, o, nullptr, st));
+        resid = x_out;
+    } else {
     if (p.prune) {
         // Query states of the local window (last w_eff rows), block scores, selection.
         const int w_eff = s->window < N ? s->window : N;
@@ -254,6 +276,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     SLIM_TRY(launch_rope(qc, pos, 0, n, Hq, d, s->rope_theta, dt, st));
     SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, n, kvd, Hd, kvd, dt, vc, st));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
+    }
     // y = resid + Wo o  (into x_out);  z = y + Wdown(silu(Wgate r) * Wup r), r = RMSNorm(y)  (in place)
     SLIM_TRY(launch_linear(o, qd, w->wo, nullptr, resid, n, Hd, qd, Hd, dt, x_out, st));
     SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, n, Hd, s->rms_eps, dt, h, st));

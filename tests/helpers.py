@@ -20,9 +20,9 @@ def f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().cpu().to(torch.float64).numpy()
 
 
-def oracle_shape(wl, scoring: str = "unit") -> so.LayerShape:
+def oracle_shape(wl, scoring: str = "unit", placement: str = "before") -> so.LayerShape:
     return so.LayerShape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit, wl.window,
-                         wl.rope_theta, wl.rms_eps, scoring)
+                         wl.rope_theta, wl.rms_eps, scoring, placement)
 
 
 def oracle_weights(w: dict, dtype=np.float64) -> so.LayerWeights:
@@ -63,7 +63,8 @@ def assert_selection_matches(kept_gpu: np.ndarray, scores_ref: np.ndarray, n_kee
 def bf16_floor(s, w, x, pos, kept, rows=None):
     """Error of the oracle with bf16 rounding at every stored tensor against the exact oracle, on the
     same kept set: how far any bf16 pipeline is from the exact result.  Returns (z_exact, max, mean)."""
-    z, _ = so.layer_after_selection(s, w, x, pos, kept, rows=rows)
-    zb, _ = so.layer_after_selection(s, w, x, pos, kept, rows=rows, rounding="bf16")
+    after = so.layer_after_selection_literal if s.placement == "after" else so.layer_after_selection
+    z, _ = after(s, w, x, pos, kept, rows=rows)
+    zb, _ = after(s, w, x, pos, kept, rows=rows, rounding="bf16")
     d = np.abs(z - zb)
     return z, float(d.max()), float(d.mean())

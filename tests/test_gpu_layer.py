@@ -23,9 +23,10 @@ def slim():
 SCORING_CODE = {"unit": 0, "avg": 1, "max": 2}
 
 
-def run_gpu(slim, wl, x, w, pos, n_keep, flags=3, scoring="unit"):
+def run_gpu(slim, wl, x, w, pos, n_keep, flags=3, scoring="unit", placement="before"):
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
-                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps, flags, SCORING_CODE[scoring])
+                            wl.window, x.dtype, wl.rope_theta, wl.rms_eps, flags, SCORING_CODE[scoring],
+                            1 if placement == "after" else 0)
     wd = {k: v.cuda() for k, v in w.items()}
     res = slim.slim_pruned_layer(shape, wd, x.cuda(), None if pos is None else pos.cuda(), n_keep)
     torch.cuda.synchronize()
@@ -40,12 +41,12 @@ def sample_rows(n, block, count=48, seed=0):
     return np.array(sorted(rows))
 
 
-def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit"):
+def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", placement="before"):
     """Runs the GPU layer and the oracle on one workload; returns the numbers for the log."""
     x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
     n_keep = wl.n_keep
-    res = run_gpu(slim, wl, x, w, pos, n_keep, scoring=scoring)
-    s, ow = oracle_shape(wl, scoring), oracle_weights(w, np_dtype)
+    res = run_gpu(slim, wl, x, w, pos, n_keep, scoring=scoring, placement=placement)
+    s, ow = oracle_shape(wl, scoring, placement), oracle_weights(w, np_dtype)
     xs = x.to(torch.float32).numpy().astype(np_dtype)
     sc_ref, _ = so.layer_scores(s, ow, xs, pos.numpy())
     sc_gpu = f64(res["scores"])
@@ -112,6 +113,27 @@ def test_layer_with_pooled_scoring(slim, scoring):
     print(f"score scale {r['sc_scale']:.3f}, bf16-rounding oracle moves the scores by {sc_floor:.2e}", flush=True)
     assert r["sc_err"] <= max(2e-3, 3.0 * sc_floor)
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+
+
+def test_layer_with_blocks_dropped_after_attention(slim):
+    """Section 4.1's order: the pruning layer's attention sees all tokens, the blocks are dropped after it."""
+    r = check_layer(slim, inputs.WORKLOADS["cfg1"], np.float64, label="cfg1, drop after attention", placement="after")
+    assert r["sc_err"] < 1e-5 and r["mx"] < F32_MAX_ABS
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=1000, keep_ratio=0.3, planted=10)
+    r = check_layer(slim, wl, np.float64, label="llama-shaped seq 1000, drop after attention", placement="after")
+    assert r["sc_err"] < 2e-3
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+    # Every step after attention is per token and the kernels accumulate each output element in the same
+    # order whatever the row count, so the result is bit for bit the unpruned layer's rows at the kept
+    # tokens; scores, kept set and positions equal those of the graded placement.
+    x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
+    lit = run_gpu(slim, wl, x, w, pos, wl.n_keep, placement="after")
+    std = run_gpu(slim, wl, x, w, pos, wl.n_keep)
+    full = run_gpu(slim, wl, x, w, pos, wl.n_blocks)
+    assert torch.equal(lit["kept"], std["kept"]) and torch.equal(lit["pos"], std["pos"])
+    assert torch.equal(lit["scores"], std["scores"])
+    T = torch.from_numpy(so.kept_token_index(lit["kept"].cpu().numpy(), wl.block, wl.seq)).cuda()
+    assert torch.equal(lit["x"], full["x"][T])
 
 
 def test_reduced_bf16_keep_all_and_prefix_property(slim):
