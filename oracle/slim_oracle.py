@@ -259,14 +259,24 @@ class LayerWeights:
     w_gate: np.ndarray
     w_up: np.ndarray
     w_down: np.ndarray
+    # Biases of the Q/K/V projections (length = out_features), None for a model without them.  The
+    # paper's second model family (Qwen2.5) has them; its LLaMA family does not.
+    bq: np.ndarray | None = None
+    bk: np.ndarray | None = None
+    bv: np.ndarray | None = None
 
     def astype(self, dtype):
-        return LayerWeights(*[getattr(self, f).astype(dtype) for f in self.__dataclass_fields__])
+        return LayerWeights(*[None if getattr(self, f) is None else getattr(self, f).astype(dtype)
+                              for f in self.__dataclass_fields__])
 
 
-def project_heads(h, W, n_heads, head_dim, pos, theta, rope: bool, rounding=None):
-    """A projection reshaped to heads, with RoPE at the tokens' own positions when asked."""
-    y = linear(h, W).reshape(h.shape[0], n_heads, head_dim)
+def project_heads(h, W, n_heads, head_dim, pos, theta, rope: bool, rounding=None, bias=None):
+    """A projection (plus its bias, if the model has one) reshaped to heads, with RoPE at the tokens'
+    own positions when asked."""
+    y = linear(h, W)
+    if bias is not None:
+        y = y + bias
+    y = y.reshape(h.shape[0], n_heads, head_dim)
     if rope:
         cos, sin = rope_cos_sin(pos, head_dim, theta, h.dtype)
         y = apply_rope(y, cos, sin)
@@ -278,10 +288,10 @@ def layer_scores(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
     last min(window, N) tokens (both post-RoPE), then the block scores.  Returns (scores, k)."""
     N = x.shape[0]
     h = _rnd(rmsnorm(x, w.g_attn, s.rms_eps), rounding)
-    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding, w.bk)
     w_eff = min(s.window, N)
     q_win = project_heads(h[N - w_eff:], w.wq, s.n_q_heads, s.head_dim, pos[N - w_eff:],
-                          s.rope_theta, True, rounding)
+                          s.rope_theta, True, rounding, w.bq)
     if s.scoring != "unit":
         return block_scores_pooled(q_win, k, s.block, s.scoring), k
     return block_scores(q_win, k, s.block, s.unit), k
@@ -297,11 +307,11 @@ def layer_after_selection(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np
     xk, posk = compact_tokens(x, pos, kept_blocks, s.block)
     n = xk.shape[0]
     h = _rnd(rmsnorm(xk, w.g_attn, s.rms_eps), rounding)
-    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, posk, s.rope_theta, True, rounding)
-    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, posk, s.rope_theta, False, rounding)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, posk, s.rope_theta, True, rounding, w.bk)
+    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, posk, s.rope_theta, False, rounding, w.bv)
     if rows is None:
         rows = np.arange(n)
-    q = project_heads(h[rows], w.wq, s.n_q_heads, s.head_dim, posk[rows], s.rope_theta, True, rounding)
+    q = project_heads(h[rows], w.wq, s.n_q_heads, s.head_dim, posk[rows], s.rope_theta, True, rounding, w.bq)
     o = _rnd(causal_gqa_attention(q, k, v, rows=rows, rounding=rounding), rounding)
     y = _rnd(xk[rows] + linear(o.reshape(len(rows), -1), w.wo), rounding)
     r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
@@ -321,9 +331,9 @@ def layer_after_selection_literal(s: LayerShape, w: LayerWeights, x: np.ndarray,
     T = kept_token_index(kept_blocks, s.block, N)
     Tr = T if rows is None else T[rows]
     h = _rnd(rmsnorm(x, w.g_attn, s.rms_eps), rounding)
-    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding)
-    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, pos, s.rope_theta, False, rounding)
-    q = project_heads(h[Tr], w.wq, s.n_q_heads, s.head_dim, pos[Tr], s.rope_theta, True, rounding)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding, w.bk)
+    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, pos, s.rope_theta, False, rounding, w.bv)
+    q = project_heads(h[Tr], w.wq, s.n_q_heads, s.head_dim, pos[Tr], s.rope_theta, True, rounding, w.bq)
     o = _rnd(causal_gqa_attention(q, k, v, rows=Tr, rounding=rounding), rounding)
     y = _rnd(x[Tr] + linear(o.reshape(len(Tr), -1), w.wo), rounding)
     r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)

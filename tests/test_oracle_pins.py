@@ -37,12 +37,12 @@ def brute_attention(q, k, v, scale):
 def torch_layer_unpruned(s, w, x, pos):
     """The unpruned layer composed from torch CPU library ops in float64 (HF-style RoPE)."""
     xt = torch.from_numpy(x)
-    W = {f: torch.from_numpy(getattr(w, f)) for f in w.__dataclass_fields__}
+    W = {f: None if getattr(w, f) is None else torch.from_numpy(getattr(w, f)) for f in w.__dataclass_fields__}
     n, d = x.shape[0], s.head_dim
     h = F.rms_norm(xt, (s.hidden,), W["g_attn"], s.rms_eps)
-    q = F.linear(h, W["wq"]).view(n, s.n_q_heads, d).transpose(0, 1)
-    k = F.linear(h, W["wk"]).view(n, s.n_kv_heads, d).transpose(0, 1)
-    v = F.linear(h, W["wv"]).view(n, s.n_kv_heads, d).transpose(0, 1)
+    q = F.linear(h, W["wq"], W["bq"]).view(n, s.n_q_heads, d).transpose(0, 1)
+    k = F.linear(h, W["wk"], W["bk"]).view(n, s.n_kv_heads, d).transpose(0, 1)
+    v = F.linear(h, W["wv"], W["bv"]).view(n, s.n_kv_heads, d).transpose(0, 1)
     inv = 1.0 / (s.rope_theta ** (torch.arange(0, d, 2, dtype=torch.float64) / d))
     ang = torch.from_numpy(pos.astype(np.float64))[:, None] * inv[None, :]
     emb = torch.cat([ang, ang], dim=-1)
@@ -520,6 +520,30 @@ def test_placement_after_attention_is_the_unpruned_layer_at_the_kept_tokens():
     rows = np.array([0, 7, 8, 20, len(T) - 1])
     z_rows, _ = so.layer_after_selection_literal(lit, w, x, pos, a["kept_blocks"], rows=rows)
     np.testing.assert_allclose(z_rows, a["z"][rows], rtol=1e-12, atol=1e-13)
+
+
+def test_qkv_biases_enter_before_rope_and_match_the_library_layer():
+    """Second model family of the paper (Qwen2.5): Q/K/V projections carry a bias.  Pinned against the torch
+    composition (F.linear with bias, HF-style RoPE afterwards); zero biases change nothing; the window
+    query and the Key states that the scores read include the bias."""
+    import dataclasses
+    s, w, x, pos = small_layer(seed=21, n=40, Hq=6, Hkv=2)          # 3 query heads per kv head
+    r = np.random.default_rng(5)
+    wb = dataclasses.replace(w, bq=r.standard_normal(6 * 8), bk=r.standard_normal(2 * 8), bv=r.standard_normal(2 * 8))
+    full = so.pruned_layer(s, wb, x, pos, n_keep=10**6)
+    np.testing.assert_allclose(full["z"], torch_layer_unpruned(s, wb, x, pos), rtol=1e-9, atol=1e-11)
+    assert np.abs(full["z"] - so.pruned_layer(s, w, x, pos, n_keep=10**6)["z"]).max() > 1e-2
+    wz = dataclasses.replace(w, bq=np.zeros(48), bk=np.zeros(16), bv=np.zeros(16))
+    np.testing.assert_array_equal(so.pruned_layer(s, wz, x, pos, 3)["z"], so.pruned_layer(s, w, x, pos, 3)["z"])
+    # scores: keys and window queries with bias, by hand from the definitions
+    h = so.rmsnorm(x, wb.g_attn, s.rms_eps)
+    cos, sin = so.rope_cos_sin(pos, s.head_dim, s.rope_theta, np.float64)
+    k = so.apply_rope((h @ wb.wk.T + wb.bk).reshape(40, 2, 8), cos, sin)
+    q = so.apply_rope((h @ wb.wq.T + wb.bq).reshape(40, 6, 8), cos, sin)[-s.window:]
+    np.testing.assert_allclose(so.layer_scores(s, wb, x, pos)[0], so.block_scores(q, k, s.block, s.unit), rtol=1e-12)
+    # pruned layer with biases equals the library layer on the gathered rows when the kept set is a prefix
+    res = so.layer_after_selection(s, wb, x, pos, np.array([0, 1, 2], dtype=np.int32))[0]
+    np.testing.assert_allclose(res, torch_layer_unpruned(s, wb, x[:24], pos[:24]), rtol=1e-9, atol=1e-11)
 
 
 def test_schedule_runs_pruning_layers_on_incoming_blocks():
