@@ -212,9 +212,12 @@ def bench_model(args, slim, inputs, wl, dev):
         "metric": "pruned-prefill tokens/s", "value": round(wl.seq / (ms * 1e-3), 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: 32-layer LLaMA-3.1-8B-shaped prefill, seq {wl.seq}, pruning at layers "
-                               f"8/16/24 to 50/25/12.5 % of the incoming blocks (block {wl.block}, window {wl.window})",
-                   "n_tokens": wl.seq, "n_keep_blocks": [k for k in keeps if k], "tokens_after_layer": per_layer[::8],
+        "config": {"workload": f"{wl.name}: {wl.n_layers}-layer {wl.family}-shaped prefill, seq {wl.seq}, pruning at "
+                               f"layers {'/'.join(str(l) for l in sorted(wl.schedule))} to "
+                               f"{'/'.join(f'{100 * wl.schedule[l]:g}' for l in sorted(wl.schedule))} % of the incoming "
+                               f"blocks (block {wl.block}, window {wl.window})",
+                   "n_tokens": wl.seq, "n_keep_blocks": [k for k in keeps if k],
+                   "tokens_after_pruning_layers": [wl.seq] + [per_layer[l] for l in sorted(wl.schedule)],
                    "seed": wl.seed},
         "prefill_ms": round(ms, 3), "model_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
         "model_mfma_frac": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -304,7 +307,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": f"{wl.name}: LLaMA-3.1-8B-shaped pruned prefill layer, seq {wl.seq}, block {wl.block}, "
+        "config": {"workload": f"{wl.name}: {wl.family}-shaped pruned prefill layer, seq {wl.seq}, block {wl.block}, "
                                f"window {wl.window}, keep ratio {wl.keep_ratio}",
                    "n_tokens": wl.seq, "n_keep_blocks": n_keep, "n_kept_tokens": n_out, "hidden": Hd,
                    "heads": f"{Hq}q/{Hkv}kv x {d}", "ffn": F, "seed": wl.seed},

@@ -127,6 +127,10 @@ int slim_rope(void* x, const int* pos, int n, int n_heads, int head_dim, float t
  * Row strides in elements: lda for a, ldo for out and residual.  bf16 needs k_in % 8 == 0. */
 int slim_linear(const void* a, int lda, const void* w, const void* residual, int m, int n_out,
                 int k_in, int ldo, int dtype, void* out, void* stream);
+/* out[m, n_out] = a . w^T + bias[n_out] (the Q/K/V projections of models that carry a bias; the sum is
+ * formed in float and rounded once).  bias: n_out elements of dtype, 16-byte aligned. */
+int slim_linear_bias(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in,
+                     int ldo, int dtype, void* out, void* stream);
 /* out[m, n_out] = silu(a . w_gate^T) * (a . w_up^T), both weights [n_out, k_in]. */
 int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m,
                        int n_out, int k_in, int ldo, int dtype, void* out, void* stream);
@@ -153,6 +157,8 @@ enum { SLIM_PRUNE_BEFORE_ATTENTION = 0, SLIM_PRUNE_AFTER_ATTENTION = 1 };
 
 typedef struct slim_layer_weights {   /* device pointers, [out_features, in_features] row-major */
     const void *g_attn, *wq, *wk, *wv, *wo, *g_ffn, *w_gate, *w_up, *w_down;
+    const void *bq, *bk, *bv;         /* biases of the Q/K/V projections ([out_features], 16-byte aligned)
+                                         or NULL: the paper's LLaMA models have none, its Qwen2.5 models do */
 } slim_layer_weights;
 
 /* Tokens left after keeping n_keep of the blocks of an n_tokens sequence (last block among them). */

@@ -4,7 +4,7 @@ from .binding import (  # noqa: F401
     BF16, F32, FORCE_FIRST, FORCE_LAST, POOL_AVG, POOL_MAX, PRUNE_BEFORE_ATTENTION,
     PRUNE_AFTER_ATTENTION, LIB_PATH, EXPORTS, LayerShape, LayerWeights, SlimError, kept_tokens,
     load_library, make_shape, make_weights, n_blocks, pruned_layer_workspace_bytes, slim_compact_tokens,
-    slim_linear, slim_prefill_attn, slim_pruned_layer, slim_rmsnorm, slim_rope, slim_score_blocks,
+    slim_linear, slim_linear_bias, slim_prefill_attn, slim_pruned_layer, slim_rmsnorm, slim_rope, slim_score_blocks,
     slim_score_blocks_pooled,
     slim_select_topk_blocks, slim_swiglu_linear, slim_prefill_model, schedule_keep_counts, probe_mfma, probe_copy,
 )

@@ -24,7 +24,7 @@ EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
     "slim_score_blocks_pooled",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
-    "slim_linear", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
+    "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
     "slim_probe_mfma_flops", "slim_probe_mfma", "slim_probe_copy",
 )
@@ -44,7 +44,8 @@ class LayerShape(C.Structure):
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_ffn", "w_gate", "w_up", "w_down")]
+    _fields_ = [(n, C.c_void_p) for n in ("g_attn", "wq", "wk", "wv", "wo", "g_ffn", "w_gate", "w_up", "w_down",
+                                          "bq", "bk", "bv")]
 
 
 _lib = None
@@ -75,6 +76,7 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_rmsnorm.argtypes = [vp, vp, i, i, f, i, vp, vp]
     lib.slim_rope.argtypes = [vp, vp, i, i, i, f, i, vp]
     lib.slim_linear.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp]
+    lib.slim_linear_bias.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp]
     lib.slim_swiglu_linear.argtypes = [vp, i, vp, vp, i, i, i, i, i, vp, vp]
     lib.slim_kept_tokens.argtypes = [i, i, i]
     lib.slim_pruned_layer_workspace_bytes.restype = sz
@@ -245,6 +247,18 @@ def slim_linear(a: torch.Tensor, w: torch.Tensor, residual: torch.Tensor | None 
     return out
 
 
+def slim_linear_bias(a: torch.Tensor, w: torch.Tensor, bias: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """a[m,k] . w[n,k]^T + bias[n]."""
+    lib = load_library()
+    m, k = a.shape
+    n = w.shape[0]
+    if out is None:
+        out = torch.empty((m, n), dtype=a.dtype, device=a.device)
+    _check(lib.slim_linear_bias(_dev(a, "a"), k, _dev(w, "w"), _dev(bias, "bias"), m, n, k, n, _dtype_code(a),
+                                _dev(out, "out"), _stream()), "slim_linear_bias")
+    return out
+
+
 def slim_swiglu_linear(a: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor,
                        out: torch.Tensor | None = None) -> torch.Tensor:
     lib = load_library()
@@ -267,8 +281,9 @@ def make_shape(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block, unit, window
 
 
 def make_weights(w: dict) -> LayerWeights:
-    """`w` maps the field names of slim_layer_weights to GPU tensors (kept alive by the caller)."""
-    return LayerWeights(*[_dev(w[n], n) for n, _ in LayerWeights._fields_])
+    """`w` maps the field names of slim_layer_weights to GPU tensors (kept alive by the caller); the
+    biases bq/bk/bv may be absent (NULL)."""
+    return LayerWeights(*[_dev(w.get(n), n) for n, _ in LayerWeights._fields_])
 
 
 def pruned_layer_workspace_bytes(shape: LayerShape, n_tokens: int, n_keep: int) -> int:

@@ -172,7 +172,16 @@ int slim_linear(const void* a, int lda, const void* w, const void* residual, int
                 int dtype, void* out, void* stream) {
     int rc = linear_checks(a, lda, w, m, n_out, k_in, ldo, dtype, out);
     if (rc) return rc;
-    return launch_linear(a, lda, w, nullptr, residual, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
+    return launch_linear(a, lda, w, nullptr, residual, nullptr, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
+}
+
+int slim_linear_bias(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in, int ldo,
+                     int dtype, void* out, void* stream) {
+    int rc = linear_checks(a, lda, w, m, n_out, k_in, ldo, dtype, out);
+    if (rc) return rc;
+    if (!bias) return SLIM_INVALID_ARG;
+    if (!aligned16(bias)) return SLIM_UNSUPPORTED;
+    return launch_linear(a, lda, w, nullptr, nullptr, bias, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
 }
 
 int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m, int n_out, int k_in,
@@ -181,7 +190,7 @@ int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w
     int rc = linear_checks(a, lda, w_gate, m, n_out, k_in, ldo, dtype, out);
     if (rc) return rc;
     if (dtype == SLIM_BF16 && !aligned16(w_up)) return SLIM_UNSUPPORTED;
-    return launch_linear(a, lda, w_gate, w_up, nullptr, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
+    return launch_linear(a, lda, w_gate, w_up, nullptr, nullptr, m, n_out, k_in, ldo, dtype, out, (hipStream_t)stream);
 }
 
 int slim_kept_tokens(int n_tokens, int block, int n_keep) {
@@ -214,6 +223,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     }
     if (workspace_bytes < p.total) return SLIM_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255u) || !aligned16(x_in) || !aligned16(x_out)) return SLIM_UNSUPPORTED;
+    if ((w->bq && !aligned16(w->bq)) || (w->bk && !aligned16(w->bk)) || (w->bv && !aligned16(w->bv))) return SLIM_UNSUPPORTED;
 
     hipStream_t st = (hipStream_t)stream;
     unsigned char* ws = (unsigned char*)workspace;
@@ -227,7 +237,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
 
     // Key states of every incoming token (both paths need them).
     SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
-    SLIM_TRY(launch_linear(h, Hd, w->wk, nullptr, nullptr, N, kvd, Hd, kvd, dt, k_all, st));
+    SLIM_TRY(launch_linear(h, Hd, w->wk, nullptr, nullptr, w->bk, N, kvd, Hd, kvd, dt, k_all, st));
     SLIM_TRY(launch_rope(k_all, pos_in, 0, N, Hkv, d, s->rope_theta, dt, st));
 
     const void* resid = x_in;          // residual stream entering the attention branch
@@ -237,9 +247,9 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
-        SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, N, qd, Hd, qd, dt, qc, st));
+        SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, w->bq, N, qd, Hd, qd, dt, qc, st));
         SLIM_TRY(launch_rope(qc, pos_in, 0, N, Hq, d, s->rope_theta, dt, st));
-        SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, N, kvd, Hd, kvd, dt, vc, st));
+        SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, w->bv, N, kvd, Hd, kvd, dt, vc, st));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
         const int w_eff = s->window < N ? s->window : N;
         const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
@@ -255,7 +265,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         // Query states of the local window (last w_eff rows), block scores, selection.
         const int w_eff = s->window < N ? s->window : N;
         const unsigned char* h_win = (const unsigned char*)h + (size_t)(N - w_eff) * Hd * es;
-        SLIM_TRY(launch_linear(h_win, Hd, w->wq, nullptr, nullptr, w_eff, qd, Hd, qd, dt, q_win, st));
+        SLIM_TRY(launch_linear(h_win, Hd, w->wq, nullptr, nullptr, w->bq, w_eff, qd, Hd, qd, dt, q_win, st));
         SLIM_TRY(launch_rope(q_win, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, d, s->rope_theta, dt, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(launch_score(q_win, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st));
@@ -272,16 +282,16 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     }
 
     // Q, V of the rows that continue; RoPE on Q at the original positions.
-    SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, n, qd, Hd, qd, dt, qc, st));
+    SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, w->bq, n, qd, Hd, qd, dt, qc, st));
     SLIM_TRY(launch_rope(qc, pos, 0, n, Hq, d, s->rope_theta, dt, st));
-    SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, n, kvd, Hd, kvd, dt, vc, st));
+    SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, w->bv, n, kvd, Hd, kvd, dt, vc, st));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
     }
     // y = resid + Wo o  (into x_out);  z = y + Wdown(silu(Wgate r) * Wup r), r = RMSNorm(y)  (in place)
-    SLIM_TRY(launch_linear(o, qd, w->wo, nullptr, resid, n, Hd, qd, Hd, dt, x_out, st));
+    SLIM_TRY(launch_linear(o, qd, w->wo, nullptr, resid, nullptr, n, Hd, qd, Hd, dt, x_out, st));
     SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, n, Hd, s->rms_eps, dt, h, st));
-    SLIM_TRY(launch_linear(h, Hd, w->w_gate, w->w_up, nullptr, n, s->ffn, Hd, s->ffn, dt, act, st));
-    SLIM_TRY(launch_linear(act, s->ffn, w->w_down, nullptr, x_out, n, Hd, s->ffn, Hd, dt, x_out, st));
+    SLIM_TRY(launch_linear(h, Hd, w->w_gate, w->w_up, nullptr, nullptr, n, s->ffn, Hd, s->ffn, dt, act, st));
+    SLIM_TRY(launch_linear(act, s->ffn, w->w_down, nullptr, x_out, nullptr, n, Hd, s->ffn, Hd, dt, x_out, st));
 #undef SLIM_TRY
     return SLIM_OK;
 }

@@ -1,6 +1,7 @@
 // Dense projections of the layer ("QKV Generation", output projection and FFN of Fig. 2):
 //   out[m, n] = sum_k a[m, k] * w[n, k]            (both operands contiguous along k)
-// with three epilogues: plain, + residual, and SwiGLU (two weight matrices, silu(gate) * up).
+// with four epilogues: plain, + bias[n] (Q/K/V projections of models that have one), + residual, and
+// SwiGLU (two weight matrices, silu(gate) * up).
 //
 // bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The weight tile is the MFMA "A" operand
 // and the activation tile the "B" operand, so a lane ends up with 4 consecutive output features of
@@ -22,7 +23,7 @@
 
 namespace slim {
 
-enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_BIAS = 3 };   // EPI_BIAS: R is a bias vector [N]
 
 constexpr int BK = 64;                                   // k-depth of an LDS tile (8 chunks of 16 bytes)
 
@@ -60,8 +61,8 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 :
                 }
                 bf16_t* dst = C + (size_t)m * ldo + n;
                 if (vec_ok) {
-                    if (EPI == EPI_RESIDUAL) {
-                        const uint2 r = *reinterpret_cast<const uint2*>(R + (size_t)m * ldo + n);
+                    if (EPI == EPI_RESIDUAL || EPI == EPI_BIAS) {
+                        const uint2 r = *reinterpret_cast<const uint2*>(EPI == EPI_BIAS ? R + n : R + (size_t)m * ldo + n);
                         o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
                     }
                     *reinterpret_cast<uint2*>(dst) = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
@@ -71,6 +72,7 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 :
                         if (n + e < N) {
                             float val = o[e];
                             if (EPI == EPI_RESIDUAL) val += bf16_to_f32(R[(size_t)m * ldo + n + e]);
+                            if (EPI == EPI_BIAS) val += bf16_to_f32(R[n + e]);
                             dst[e] = f32_to_bf16(val);
                         }
                     }
@@ -129,6 +131,13 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
                 if (EPI == EPI_RESIDUAL) {
                     const uint2 r = *cell;
                     o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
+                }
+                if (EPI == EPI_BIAS) {                    // 4 consecutive features of the bias vector (N % 8 == 0 here)
+                    const int n = nw + i * 32 + 8 * vg + 4 * hh;
+                    if (n < N) {
+                        const uint2 r = *reinterpret_cast<const uint2*>(R + n);
+                        o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
+                    }
                 }
                 *cell = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
             }
@@ -288,7 +297,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
     __builtin_amdgcn_s_waitcnt(0x0070);
     workgroup_barrier();
     const bool wide = (N % 8 == 0) && (ldo % 8 == 0) && (((uintptr_t)C & 15) == 0) &&
-                      (EPI != EPI_RESIDUAL || ((uintptr_t)R & 15) == 0);
+                      (EPI != EPI_RESIDUAL || ((uintptr_t)R & 15) == 0) && (EPI != EPI_BIAS || ((uintptr_t)R & 7) == 0);
     if (wide)
         store_tile_via_lds<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
                                         lds + wave * (TA * 32 * TW * 64));
@@ -602,18 +611,21 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
             float o = acc[0][i][j];
             if (EPI == EPI_SWIGLU) { const float g = o; o = g / (1.0f + expf(-g)) * acc[NW - 1][i][j]; }
             if (EPI == EPI_RESIDUAL) o += R[(size_t)m * ldo + n];
+            if (EPI == EPI_BIAS) o += R[n];
             C[(size_t)m * ldo + n] = o;
         }
     }
 }
 
-int launch_linear(const void* a, int lda, const void* w0, const void* w1, const void* residual, int m,
-                  int n_out, int k_in, int ldo, int dtype, void* out, hipStream_t st) {
+// At most one of w1 (SwiGLU), residual and bias is set.
+int launch_linear(const void* a, int lda, const void* w0, const void* w1, const void* residual, const void* bias,
+                  int m, int n_out, int k_in, int ldo, int dtype, void* out, hipStream_t st) {
     if (dtype == SLIM_F32) {
         dim3 grid((n_out + 63) / 64, (m + 63) / 64);
 #define SLIM_F32_GEMM(E) hipLaunchKernelGGL(gemm_f32_kernel<E>, grid, dim3(256), 0, st, (const float*)a, lda, \
-        (const float*)w0, (const float*)w1, (const float*)residual, (float*)out, ldo, m, n_out, k_in)
-        if (w1) SLIM_F32_GEMM(EPI_SWIGLU); else if (residual) SLIM_F32_GEMM(EPI_RESIDUAL); else SLIM_F32_GEMM(EPI_PLAIN);
+        (const float*)w0, (const float*)w1, (const float*)(bias ? bias : residual), (float*)out, ldo, m, n_out, k_in)
+        if (w1) SLIM_F32_GEMM(EPI_SWIGLU); else if (residual) SLIM_F32_GEMM(EPI_RESIDUAL);
+        else if (bias) SLIM_F32_GEMM(EPI_BIAS); else SLIM_F32_GEMM(EPI_PLAIN);
 #undef SLIM_F32_GEMM
         return check_launch();
     }
@@ -621,6 +633,7 @@ int launch_linear(const void* a, int lda, const void* w0, const void* w1, const 
     bf16_t* C = (bf16_t*)out;
     if (w1) return dispatch_bf16<EPI_SWIGLU>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
     if (residual) return dispatch_bf16<EPI_RESIDUAL>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
+    if (bias) return dispatch_bf16<EPI_BIAS>(A, lda, W0, W1, (const bf16_t*)bias, C, ldo, m, n_out, k_in, st);
     return dispatch_bf16<EPI_PLAIN>(A, lda, W0, W1, R, C, ldo, m, n_out, k_in, st);
 }
 

@@ -100,7 +100,7 @@ inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 // Internal launchers (each validates nothing: the C entry points do).
 int launch_rmsnorm(const void* x, const void* gain, int n, int hidden, float eps, int dtype, void* out, hipStream_t st);
 int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float theta, int dtype, hipStream_t st);
-int launch_linear(const void* a, int lda, const void* w0, const void* w1, const void* residual, int m,
+int launch_linear(const void* a, int lda, const void* w0, const void* w1, const void* residual, const void* bias, int m,
                   int n_out, int k_in, int ldo, int dtype, void* out, hipStream_t st);
 int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv, int d, int block, int unit,
                  int pooling, int dtype, float* scores, float* qtilde, hipStream_t st);

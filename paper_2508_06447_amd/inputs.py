@@ -8,7 +8,8 @@ bf16 workloads, rounded to bfloat16 once, so every consumer reads the same bits.
 Draw order per workload (fixed): hidden states x, planted-token indices or block ranks, then for a
 layer Wq, Wk, Wv, Wo, Wgate, Wup, Wdown, each from its own generator seeded with (seed, 1000 + layer,
 index), so a process never has to hold all layers on the host and matrices can be drawn in parallel.
-Weights are N(0, 0.02^2); RMSNorm gains are exactly 1; there are no biases.
+Weights are N(0, 0.02^2); RMSNorm gains are exactly 1.  The LLaMA-shaped workloads have no biases; the
+Qwen2.5-shaped ones add bq, bk, bv ~ N(0, 0.5^2) from generators (seed, 1000 + layer, 7..9).
 """
 from __future__ import annotations
 
@@ -40,6 +41,8 @@ class Workload:
     schedule: dict = field(default_factory=dict)   # layer -> keep ratio of incoming blocks
     rope_theta: float = 500000.0
     rms_eps: float = 1e-5
+    qkv_bias: bool = False
+    family: str = "LLaMA-3.1-8B"
 
     @property
     def n_blocks(self) -> int:
@@ -68,6 +71,8 @@ def kept_tokens(n_tokens: int, block: int, n_keep: int) -> int:
 
 
 _LLAMA = dict(hidden=4096, n_q_heads=32, n_kv_heads=8, head_dim=128, ffn=14336, unit=8)
+_QWEN = dict(hidden=3584, n_q_heads=28, n_kv_heads=4, head_dim=128, ffn=18944, unit=8, rope_theta=1000000.0,
+             rms_eps=1e-6, qkv_bias=True, family="Qwen2.5-7B")
 
 WORKLOADS = {
     "cfg1": Workload("cfg1", "fp32", 512, 256, 4, 2, 64, 688, 16, 8, 32, 0.5, 0, "planted", planted=8),
@@ -79,6 +84,13 @@ WORKLOADS = {
                      x_kind="planted", planted=655, **_LLAMA),
     "cfg5": Workload("cfg5", "bf16", 32768, block=64, window=64, keep_ratio=1.0, seed=4,
                      x_kind="normal", n_layers=32, schedule={8: 0.5, 16: 0.25, 24: 0.125}, **_LLAMA),
+    # Second model family of the paper's evaluation (Section 5.1: Qwen2.5-7B-Instruct, pruning at layers
+    # 9/18/26 down to 12k/6k/4k tokens).  The layer shapes are not in the paper; they are the public model
+    # card's (28 layers, hidden 3584, 28 query / 4 kv heads of 128, FFN 18944, Q/K/V bias, theta 1e6).
+    "cfg6": Workload("cfg6", "bf16", 32768, block=64, window=64, keep_ratio=0.375, seed=5,
+                     x_kind="zipf", **_QWEN),
+    "cfg7": Workload("cfg7", "bf16", 32768, block=64, window=64, keep_ratio=1.0, seed=6,
+                     x_kind="normal", n_layers=28, schedule={9: 0.375, 18: 0.5, 26: 0.66666}, **_QWEN),
 }
 
 
@@ -132,6 +144,10 @@ def layer_weights(wl: Workload, layer: int = 0, pool=None) -> dict:
     ones = np.ones(wl.hidden, dtype=np.float32)
     out["g_attn"] = _store(ones, wl.dtype)
     out["g_ffn"] = _store(ones.copy(), wl.dtype)
+    if wl.qkv_bias:
+        for i, name in enumerate(("q", "k", "v")):
+            rng = np.random.default_rng([wl.seed, 1000 + layer, 7 + i])
+            out["b" + name] = _store(0.5 * rng.standard_normal(out["w" + name].shape[0], dtype=np.float32), wl.dtype)
     return out
 
 

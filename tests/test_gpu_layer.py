@@ -155,10 +155,18 @@ def test_reduced_bf16_keep_all_and_prefix_property(slim):
     assert lead >= 1 and np.abs(a - b).max() <= 2 * MAX_ABS
 
 
-@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4"])
+def test_reduced_qwen_shaped_layer_full_output(slim):
+    """Second model family (28 query / 4 kv heads, hidden 3584, FFN 18944, Q/K/V biases, theta 1e6)."""
+    wl = inputs.scaled(inputs.WORKLOADS["cfg6"], seq=1000, x_kind="planted", planted=10)
+    r = check_layer(slim, wl, np.float64, label="qwen-shaped seq 1000 keep 0.375")
+    assert r["sc_err"] < 4e-3                             # biases of size 0.5 make the scores larger
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg6"])
 def test_full_size_workloads_sampled_rows(slim, name):
     wl = inputs.WORKLOADS[name]
     print(f"{name}: N={wl.seq} nb={wl.n_blocks} n_keep={wl.n_keep} n'={wl.n_kept_tokens}", flush=True)
     r = check_layer(slim, wl, np.float32, rows_count=40, label=name)
-    assert r["sc_err"] < 2e-3
+    assert r["sc_err"] < (4e-3 if wl.qkv_bias else 2e-3)  # biases of size 0.5 make the scores larger
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])

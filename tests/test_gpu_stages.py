@@ -195,6 +195,19 @@ def test_linear_all_epilogues(slim, m, n, k, dtype):
                                atol=rel * np.abs(sw).max())
 
 
+@pytest.mark.parametrize("m,n,k,dtype", [
+    (1300, 3584, 256, torch.bfloat16), (64, 512, 3584, torch.bfloat16), (300, 520, 192, torch.bfloat16),
+    (700, 260, 200, torch.bfloat16), (130, 70, 50, torch.float32),
+])
+def test_linear_with_bias(slim, m, n, k, dtype):
+    print(f"linear+bias m={m} n={n} k={k} {dtype}", flush=True)
+    a, w, b = rand((m, k), dtype, 1), rand((n, k), dtype, 2, 0.05), rand((n,), dtype, 3, 2.0)
+    want = f64(a) @ f64(w).T + f64(b)
+    rel = 2.0 ** -8 if dtype == torch.bfloat16 else 1e-5
+    np.testing.assert_allclose(f64(slim.slim_linear_bias(dev(a), dev(w), dev(b))), want, rtol=rel,
+                               atol=rel * np.abs(want).max())
+
+
 # ------------------------------------------------------------------------------------------ attention
 @pytest.mark.parametrize("n,Hq,Hkv,d,dtype", [
     (1, 4, 1, 128, torch.bfloat16), (37, 4, 2, 128, torch.bfloat16), (128, 8, 8, 128, torch.bfloat16),
