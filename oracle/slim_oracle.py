@@ -144,6 +144,50 @@ def block_scores_pooled(q_win: np.ndarray, k: np.ndarray, block: int, pooling: s
     return out
 
 
+def all_unit_keys(k: np.ndarray, block: int, unit: int) -> np.ndarray:
+    """Eq. (1) for every block of the prompt: k[N, Hkv, d] -> k_rep[nb, M, Hkv, d], M = ceil(block/unit).
+    Units that do not exist (short last block) are NaN.  This is what a decode step can keep on the GPU
+    when the Key states themselves have been moved to CPU memory."""
+    N = k.shape[0]
+    nb, M = n_blocks(N, block), (block + unit - 1) // unit
+    out = np.full((nb, M) + k.shape[1:], np.nan, dtype=k.dtype)
+    for j in range(nb):
+        reps = unit_keys(k[j * block:min((j + 1) * block, N)], unit)
+        out[j, :reps.shape[0]] = reps
+    return out
+
+
+def block_scores_from_unit_keys(q_win: np.ndarray, k_rep: np.ndarray) -> np.ndarray:
+    """Eq. (2) on stored representative keys.  q_win[w, Hq, d] are the Query states of the local window:
+    the end of the prompt during prefill, the most recently decoded tokens during decoding (Section 4.2)."""
+    Hq, Hkv = q_win.shape[1], k_rep.shape[2]
+    q_l = window_query(q_win)
+    out = np.empty(k_rep.shape[0], dtype=k_rep.dtype)
+    for j in range(k_rep.shape[0]):
+        present = ~np.isnan(k_rep[j, :, 0, 0])
+        k_rep_h = np.repeat(k_rep[j, present], Hq // Hkv, axis=1)
+        out[j] = np.einsum("hd,mhd->mh", q_l, k_rep_h).mean(axis=1).max()
+    return out
+
+
+def kv_swap_step(active_prev, candidate, memory, gamma: float):
+    """Algorithm 1 (overlap-aware KV swapping), one inference step.  Sets of block indices:
+    active_prev = B_active(t-1) (KV on the GPU), candidate = B_candidate(t), memory = B_Memory (KV present
+    in the CPU pool).  Returns dict(active, offload, load, memory, overlap, swapped).  The CPU pool keeps
+    what was once offloaded (prompt KV never changes), so B_Memory only grows; a block to load must be
+    in it."""
+    active_prev, candidate, memory = set(active_prev), set(candidate), set(memory)
+    overlap = len(candidate & active_prev) / len(candidate)
+    if overlap < gamma:
+        active = set(candidate)
+        offload = (active_prev - active) - memory
+        load = active - active_prev
+        assert load <= memory, "a block to prefetch must be in the CPU pool"
+        return dict(active=active, offload=offload, load=load, memory=memory | offload, overlap=overlap,
+                    swapped=True)
+    return dict(active=active_prev, offload=set(), load=set(), memory=memory, overlap=overlap, swapped=False)
+
+
 def select_blocks(scores: np.ndarray, n_keep: int, force_first: bool = True,
                   force_last: bool = True) -> np.ndarray:
     """Forced blocks (first = attention sink; last) are always kept; the remaining

@@ -412,6 +412,52 @@ def test_attention_is_stable_for_large_logits():
     np.testing.assert_allclose(out[4, 0], v[2, 0], rtol=1e-12)     # the huge logit takes everything
 
 
+# ----------------------------------------------------------------------------- decode-time pieces
+def test_scores_from_stored_unit_keys_equal_eq_1_2_incl_ragged():
+    for (N, block, unit, w, Hq, Hkv, d) in [(24, 8, 4, 3, 4, 2, 4), (29, 8, 3, 5, 6, 2, 2), (10, 4, 1, 4, 2, 1, 6)]:
+        q, k = rng.standard_normal((w, Hq, d)), rng.standard_normal((N, Hkv, d))
+        kr = so.all_unit_keys(k, block, unit)
+        assert kr.shape == (so.n_blocks(N, block), -(-block // unit), Hkv, d)
+        np.testing.assert_allclose(so.block_scores_from_unit_keys(q, kr), brute_scores(q, k, block, unit),
+                                   rtol=1e-11, atol=1e-12)
+        # the stored means are the plain means of the units' tokens; missing units are marked
+        np.testing.assert_allclose(kr[0, 0], k[:unit].mean(0), rtol=1e-13)
+        last_len = N - (kr.shape[0] - 1) * block
+        assert np.isnan(kr[-1, -(-last_len // unit):]).all() and not np.isnan(kr[-1, 0]).any()
+
+
+def test_kv_swap_hand_worked_and_invariants():
+    # worked by hand from Algorithm 1: 8 blocks, 4 active
+    r = so.kv_swap_step({0, 1, 2, 3}, {0, 1, 4, 5}, {4, 5, 6, 7}, 0.9)
+    assert r["overlap"] == 0.5 and r["swapped"]
+    assert r["active"] == {0, 1, 4, 5} and r["offload"] == {2, 3} and r["load"] == {4, 5}
+    assert r["memory"] == {2, 3, 4, 5, 6, 7}
+    # block 2 already has a copy in the pool: its GPU memory is released without a transfer
+    r = so.kv_swap_step({0, 1, 2, 3}, {0, 1, 4, 5}, {2, 4, 5, 6, 7}, 0.9)
+    assert r["offload"] == {3} and r["load"] == {4, 5} and r["memory"] == {2, 3, 4, 5, 6, 7}
+    # 3 of 4 candidates resident: 0.75 >= gamma 0.75 keeps the old set (the test is strict "<"), 0.76 swaps
+    r = so.kv_swap_step({0, 1, 2, 3}, {0, 1, 2, 7}, {4, 5, 6, 7}, 0.75)
+    assert not r["swapped"] and r["active"] == {0, 1, 2, 3} and not r["offload"] and not r["load"]
+    assert so.kv_swap_step({0, 1, 2, 3}, {0, 1, 2, 7}, {4, 5, 6, 7}, 0.76)["swapped"]
+    # gamma = 0 never swaps; gamma > 1 always takes the candidate set, with nothing to move when it is the old set
+    assert not so.kv_swap_step({0, 1}, {2, 3}, {2, 3}, 0.0)["swapped"]
+    r = so.kv_swap_step({0, 1}, {0, 1}, {5}, 1.5)
+    assert r["swapped"] and r["overlap"] == 1.0 and not r["offload"] and not r["load"]
+    # random walks: set sizes stay fixed, every block is on the GPU or in the pool, traffic only on swaps
+    g = np.random.default_rng(3)
+    nb, na = 40, 10
+    active, memory = set(range(na)), set(range(na, nb))
+    for _ in range(200):
+        cand = {0} | set(g.choice(np.arange(1, nb), na - 1, replace=False).tolist())
+        prev = set(active)
+        r = so.kv_swap_step(active, cand, memory, 0.6)
+        active, memory = r["active"], r["memory"]
+        assert len(active) == na and active in (cand, prev)
+        assert set(range(nb)) == active | memory
+        assert r["load"].isdisjoint(prev) and r["offload"] <= prev - active and len(r["load"]) == len(prev - active)
+        assert r["swapped"] == (len(cand & prev) / na < 0.6)
+
+
 # ----------------------------------------------------------------------------- the layer
 def test_unpruned_layer_equals_torch_library_composition():
     s, w, x, pos = small_layer(seed=3)
