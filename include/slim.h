@@ -77,6 +77,25 @@ int slim_score_blocks_pooled(const void* q_win, const void* k, int n_tokens, int
                              float* scores, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * The same scores from stored representative keys -- Section 4.2 in its decode-time form: during
+ * decoding the window is the most recently decoded tokens, and the Key states of inactive prompt blocks
+ * may live in CPU memory (Section 4.3), so Eq. (1) is evaluated once and kept on the GPU.
+ *   slim_unit_keys:  k[N, Hkv, d] (dtype) -> k_rep[nb, M, Hkv*d] float, M = ceil(block/unit); entry (j, m)
+ *                    is Eq. (1) for TokenUnit m of block j, averaged over the tokens it really has; units
+ *                    past the end of the prompt are written as zeros and never read.
+ *   slim_score_blocks_from_unit_keys:  Eq. (2) on k_rep with the window q_win[window, Hq, d] (dtype);
+ *                    scores[nb] float.  Equal to slim_score_blocks on the same keys up to the order of
+ *                    the float additions.  Workspace as slim_score_blocks.
+ * k_rep is caller-owned, 16-byte aligned, nb*M*Hkv*d floats.  Errors as slim_score_blocks.
+ */
+int slim_unit_keys(const void* k, int n_tokens, int n_kv_heads, int head_dim, int block, int unit, int dtype,
+                   float* k_rep, void* stream);
+int slim_score_blocks_from_unit_keys(const void* q_win, const float* k_rep, int n_tokens, int window,
+                                     int n_q_heads, int n_kv_heads, int head_dim, int block, int unit,
+                                     int dtype, float* scores, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Block selection -- last paragraph of Section 4.2: the first block (attention sink) is always
  * kept; here the last block can be forced as well.  The remaining n_keep - #forced slots go to the
  * other blocks by (score descending, block index ascending).  n_keep counts the forced blocks.
@@ -205,6 +224,42 @@ int slim_prefill_model(const slim_layer_shape* s, const slim_layer_weights* laye
                        const int* n_keep, const void* x_in, const int* pos_in, int n_tokens, void* x_out,
                        int* pos_out, int* kept_blocks_out, void* workspace, size_t workspace_bytes,
                        void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Overlap-aware KV swapping -- Algorithm 1, Section 4.3, one inference step, decided and carried out on
+ * the GPU without a host round trip:
+ *   overlap = |candidate ∩ active| / |candidate|   (double; a repeated candidate counts once)
+ *   overlap <  gamma: active <- candidate;  B_offload = (active_prev \ active) \ B_Memory is copied from its
+ *                     GPU slots to the CPU pool and joins B_Memory;  B_load = active \ active_prev is copied
+ *                     from the CPU pool into the slots that became free
+ *   overlap >= gamma: nothing changes.
+ * A block is "active" iff slot_of_block[b] >= 0.  The call enqueues two kernels on `stream` (pass the
+ * stream the transfer should overlap compute from; the paper uses a second stream for it).
+ *   candidate      [n_candidates] int32, device (for instance the output of slim_select_topk_blocks)
+ *   slot_of_block  [n_blocks] int32, device, in/out: GPU slot of an active block, -1 otherwise
+ *   block_of_slot  [n_slots]  int32, device, in/out: inverse map, -1 = free slot
+ *   in_memory      [n_blocks] int32, device, in/out: 1 when the CPU pool holds the block (B_Memory); only
+ *                  ever set, never cleared (the prompt's KV does not change once written)
+ *   gpu_pool       [n_slots, block_bytes]  device
+ *   host_pool      [n_blocks, block_bytes] HOST memory that is pinned and device-mapped (hipHostMalloc),
+ *                  passed by its device-visible address; block b lives at offset b*block_bytes
+ *   block_bytes    payload of one block (its K and V rows, of one layer or of every layer that shares the
+ *                  block set); multiple of 16; both pools 16-byte aligned
+ *   info           [8] int32, device, out: {|candidate|, |candidate ∩ active|, swapped (0/1), blocks copied
+ *                  out, blocks copied in, error bits, slots released, 0}.  Error bits: 1 = a candidate outside
+ *                  [0, n_blocks); 2 = a block to load is not in the CPU pool; 4 = more candidates than slots;
+ *                  8 = the two maps are not inverse to each other.  With a non-zero error nothing is moved
+ *                  and the maps are left as they were.
+ *   workspace      >= slim_kv_swap_workspace_bytes(n_blocks, n_slots) bytes, device, 256-byte aligned
+ * Which free slot an arriving block takes is the library's choice (ascending blocks into ascending
+ * freed slots); callers read it from slot_of_block.  The host sees offloaded bytes after it has synchronised
+ * with `stream`.  Errors (host side, nothing enqueued): INVALID_ARG (null, sizes < 1, gamma not in [0, 1]
+ * or NaN), UNSUPPORTED (alignment, block_bytes % 16), WORKSPACE_TOO_SMALL.
+ */
+size_t slim_kv_swap_workspace_bytes(int n_blocks, int n_slots);
+int slim_kv_swap(const int* candidate, int n_candidates, int n_blocks, double gamma, int* slot_of_block,
+                 int* block_of_slot, int* in_memory, int n_slots, void* gpu_pool, void* host_pool,
+                 size_t block_bytes, int* info, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Measurement probes (no counterpart in the paper): measured ceilings to set beside the nameplate

@@ -22,7 +22,8 @@ FORCE_FIRST, FORCE_LAST = 1, 2
 
 EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
-    "slim_score_blocks_pooled",
+    "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
+    "slim_kv_swap_workspace_bytes", "slim_kv_swap",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
@@ -70,6 +71,11 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_score_blocks_workspace_bytes.argtypes = [i, i]
     lib.slim_score_blocks.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
     lib.slim_score_blocks_pooled.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
+    lib.slim_unit_keys.argtypes = [vp, i, i, i, i, i, i, vp, vp]
+    lib.slim_score_blocks_from_unit_keys.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
+    lib.slim_kv_swap_workspace_bytes.restype = sz
+    lib.slim_kv_swap_workspace_bytes.argtypes = [i, i]
+    lib.slim_kv_swap.argtypes = [vp, i, i, C.c_double, vp, vp, vp, i, vp, vp, sz, vp, vp, sz, vp]
     lib.slim_select_topk_blocks.argtypes = [vp, i, i, u, vp, vp]
     lib.slim_compact_tokens.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp, vp]
     lib.slim_prefill_attn.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp, vp]
@@ -171,6 +177,74 @@ def slim_score_blocks_pooled(q_win: torch.Tensor, k: torch.Tensor, block: int, p
                                         _dtype_code(k), _dev(scores, "scores"), _dev(workspace, "workspace"),
                                         workspace.numel(), _stream()), "slim_score_blocks_pooled")
     return scores
+
+
+def slim_unit_keys(k: torch.Tensor, block: int, unit: int, k_rep: torch.Tensor | None = None) -> torch.Tensor:
+    """k[N,Hkv,d] -> k_rep[nb, M, Hkv*d] float32 (Eq. 1 for every TokenUnit; missing units are zeros)."""
+    lib = load_library()
+    N, Hkv, d = k.shape
+    M = (block + unit - 1) // unit
+    if k_rep is None:
+        k_rep = torch.empty(n_blocks(N, block), M, Hkv * d, dtype=torch.float32, device=k.device)
+    _check(lib.slim_unit_keys(_dev(k, "k"), N, Hkv, d, block, unit, _dtype_code(k), _dev(k_rep, "k_rep"), _stream()),
+           "slim_unit_keys")
+    return k_rep
+
+
+def slim_score_blocks_from_unit_keys(q_win: torch.Tensor, k_rep: torch.Tensor, n_tokens: int, n_kv_heads: int,
+                                     block: int, unit: int, scores: torch.Tensor | None = None,
+                                     workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q_win[w,Hq,d], k_rep[nb,M,Hkv*d] float32 -> scores[nb] float32 (Eq. 2 on stored unit keys)."""
+    lib = load_library()
+    w, Hq, d = q_win.shape
+    if scores is None:
+        scores = torch.empty(n_blocks(n_tokens, block), dtype=torch.float32, device=k_rep.device)
+    need = lib.slim_score_blocks_workspace_bytes(n_kv_heads, d)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=k_rep.device)
+    _check(lib.slim_score_blocks_from_unit_keys(_dev(q_win, "q_win"), _dev(k_rep, "k_rep"), n_tokens, w, Hq, n_kv_heads,
+                                                d, block, unit, _dtype_code(q_win), _dev(scores, "scores"),
+                                                _dev(workspace, "workspace"), workspace.numel(), _stream()),
+           "slim_score_blocks_from_unit_keys")
+    return scores
+
+
+def _pinned(t: torch.Tensor, name: str):
+    """Address of a pinned host tensor; under HIP's unified addressing the GPU reads it at the same address."""
+    if t.is_cuda or not t.is_pinned():
+        raise ValueError(f"{name} must be a pinned host tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def slim_kv_swap(candidate: torch.Tensor, gamma: float, slot_of_block: torch.Tensor, block_of_slot: torch.Tensor,
+                 in_memory: torch.Tensor, gpu_pool: torch.Tensor, host_pool: torch.Tensor,
+                 info: torch.Tensor | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """One step of Algorithm 1 on device state.  gpu_pool[n_slots, ...] on the GPU, host_pool[n_blocks, ...] pinned
+    host memory with the same payload shape; the int32 maps are updated in place.  Returns info[8] (device)."""
+    lib = load_library()
+    nb, ns = slot_of_block.numel(), block_of_slot.numel()
+    block_bytes = gpu_pool[0].numel() * gpu_pool.element_size()
+    if host_pool.shape[0] != nb or gpu_pool.shape[0] != ns or \
+            host_pool[0].numel() * host_pool.element_size() != block_bytes:
+        raise ValueError("pool shapes do not match the maps")
+    for t, name in ((candidate, "candidate"), (slot_of_block, "slot_of_block"), (block_of_slot, "block_of_slot"),
+                    (in_memory, "in_memory")):
+        if t.dtype != torch.int32:
+            raise TypeError(f"{name} must be int32")
+    dev = slot_of_block.device
+    if info is None:
+        info = torch.empty(8, dtype=torch.int32, device=dev)
+    need = lib.slim_kv_swap_workspace_bytes(nb, ns)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    _check(lib.slim_kv_swap(_dev(candidate, "candidate"), candidate.numel(), nb, float(gamma),
+                            _dev(slot_of_block, "slot_of_block"), _dev(block_of_slot, "block_of_slot"),
+                            _dev(in_memory, "in_memory"), ns, _dev(gpu_pool, "gpu_pool"), _pinned(host_pool, "host_pool"),
+                            block_bytes, _dev(info, "info"), _dev(workspace, "workspace"), workspace.numel(), _stream()),
+           "slim_kv_swap")
+    return info
 
 
 def slim_select_topk_blocks(scores: torch.Tensor, n_keep: int, force_flags: int = FORCE_FIRST | FORCE_LAST,

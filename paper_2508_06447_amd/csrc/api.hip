@@ -118,6 +118,47 @@ int slim_score_blocks_pooled(const void* q_win, const void* k, int n_tokens, int
                         scores, (float*)workspace, (hipStream_t)stream);
 }
 
+int slim_unit_keys(const void* k, int n_tokens, int n_kv_heads, int head_dim, int block, int unit, int dtype,
+                   float* k_rep, void* stream) {
+    if (!k || !k_rep || n_tokens < 1 || n_kv_heads < 1 || head_dim < 1 || block < 1 || unit < 1 || unit > block)
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const int E = n_kv_heads * head_dim;
+    if (E % (dtype == SLIM_BF16 ? 8 : 4) != 0 || E > 8192 || !aligned16(k) || !aligned16(k_rep)) return SLIM_UNSUPPORTED;
+    return launch_unit_keys(k, n_tokens, E, block, unit, dtype, k_rep, (hipStream_t)stream);
+}
+
+int slim_score_blocks_from_unit_keys(const void* q_win, const float* k_rep, int n_tokens, int window, int n_q_heads,
+                                     int n_kv_heads, int head_dim, int block, int unit, int dtype, float* scores,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q_win || !k_rep || !scores || !workspace || n_tokens < 1 || window < 1 || n_q_heads < 1 || n_kv_heads < 1 ||
+        head_dim < 1 || block < 1 || unit < 1 || unit > block || n_q_heads % n_kv_heads != 0)
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const int E = n_kv_heads * head_dim;
+    if (E % (dtype == SLIM_BF16 ? 8 : 4) != 0 || E > 8192 || !aligned16(k_rep)) return SLIM_UNSUPPORTED;
+    if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
+    return launch_score_from_unit_keys(q_win, k_rep, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit,
+                                       dtype, scores, (float*)workspace, (hipStream_t)stream);
+}
+
+size_t slim_kv_swap_workspace_bytes(int n_blocks, int n_slots) {
+    if (n_blocks < 1 || n_slots < 1) return 0;
+    return align_up(((size_t)n_blocks + 3 * (size_t)n_slots) * sizeof(int), 256);
+}
+
+int slim_kv_swap(const int* candidate, int n_candidates, int n_blocks, double gamma, int* slot_of_block,
+                 int* block_of_slot, int* in_memory, int n_slots, void* gpu_pool, void* host_pool, size_t block_bytes,
+                 int* info, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!candidate || !slot_of_block || !block_of_slot || !in_memory || !gpu_pool || !host_pool || !info || !workspace ||
+        n_candidates < 1 || n_blocks < 1 || n_slots < 1 || block_bytes < 1 || !(gamma >= 0.0 && gamma <= 1.0))
+        return SLIM_INVALID_ARG;
+    if (block_bytes % 16 != 0 || !aligned16(gpu_pool) || !aligned16(host_pool) || n_slots > 65535) return SLIM_UNSUPPORTED;
+    if (workspace_bytes < slim_kv_swap_workspace_bytes(n_blocks, n_slots)) return SLIM_WORKSPACE_TOO_SMALL;
+    return launch_kv_swap(candidate, n_candidates, n_blocks, gamma, slot_of_block, block_of_slot, in_memory, n_slots,
+                          gpu_pool, host_pool, block_bytes, info, (int*)workspace, (hipStream_t)stream);
+}
+
 int slim_select_topk_blocks(const float* scores, int n_blocks, int n_keep, unsigned force_flags, int* kept_blocks,
                             void* stream) {
     if (!scores || !kept_blocks || n_blocks < 1 || n_keep < 1) return SLIM_INVALID_ARG;

@@ -183,6 +183,100 @@ int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv
 }
 
 // -------------------------------------------------------------------------------------------------
+// Decode-time form of the scores (Section 4.2: during decoding the window is the most recent tokens and
+// the prompt's Key states may sit in CPU memory).  Eq. (1) is evaluated once, when the keys are produced,
+// and kept as k_rep[nb, M, E] in float; Eq. (2) then reads 1/unit of the bytes of the keys.
+// -------------------------------------------------------------------------------------------------
+// One wave per TokenUnit, 4 units per workgroup.  Units past the end of the prompt are written as zeros.
+template <typename T>
+__global__ void __launch_bounds__(256) unit_keys_kernel(const T* __restrict__ k, int N, int E, int block, int unit,
+                                                         int M, int n_units, float* __restrict__ k_rep) {
+    constexpr int V = Elem<T>::kVec;
+    const int lane = threadIdx.x & 63;
+    const int u = blockIdx.x * 4 + (threadIdx.x >> 6);   // unit index = j*M + m
+    if (u >= n_units) return;
+    const int j = u / M, m = u - j * M;
+    const int b1 = min((j + 1) * block, N);
+    const int u0 = j * block + m * unit, u1 = min(u0 + unit, b1);   // u1 <= u0: the unit does not exist
+    const float inv = u1 > u0 ? 1.f / (float)(u1 - u0) : 0.f;
+    for (int c = lane; c < E / V; c += 64) {
+        float ksum[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) ksum[i] = 0.f;
+#pragma unroll 8
+        for (int t = u0; t < u1; ++t) {
+            uint4 raw = *reinterpret_cast<const uint4*>(k + (size_t)t * E + (size_t)c * V);
+            float f[V];
+            Elem<T>::unpack(raw, f);
+#pragma unroll
+            for (int i = 0; i < V; ++i) ksum[i] += f[i];
+        }
+        float* dst = k_rep + (size_t)u * E + (size_t)c * V;
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q)
+            *reinterpret_cast<float4*>(dst + 4 * q) = make_float4(ksum[4 * q] * inv, ksum[4 * q + 1] * inv,
+                                                                  ksum[4 * q + 2] * inv, ksum[4 * q + 3] * inv);
+    }
+}
+
+// One workgroup per block, one wave per stored unit key: dot with qt, max over the units the block has.
+__global__ void __launch_bounds__(1024) unit_score_kernel(const float* __restrict__ k_rep,
+                                                           const float* __restrict__ qt, int N, int E, int block,
+                                                           int unit, int M, float* __restrict__ scores) {
+    extern __shared__ float smem[];                      // qt copy [E] + per-wave maxima [16]
+    float* qs = smem;
+    float* wmax = smem + E;
+    const int j = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    for (int e = threadIdx.x; e < E; e += blockDim.x) qs[e] = qt[e];
+    __syncthreads();
+    const int rows = min(block, N - j * block);
+    const int m_have = (rows + unit - 1) / unit;         // units this block really has
+    float best = -INFINITY;
+    for (int m = wave; m < m_have; m += nw) {
+        const float* kr = k_rep + ((size_t)j * M + m) * E;
+        float acc = 0.f;
+        for (int c = lane; c < E / 4; c += 64) {
+            const float4 a = *reinterpret_cast<const float4*>(kr + 4 * c);
+            acc += a.x * qs[4 * c] + a.y * qs[4 * c + 1] + a.z * qs[4 * c + 2] + a.w * qs[4 * c + 3];
+        }
+        best = fmaxf(best, wave_sum(acc));
+    }
+    if (lane == 0) wmax[wave] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float mx = wmax[0];
+        for (int i = 1; i < nw; ++i) mx = fmaxf(mx, wmax[i]);
+        scores[j] = mx;
+    }
+}
+
+int launch_unit_keys(const void* k, int N, int E, int block, int unit, int dtype, float* k_rep, hipStream_t st) {
+    const int nb = (N + block - 1) / block, M = (block + unit - 1) / unit, n_units = nb * M;
+    dim3 grid((n_units + 3) / 4);
+    if (dtype == SLIM_BF16)
+        hipLaunchKernelGGL(unit_keys_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)k, N, E, block, unit, M,
+                           n_units, k_rep);
+    else
+        hipLaunchKernelGGL(unit_keys_kernel<float>, grid, dim3(256), 0, st, (const float*)k, N, E, block, unit, M,
+                           n_units, k_rep);
+    return check_launch();
+}
+
+int launch_score_from_unit_keys(const void* q_win, const float* k_rep, int N, int w, int Hq, int Hkv, int d,
+                                int block, int unit, int dtype, float* scores, float* qtilde, hipStream_t st) {
+    const int E = Hkv * d, nb = (N + block - 1) / block, M = (block + unit - 1) / unit;
+    const int waves = M > 16 ? 16 : M;
+    dim3 g1((E + 63) / 64);
+    if (dtype == SLIM_BF16)
+        hipLaunchKernelGGL(window_query_kernel<bf16_t>, g1, dim3(1024), 0, st, (const bf16_t*)q_win, w, Hq, Hkv, d, qtilde);
+    else
+        hipLaunchKernelGGL(window_query_kernel<float>, g1, dim3(1024), 0, st, (const float*)q_win, w, Hq, Hkv, d, qtilde);
+    hipLaunchKernelGGL(unit_score_kernel, dim3(nb), dim3(64 * waves), (size_t)(E + 16) * sizeof(float), st, k_rep, qtilde,
+                       N, E, block, unit, M, scores);
+    return check_launch();
+}
+
+// -------------------------------------------------------------------------------------------------
 // Selection: one workgroup.  An 8-bit-digit radix select over order-preserving integer keys finds
 // the score of the last block to take; equal scores are taken in ascending index order; the kept
 // set is written ascending through a prefix sum of the keep flags.  Integer work only, so the

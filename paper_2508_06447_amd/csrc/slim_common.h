@@ -104,6 +104,12 @@ int launch_linear(const void* a, int lda, const void* w0, const void* w1, const 
                   int n_out, int k_in, int ldo, int dtype, void* out, hipStream_t st);
 int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv, int d, int block, int unit,
                  int pooling, int dtype, float* scores, float* qtilde, hipStream_t st);
+int launch_unit_keys(const void* k, int N, int E, int block, int unit, int dtype, float* k_rep, hipStream_t st);
+int launch_score_from_unit_keys(const void* q_win, const float* k_rep, int N, int w, int Hq, int Hkv, int d,
+                                int block, int unit, int dtype, float* scores, float* qtilde, hipStream_t st);
+int launch_kv_swap(const int* candidate, int n_candidates, int n_blocks, double gamma, int* slot_of_block,
+                   int* block_of_slot, int* in_memory, int n_slots, void* gpu_pool, void* host_pool,
+                   size_t block_bytes, int* info, int* workspace, hipStream_t st);
 int launch_positions(const int* pos_in, int* pos_out, int n, hipStream_t st);
 int launch_select(const float* scores, int nb, int n_keep, unsigned flags, int* kept, hipStream_t st);
 int launch_compact(const void* src, const int* pos_in, const int* kept, int n_keep, int block, int N,

@@ -1,0 +1,246 @@
+"""GPU parity of the decode-time pieces: block scores from stored unit keys (Eq. 1-2, Section 4.2) and the
+overlap-aware KV swap (Algorithm 1, Section 4.3), each through the C ABI against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slim_oracle as so
+from tests.helpers import f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def slim():
+    import paper_2508_06447_amd as slim
+    slim.load_library()
+    return slim
+
+
+def rand(shape, dtype, seed, scale=1.0):
+    g = np.random.default_rng(seed)
+    return torch.from_numpy((scale * g.standard_normal(shape)).astype(np.float32)).to(dtype)
+
+
+# ------------------------------------------------------------------------------- scores from stored unit keys
+SCORE_SHAPES = [
+    # N, window, Hq, Hkv, d, block, unit, dtype
+    (512, 16, 4, 2, 64, 16, 4, torch.float32),
+    (4096, 64, 32, 8, 128, 64, 8, torch.bfloat16),
+    (1000, 4, 32, 8, 128, 64, 8, torch.bfloat16),        # ragged last block (40 tokens = 5 units)
+    (1003, 4, 8, 2, 128, 64, 8, torch.bfloat16),         # ragged last unit as well (43 tokens)
+    (45, 2, 4, 2, 32, 8, 3, torch.float32),              # unit does not divide block
+    (700, 4, 28, 4, 128, 64, 8, torch.bfloat16),         # 7 query heads per kv head
+    (64, 4, 2, 1, 8, 64, 64, torch.float32),             # one block, one unit
+]
+
+
+@pytest.mark.parametrize("N,w,Hq,Hkv,d,block,unit,dtype", SCORE_SHAPES)
+def test_unit_keys_and_their_scores_match_oracle(slim, N, w, Hq, Hkv, d, block, unit, dtype):
+    print(f"unit-key scores N={N} w={w} Hq={Hq} Hkv={Hkv} d={d} block={block} unit={unit} {dtype}", flush=True)
+    k = rand((N, Hkv, d), dtype, seed=N + d)
+    q = rand((w, Hq, d), dtype, seed=N + d + 1)
+    k_rep = slim.slim_unit_keys(k.cuda(), block, unit)
+    want_rep = so.all_unit_keys(f64(k), block, unit)                     # [nb, M, Hkv, d], NaN where no unit
+    nb, M = want_rep.shape[:2]
+    assert tuple(k_rep.shape) == (nb, M, Hkv * d)
+    got_rep = f64(k_rep).reshape(nb, M, Hkv, d)
+    present = ~np.isnan(want_rep)
+    # float sums of at most `unit` inputs that are exact in float: a few ulp of the unit's magnitude
+    assert np.abs(got_rep[present] - want_rep[present]).max() < 1e-5
+    assert (got_rep[~present] == 0).all()
+    scores = slim.slim_score_blocks_from_unit_keys(q.cuda(), k_rep, N, Hkv, block, unit)
+    want = so.block_scores_from_unit_keys(f64(q), want_rep)
+    scale = max(1.0, float(np.abs(want).max()))
+    assert np.abs(f64(scores) - want).max() < 2e-5 * scale
+    # the prefill form on the keys themselves gives the same numbers up to the order of the float additions
+    direct = slim.slim_score_blocks(q.cuda(), k.cuda(), block, unit)
+    assert (scores - direct).abs().max().item() < 2e-5 * scale
+
+
+def test_a_decode_step_scores_stored_keys_with_a_new_window(slim):
+    """The stored unit keys are computed once; later windows (the most recent decoded tokens) reuse them."""
+    N, Hq, Hkv, d, block, unit = 2048, 32, 8, 128, 64, 8
+    k = rand((N, Hkv, d), torch.bfloat16, seed=11)
+    k_rep = slim.slim_unit_keys(k.cuda(), block, unit)
+    want_rep = so.all_unit_keys(f64(k), block, unit)
+    for step in range(3):
+        q = rand((4, Hq, d), torch.bfloat16, seed=100 + step)
+        got = slim.slim_score_blocks_from_unit_keys(q.cuda(), k_rep, N, Hkv, block, unit)
+        want = so.block_scores_from_unit_keys(f64(q), want_rep)
+        assert np.abs(f64(got) - want).max() < 2e-5 * max(1.0, float(np.abs(want).max()))
+
+
+# ------------------------------------------------------------------------------------------------ KV swap
+class SwapState:
+    """Device state of the swap plus the payloads every block must carry wherever it lives."""
+
+    def __init__(self, n_blocks, n_slots, payload_words, active, seed):
+        g = np.random.default_rng(seed)
+        self.nb, self.ns = n_blocks, n_slots
+        self.data = torch.from_numpy(g.integers(-2**31, 2**31 - 1, (n_blocks, payload_words), dtype=np.int64)
+                                     .astype(np.int32))
+        slots = g.permutation(n_slots)[:len(active)]
+        sob = np.full(n_blocks, -1, np.int32)
+        bos = np.full(n_slots, -1, np.int32)
+        for b, s in zip(sorted(active), slots):
+            sob[b], bos[s] = s, b
+        mem = np.ones(n_blocks, np.int32)
+        mem[sorted(active)] = 0                          # what is on the GPU has not been written to the CPU pool
+        self.host_pool = torch.full((n_blocks, payload_words), -1, dtype=torch.int32).pin_memory()
+        in_pool = torch.from_numpy(mem == 1)
+        self.host_pool[in_pool] = self.data[in_pool]
+        gpu = torch.full((n_slots, payload_words), -2, dtype=torch.int32)
+        for b in active:
+            gpu[sob[b]] = self.data[b]
+        self.gpu_pool = gpu.cuda()
+        self.slot_of_block = torch.from_numpy(sob).cuda()
+        self.block_of_slot = torch.from_numpy(bos).cuda()
+        self.in_memory = torch.from_numpy(mem).cuda()
+
+    def sets(self):
+        sob = self.slot_of_block.cpu().numpy()
+        mem = self.in_memory.cpu().numpy()
+        return set(np.nonzero(sob >= 0)[0].tolist()), set(np.nonzero(mem)[0].tolist())
+
+    def check_consistent(self):
+        sob, bos = self.slot_of_block.cpu().numpy(), self.block_of_slot.cpu().numpy()
+        torch.cuda.synchronize()
+        gpu, host, mem = self.gpu_pool.cpu(), self.host_pool, self.in_memory.cpu().numpy()
+        for b in range(self.nb):                         # the two maps are inverse to each other
+            if sob[b] >= 0:
+                assert 0 <= sob[b] < self.ns and bos[sob[b]] == b
+                assert torch.equal(gpu[sob[b]], self.data[b]), f"GPU slot of block {b} holds other bytes"
+            else:
+                assert mem[b] == 1, f"block {b} is neither on the GPU nor in the CPU pool"
+            if mem[b]:
+                assert torch.equal(host[b], self.data[b]), f"CPU pool entry of block {b} holds other bytes"
+        for s in range(self.ns):
+            assert bos[s] == -1 or sob[bos[s]] == s
+
+
+def run_step(slim, st, cand_list, gamma):
+    active_prev, memory = st.sets()
+    want = so.kv_swap_step(active_prev, cand_list, memory, gamma)
+    info = slim.slim_kv_swap(torch.tensor(cand_list, dtype=torch.int32).cuda(), gamma, st.slot_of_block,
+                             st.block_of_slot, st.in_memory, st.gpu_pool, st.host_pool)
+    torch.cuda.synchronize()
+    info = info.cpu().numpy()
+    active, mem = st.sets()
+    assert info[5] == 0
+    assert info[0] == len(set(cand_list)) and info[1] == len(set(cand_list) & active_prev)
+    assert bool(info[2]) == want["swapped"]
+    assert active == want["active"] and mem == want["memory"]
+    assert info[3] == len(want["offload"]) and info[4] == len(want["load"])
+    assert info[6] == (len(active_prev - want["active"]) if want["swapped"] else 0)
+    st.check_consistent()
+    return want
+
+
+@pytest.mark.parametrize("n_blocks,n_slots,n_active,words,seed", [
+    (40, 12, 10, 20, 0),            # payload smaller than one thread's share
+    (512, 128, 128, 4096, 1),       # every slot in use
+    (333, 90, 50, 1028, 2),         # spare slots, payload not a multiple of the copy tile
+    (2100, 1100, 1000, 8, 3),       # more blocks and slots than one pass of the planning workgroup
+])
+def test_kv_swap_random_walk_matches_algorithm_1(slim, n_blocks, n_slots, n_active, words, seed):
+    print(f"kv swap walk nb={n_blocks} slots={n_slots} active={n_active} words={words}", flush=True)
+    g = np.random.default_rng(seed)
+    active0 = set(g.choice(n_blocks, n_active, replace=False).tolist())
+    st = SwapState(n_blocks, n_slots, words, active0, seed)
+    st.check_consistent()
+    n_swaps = 0
+    for step in range(14):
+        active, _ = st.sets()
+        gamma = [0.9, 0.5, 1.0, 0.0, 0.99, 0.9, 0.75][step % 7]
+        # candidate: the active set with a random share replaced, its size drifting within the slots
+        size = int(np.clip(len(active) + g.integers(-3, 4), 1, n_slots))
+        stay = g.permutation(sorted(active))[:int(round(size * g.choice([1.0, 0.95, 0.9, 0.8, 0.4, 0.0])))]
+        others = g.permutation(sorted(set(range(n_blocks)) - active))[:size - len(stay)]
+        cand = [int(c) for c in np.concatenate([stay, others]).astype(np.int64)]
+        if step % 3 == 0 and cand:
+            cand = cand + cand[:2]                       # repeated indices count once
+        cand = [cand[i] for i in g.permutation(len(cand))]
+        want = run_step(slim, st, cand, gamma)
+        n_swaps += want["swapped"]
+    assert 0 < n_swaps < 14                              # both branches were taken
+
+
+def test_kv_swap_edges_of_the_threshold(slim):
+    st = SwapState(20, 10, 16, set(range(10)), seed=5)
+    # 9 of 10 candidates already active: overlap 0.9 is not < 0.9 -> reuse; it is < 0.91 -> swap
+    cand = list(range(9)) + [15]
+    assert not run_step(slim, st, cand, 0.9)["swapped"]
+    assert not run_step(slim, st, cand, 0.0)["swapped"]
+    assert run_step(slim, st, cand, 0.91)["swapped"]
+    # identical sets: overlap 1.0 never swaps, even at gamma = 1
+    assert not run_step(slim, st, cand, 1.0)["swapped"]
+    # disjoint candidate: swaps at any gamma > 0; the 10 leaving blocks are copied out only if not in the pool
+    w = run_step(slim, st, list(range(10, 15)) + [16, 17], 0.5)
+    assert w["swapped"] and w["offload"] == {0, 1, 2, 3, 4, 5, 6, 7, 8}      # block 15 was in the pool already
+    # a single candidate
+    assert run_step(slim, st, [3], 0.9)["swapped"]
+    assert st.sets()[0] == {3}
+
+
+def test_kv_swap_reports_errors_and_leaves_the_state_alone(slim):
+    st = SwapState(20, 6, 16, {0, 1, 2, 3}, seed=6)
+
+    def snapshot():
+        return [t.clone() for t in (st.slot_of_block, st.block_of_slot, st.in_memory, st.gpu_pool)] + \
+               [st.host_pool.clone()]
+
+    def same(a, b):
+        return all(torch.equal(x.cpu(), y.cpu()) for x, y in zip(a, b))
+
+    def call(cand, gamma=0.9):
+        info = slim.slim_kv_swap(torch.tensor(cand, dtype=torch.int32).cuda(), gamma, st.slot_of_block,
+                                 st.block_of_slot, st.in_memory, st.gpu_pool, st.host_pool)
+        torch.cuda.synchronize()
+        return info.cpu().numpy()
+
+    before = snapshot()
+    assert call([0, 1, 25])[5] & 1                       # candidate outside [0, n_blocks)
+    assert call([0, -1])[5] & 1
+    assert call([5, 6, 7, 8, 9, 10, 11])[5] & 4          # seven candidates, six slots
+    assert same(before, snapshot())
+    st.in_memory[7] = 0                                  # block 7 is nowhere: it cannot be loaded
+    before = snapshot()
+    assert call([0, 7])[5] & 2
+    assert same(before, snapshot())
+    st.in_memory[7] = 1
+    st.block_of_slot[int(st.slot_of_block[2])] = 3       # maps no longer inverse
+    before = snapshot()
+    assert call([0, 9])[5] & 8
+    assert same(before, snapshot())
+    # host-side argument errors
+    with pytest.raises(slim.SlimError):
+        call([0, 1], gamma=1.5)
+    with pytest.raises(slim.SlimError):
+        call([0, 1], gamma=float("nan"))
+
+
+def test_kv_swap_on_a_second_stream_beside_compute(slim):
+    """The swap is enqueued on its own stream while a projection runs on the current one (Section 4.3:
+    the transfer overlaps the FFN and the next QKV generation); both results are intact."""
+    n_blocks, n_slots, words = 512, 128, 65536           # 256 KiB per block: 64 tokens of K and V of one layer
+    st = SwapState(n_blocks, n_slots, words, set(range(0, 256, 2)), seed=9)
+    a = rand((2048, 4096), torch.bfloat16, 1).cuda()
+    w = rand((4096, 4096), torch.bfloat16, 2, scale=0.02).cuda()
+    ref = slim.slim_linear(a, w)
+    torch.cuda.synchronize()
+    active_prev, memory = st.sets()
+    cand = sorted(active_prev)[:96] + list(range(257, 289))          # 32 of 128 replaced
+    want = so.kv_swap_step(active_prev, cand, memory, 0.9)
+    side = torch.cuda.Stream()
+    cand_t = torch.tensor(cand, dtype=torch.int32).cuda()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        info = slim.slim_kv_swap(cand_t, 0.9, st.slot_of_block, st.block_of_slot, st.in_memory, st.gpu_pool,
+                                 st.host_pool)
+    outs = [slim.slim_linear(a, w) for _ in range(4)]
+    torch.cuda.synchronize()
+    assert info.cpu().numpy()[2] == 1 and st.sets()[0] == want["active"] and st.sets()[1] == want["memory"]
+    st.check_consistent()
+    for o in outs:
+        assert torch.equal(o, ref)
