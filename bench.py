@@ -236,6 +236,124 @@ def bench_model(args, slim, inputs, wl, dev):
     print(json.dumps(rec))
 
 
+def bench_decode(args, slim, dev):
+    """Decode-time pieces at the 32K-prompt shape (variant, not the graded line): scores from stored unit keys
+    and one overlap-aware KV swap step that replaces a quarter of a 128-block active set, alone and beside the
+    FFN projection it is meant to hide behind.  The swap moves bytes over the host link, so its yardstick is that
+    link (PCIe 5.0 x16, 64 GB/s each way), not HBM."""
+    import torch
+    from paper_2508_06447_amd import inputs
+    wl = inputs.WORKLOADS["cfg3"]
+    N, Hq, Hkv, d, block, unit = wl.seq, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block, wl.unit
+    E, nb, M = Hkv * d, wl.n_blocks, block // unit
+    bf = torch.bfloat16
+    k = torch.randn(N, Hkv, d, device=dev).to(bf)
+    q = torch.randn(4, Hq, d, device=dev).to(bf)
+    k_rep = slim.slim_unit_keys(k, block, unit)
+    sc = torch.empty(nb, dtype=torch.float32, device=dev)
+    ws = torch.empty(4096 * 4, dtype=torch.uint8, device=dev)
+    reps = max(10, args.steps)
+    rec_k = {}
+    _, t = time_gpu(lambda: slim.slim_unit_keys(k, block, unit, k_rep), reps)
+    b = N * E * 2 + nb * M * E * 4
+    rec_k["unit_keys"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1), "frac_hbm": round(b / t / 1e6 / PEAK_HBM_GBS, 4)}
+    _, t = time_gpu(lambda: slim.slim_score_blocks_from_unit_keys(q, k_rep, N, Hkv, block, unit, sc, ws), reps)
+    b = nb * M * E * 4
+    rec_k["score_from_unit_keys"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1), "note": "two launches (window query, scores)"}
+    _, t = time_gpu(lambda: slim.slim_score_blocks(q, k, block, unit, sc, ws), reps)
+    b = N * E * 2
+    rec_k["score_from_keys"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1)}
+
+    n_slots, n_swap = 128, 32
+    swaps = {}
+    h = torch.randn(9856, wl.hidden, device=dev).to(bf)
+    wg = torch.randn(wl.ffn, wl.hidden, device=dev).to(bf)
+    wu = torch.randn(wl.ffn, wl.hidden, device=dev).to(bf)
+    act = torch.empty(9856, wl.ffn, device=dev, dtype=bf)
+    gemm = lambda: slim.slim_swiglu_linear(h, wg, wu, out=act)
+    _, t_gemm = time_gpu(gemm, reps)
+    side = torch.cuda.Stream()
+    for layers in (1, 10):
+        words = layers * block * 2 * E * 2 // 4           # K and V rows of one block, `layers` layers, in 4-byte words
+        gpu_pool = torch.zeros(n_slots, words, dtype=torch.int32, device=dev)
+        host_pool = torch.zeros(nb, words, dtype=torch.int32).pin_memory()
+        sob = torch.full((nb,), -1, dtype=torch.int32)
+        bos = torch.arange(n_slots, dtype=torch.int32)
+        sob[:n_slots] = torch.arange(n_slots, dtype=torch.int32)
+        sob, bos = sob.to(dev), bos.to(dev)
+        mem = torch.ones(nb, dtype=torch.int32, device=dev)
+        cand_a = torch.arange(n_slots, dtype=torch.int32, device=dev)
+        cand_b = torch.cat([torch.arange(n_slots - n_swap), torch.arange(256, 256 + n_swap)]).to(torch.int32).to(dev)
+        info = torch.empty(8, dtype=torch.int32, device=dev)
+        wsw = torch.empty(slim.load_library().slim_kv_swap_workspace_bytes(nb, n_slots), dtype=torch.uint8, device=dev)
+        state = {"i": 0}
+
+        def swap(fresh=False):
+            if fresh:
+                mem.copy_((sob < 0).to(torch.int32))      # what sits on the GPU has no copy in the CPU pool yet
+            c = cand_b if state["i"] % 2 == 0 else cand_a
+            state["i"] += 1
+            slim.slim_kv_swap(c, 0.9, sob, bos, mem, gpu_pool, host_pool, info, wsw)
+
+        def timed(fn, n):
+            evs = []
+            for _ in range(n):
+                a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                fn(a, b_)
+                evs.append((a, b_))
+            torch.cuda.synchronize()
+            ts = [a.elapsed_time(b_) for a, b_ in evs]
+            return sum(ts) / len(ts)
+
+        def load_only(a, b_):
+            a.record(); swap(); b_.record()
+
+        def with_offload(a, b_):
+            mem.copy_((sob < 0).to(torch.int32)); a.record(); swap(); b_.record()
+
+        swap(); swap(); torch.cuda.synchronize()
+        t_load = timed(load_only, reps)
+        t_both = timed(with_offload, reps)
+        assert int(info.cpu()[2]) == 1 and int(info.cpu()[4]) == n_swap
+        keep = cand_b if state["i"] % 2 == 1 else cand_a  # the set that is active now: overlap 1, nothing moves
+        _, t_noswap = time_gpu(lambda: slim.slim_kv_swap(keep, 0.9, sob, bos, mem, gpu_pool, host_pool, info, wsw), reps)
+        # beside the FFN projection: the swap on a second stream, the projection on the current one
+        torch.cuda.synchronize()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_pairs = 6
+        with torch.cuda.stream(side):
+            s0.record()
+            for _ in range(n_pairs):
+                swap()
+            s1.record()
+        a0.record()
+        for _ in range(n_pairs):
+            gemm()
+        a1.record()
+        torch.cuda.synchronize()
+        payload = n_swap * words * 4
+        swaps[f"{layers}_layer_payload"] = {
+            "block_bytes": words * 4, "blocks_loaded": n_swap, "bytes_each_way": payload,
+            "load_only_ms": round(t_load, 4), "load_gbs": round(payload / t_load / 1e6, 1),
+            "offload_and_load_ms": round(t_both, 4), "offload_and_load_gbs_each_way": round(payload / t_both / 1e6, 1),
+            "no_swap_step_ms": round(t_noswap, 4),
+            "beside_swiglu_gemm": {"gemm_alone_ms": round(t_gemm, 4), "gemm_ms": round(a0.elapsed_time(a1) / n_pairs, 4),
+                                   "swap_ms": round(s0.elapsed_time(s1) / n_pairs, 4)},
+        }
+        del gpu_pool, host_pool
+    big = swaps["10_layer_payload"]
+    rec = {"metric": "kv-swap load GB/s", "value": big["load_gbs"], "unit": "GB/s", "n_gpus": 1, "steps": reps,
+           "warmup": 3, "ms_per_step": big["load_only_ms"], "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+           "config": {"workload": f"decode-step KV manager at the cfg3 shape: {nb} prompt blocks of {block} tokens, "
+                                  f"{n_slots} GPU slots, {n_swap} blocks replaced per swap, gamma 0.9", "variant": "decode"},
+           "kernels": rec_k, "kv_swap": swaps,
+           "roofline": {"kernel": "kv_swap_copy_kernel", "bound": "pcie", "achieved": big["load_gbs"], "peak": 64.0,
+                        "unit": "GB/s", "frac": round(big["load_gbs"] / 64.0, 4), "traffic": None}}
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -263,6 +381,8 @@ def main():
         sys.exit(1)
     slim.load_library()
     dev = torch.device("cuda:0")
+    if args.workload == "decode":
+        return bench_decode(args, slim, dev)
     wl = inputs.WORKLOADS[args.workload]
     if wl.n_layers > 1:
         return bench_model(args, slim, inputs, wl, dev)

@@ -144,7 +144,7 @@ int slim_score_blocks_from_unit_keys(const void* q_win, const float* k_rep, int 
 
 size_t slim_kv_swap_workspace_bytes(int n_blocks, int n_slots) {
     if (n_blocks < 1 || n_slots < 1) return 0;
-    return align_up(((size_t)n_blocks + 3 * (size_t)n_slots) * sizeof(int), 256);
+    return align_up(((size_t)n_blocks + 4 * (size_t)n_slots + 1) * sizeof(int), 256);
 }
 
 int slim_kv_swap(const int* candidate, int n_candidates, int n_blocks, double gamma, int* slot_of_block,
@@ -153,7 +153,7 @@ int slim_kv_swap(const int* candidate, int n_candidates, int n_blocks, double ga
     if (!candidate || !slot_of_block || !block_of_slot || !in_memory || !gpu_pool || !host_pool || !info || !workspace ||
         n_candidates < 1 || n_blocks < 1 || n_slots < 1 || block_bytes < 1 || !(gamma >= 0.0 && gamma <= 1.0))
         return SLIM_INVALID_ARG;
-    if (block_bytes % 16 != 0 || !aligned16(gpu_pool) || !aligned16(host_pool) || n_slots > 65535) return SLIM_UNSUPPORTED;
+    if (block_bytes % 16 != 0 || !aligned16(gpu_pool) || !aligned16(host_pool)) return SLIM_UNSUPPORTED;
     if (workspace_bytes < slim_kv_swap_workspace_bytes(n_blocks, n_slots)) return SLIM_WORKSPACE_TOO_SMALL;
     return launch_kv_swap(candidate, n_candidates, n_blocks, gamma, slot_of_block, block_of_slot, in_memory, n_slots,
                           gpu_pool, host_pool, block_bytes, info, (int*)workspace, (hipStream_t)stream);

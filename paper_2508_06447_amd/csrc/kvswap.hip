@@ -37,9 +37,10 @@ __device__ int plan_exclusive_scan(int v, int* wsum /*[16]*/, int& total) {
     return base + inc - v;
 }
 
-// Workspace (ints): flag[n_blocks] | in_list[n_slots] | slot_out[n_slots] | slot_in[n_slots].
+// Workspace (ints): flag[n_blocks] | in_list[n_slots] | slot_out[n_slots] | slot_in[n_slots] | move_slot[n_slots] | n_moves.
 // slot_out[s] = block whose payload the copy kernel writes from slot s to the CPU pool (-1: none),
-// slot_in[s]  = block whose payload it then reads from the CPU pool into slot s (-1: none).
+// slot_in[s]  = block whose payload it then reads from the CPU pool into slot s (-1: none),
+// move_slot[0..n_moves) = the slots that have either, ascending.
 __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* __restrict__ candidate, int n_cand,
                                                                      int n_blocks, double gamma,
                                                                      int* __restrict__ slot_of_block,
@@ -52,6 +53,7 @@ __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* _
     int* in_list = ws + n_blocks;
     int* slot_out = in_list + n_slots;
     int* slot_in = slot_out + n_slots;
+    int* move_slot = slot_in + n_slots;
     const int tid = threadIdx.x;
     if (tid == 0) { s_cand = 0; s_ov = 0; s_err = 0; s_missing = 0; }
     __syncthreads();
@@ -87,7 +89,7 @@ __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* _
         if (s_missing > 0) err |= 2;                     // a block to load is neither on the GPU nor in the CPU pool
         if (nc > n_slots) err |= 4;                      // the GPU pool cannot hold the candidate set
     }
-    int n_off = 0, n_freed = 0;
+    int n_off = 0, n_freed = 0, n_moves = 0;
     if (swap && err == 0) {
         // Blocks to load, ascending.
         int base = 0;
@@ -110,7 +112,7 @@ __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* _
             int tot;
             const int r = plan_exclusive_scan(freeable, wsum, tot) + base;
             base += tot;
-            int copies = 0;
+            int copies = 0, arrives = 0;
             if (leaves) {
                 slot_of_block[b] = -1;
                 if (!in_memory[b]) { slot_out[s] = b; in_memory[b] = 1; copies = 1; }   // B_offload: not yet in the CPU pool
@@ -119,16 +121,20 @@ __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* _
                 const int nb_in = r < n_load ? in_list[r] : -1;
                 slot_in[s] = nb_in;
                 block_of_slot[s] = nb_in;
-                if (nb_in >= 0) slot_of_block[nb_in] = s;
+                if (nb_in >= 0) { slot_of_block[nb_in] = s; arrives = 1; }
             }
-            int t1, t2;
+            int t1, t2, t3;
             plan_exclusive_scan(copies, wsum, t1);
             plan_exclusive_scan(leaves ? 1 : 0, wsum, t2);
+            const int mv = plan_exclusive_scan(copies | arrives, wsum, t3) + n_moves;
+            if (copies | arrives) move_slot[mv] = s;
             n_off += t1;
             n_freed += t2;
+            n_moves += t3;
         }
     }
     if (tid == 0) {
+        move_slot[n_slots] = n_moves;
         info[INFO_CAND] = nc;
         info[INFO_OVERLAP] = nov;
         info[INFO_SWAPPED] = (swap && err == 0) ? 1 : 0;
@@ -140,47 +146,61 @@ __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* _
     }
 }
 
-// grid = (chunks of a payload, n_slots).  A thread owns kVecs 16-byte pieces of its slot: it first writes them to
-// the leaving block's place in the CPU pool (when that block has to be offloaded), then overwrites them with the
-// arriving block's bytes, so a slot is read before it is reused without any synchronisation between threads.
+// A fixed, small number of workgroups walks the move list: work item = (move, chunk of the payload).  The link to
+// the host, not the GPU, bounds this kernel: a read over it takes on the order of 10 us, so the rate is set by the
+// bytes in flight.  32 workgroups x 256 threads x 8 x 16 bytes = 1 MiB in flight reaches about 56 GB/s on a
+// PCIe 5.0 x16 link; 16 workgroups reach 42 GB/s, 64 add nothing.  One workgroup per item (thousands of waves that
+// all wait on the link) would instead sit on every compute unit and stall the compute kernels that the transfer is
+// meant to hide behind.
+// A thread owns kSwapVecs 16-byte pieces of its chunk: it first writes them to the leaving block's place in the CPU
+// pool (when that block has to be offloaded), then overwrites them with the arriving block's bytes, so a slot is
+// read before it is reused without any synchronisation between threads.
 constexpr int kSwapThreads = 256;
 constexpr int kSwapVecs = 8;
+constexpr int kSwapWorkgroups = 32;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __global__ void __launch_bounds__(kSwapThreads) kv_swap_copy_kernel(const int* __restrict__ slot_out,
                                                                     const int* __restrict__ slot_in,
+                                                                    const int* __restrict__ move_slot,
+                                                                    const int* __restrict__ n_moves_p,
                                                                     u32x4* __restrict__ gpu_pool,
                                                                     u32x4* __restrict__ host_pool, size_t block_vecs) {
-    const int s = blockIdx.y;
-    const int b_out = slot_out[s], b_in = slot_in[s];
-    if (b_out < 0 && b_in < 0) return;
-    u32x4* g = gpu_pool + (size_t)s * block_vecs;
-    const size_t base = (size_t)blockIdx.x * (kSwapThreads * kSwapVecs) + threadIdx.x;
-    u32x4 tmp[kSwapVecs];
-    if (b_out >= 0) {
-        u32x4* h = host_pool + (size_t)b_out * block_vecs;
+    constexpr size_t per = (size_t)kSwapThreads * kSwapVecs;
+    const size_t chunks = (block_vecs + per - 1) / per;
+    const size_t n_items = (size_t)(*n_moves_p) * chunks;
+    for (size_t it = blockIdx.x; it < n_items; it += gridDim.x) {
+        const size_t mv = it / chunks, chunk = it - mv * chunks;
+        const int s = move_slot[mv];
+        const int b_out = slot_out[s], b_in = slot_in[s];
+        u32x4* g = gpu_pool + (size_t)s * block_vecs;
+        const size_t base = chunk * per + threadIdx.x;
+        u32x4 tmp[kSwapVecs];
+        if (b_out >= 0) {
+            u32x4* h = host_pool + (size_t)b_out * block_vecs;
 #pragma unroll
-        for (int u = 0; u < kSwapVecs; ++u) {
-            const size_t o = base + (size_t)u * kSwapThreads;
-            if (o < block_vecs) tmp[u] = g[o];
+            for (int u = 0; u < kSwapVecs; ++u) {
+                const size_t o = base + (size_t)u * kSwapThreads;
+                if (o < block_vecs) tmp[u] = g[o];
+            }
+#pragma unroll
+            for (int u = 0; u < kSwapVecs; ++u) {
+                const size_t o = base + (size_t)u * kSwapThreads;
+                if (o < block_vecs) __builtin_nontemporal_store(tmp[u], h + o);
+            }
         }
+        if (b_in >= 0) {
+            const u32x4* h = host_pool + (size_t)b_in * block_vecs;
 #pragma unroll
-        for (int u = 0; u < kSwapVecs; ++u) {
-            const size_t o = base + (size_t)u * kSwapThreads;
-            if (o < block_vecs) __builtin_nontemporal_store(tmp[u], h + o);
-        }
-    }
-    if (b_in >= 0) {
-        const u32x4* h = host_pool + (size_t)b_in * block_vecs;
+            for (int u = 0; u < kSwapVecs; ++u) {
+                const size_t o = base + (size_t)u * kSwapThreads;
+                if (o < block_vecs) tmp[u] = __builtin_nontemporal_load(h + o);
+            }
 #pragma unroll
-        for (int u = 0; u < kSwapVecs; ++u) {
-            const size_t o = base + (size_t)u * kSwapThreads;
-            if (o < block_vecs) tmp[u] = __builtin_nontemporal_load(h + o);
-        }
-#pragma unroll
-        for (int u = 0; u < kSwapVecs; ++u) {
-            const size_t o = base + (size_t)u * kSwapThreads;
-            if (o < block_vecs) g[o] = tmp[u];
+            for (int u = 0; u < kSwapVecs; ++u) {
+                const size_t o = base + (size_t)u * kSwapThreads;
+                if (o < block_vecs) g[o] = tmp[u];
+            }
         }
     }
 }
@@ -193,11 +213,11 @@ int launch_kv_swap(const int* candidate, int n_candidates, int n_blocks, double 
     int rc = check_launch();
     if (rc != SLIM_OK) return rc;
     const size_t block_vecs = block_bytes / 16;
-    const size_t per = (size_t)kSwapThreads * kSwapVecs;
     const int* slot_out = workspace + n_blocks + n_slots;
     const int* slot_in = slot_out + n_slots;
-    hipLaunchKernelGGL(kv_swap_copy_kernel, dim3((unsigned)((block_vecs + per - 1) / per), n_slots), dim3(kSwapThreads), 0,
-                       st, slot_out, slot_in, (u32x4*)gpu_pool, (u32x4*)host_pool, block_vecs);
+    const int* move_slot = slot_in + n_slots;
+    hipLaunchKernelGGL(kv_swap_copy_kernel, dim3(kSwapWorkgroups), dim3(kSwapThreads), 0, st, slot_out, slot_in, move_slot,
+                       move_slot + n_slots, (u32x4*)gpu_pool, (u32x4*)host_pool, block_vecs);
     return check_launch();
 }
 

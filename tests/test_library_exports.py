@@ -64,7 +64,7 @@ def test_argument_errors_are_reported_before_anything_is_enqueued(lib):
     assert lib.slim_unit_keys(one, 100, 8, 128, 64, 128, 1, one, null) == -1                      # unit > block
     assert lib.slim_unit_keys(one, 100, 8, 128, 64, 8, 1, ctypes.c_void_p(260), null) == -2       # k_rep alignment
     assert lib.slim_score_blocks_from_unit_keys(one, one, 100, 4, 32, 8, 128, 64, 8, 1, one, one, 0, null) == -3
-    assert lib.slim_kv_swap_workspace_bytes(512, 128) == (512 + 3 * 128) * 4 and lib.slim_kv_swap_workspace_bytes(0, 4) == 0
+    assert lib.slim_kv_swap_workspace_bytes(512, 128) == 4352 and lib.slim_kv_swap_workspace_bytes(0, 4) == 0
     swap = lambda n_cand, gamma, block_bytes, ws: lib.slim_kv_swap(one, n_cand, 512, gamma, one, one, one, 128, one,
                                                                   one, block_bytes, one, one, ws, null)
     assert swap(0, 0.9, 4096, 4096) == -1 and swap(4, 1.5, 4096, 4096) == -1 and swap(4, float("nan"), 4096, 4096) == -1
