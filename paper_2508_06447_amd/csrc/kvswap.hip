@@ -152,9 +152,9 @@ __global__ void __launch_bounds__(kPlanThreads) kv_swap_plan_kernel(const int* _
 // PCIe 5.0 x16 link; 16 workgroups reach 42 GB/s, 64 add nothing.  One workgroup per item (thousands of waves that
 // all wait on the link) would instead sit on every compute unit and stall the compute kernels that the transfer is
 // meant to hide behind.
-// A thread owns kSwapVecs 16-byte pieces of its chunk: it first writes them to the leaving block's place in the CPU
-// pool (when that block has to be offloaded), then overwrites them with the arriving block's bytes, so a slot is
-// read before it is reused without any synchronisation between threads.
+// A thread owns kSwapVecs 16-byte pieces of its chunk: it reads them from the slot (when the leaving block has to be
+// offloaded) before it overwrites the same pieces with the arriving block's bytes, so a slot is read before it is
+// reused without any synchronisation between threads.
 constexpr int kSwapThreads = 256;
 constexpr int kSwapVecs = 8;
 constexpr int kSwapWorkgroups = 32;
@@ -175,31 +175,35 @@ __global__ void __launch_bounds__(kSwapThreads) kv_swap_copy_kernel(const int* _
         const int b_out = slot_out[s], b_in = slot_in[s];
         u32x4* g = gpu_pool + (size_t)s * block_vecs;
         const size_t base = chunk * per + threadIdx.x;
-        u32x4 tmp[kSwapVecs];
-        if (b_out >= 0) {
-            u32x4* h = host_pool + (size_t)b_out * block_vecs;
+        // Both directions of the link are used at once: the reads of the arriving bytes are issued before the
+        // writes of the leaving ones wait for their data.
+        u32x4 leaving[kSwapVecs], arriving[kSwapVecs];
+        u32x4* h_out = host_pool + (size_t)(b_out >= 0 ? b_out : 0) * block_vecs;
+        const u32x4* h_in = host_pool + (size_t)(b_in >= 0 ? b_in : 0) * block_vecs;
+        if (b_in >= 0) {
 #pragma unroll
             for (int u = 0; u < kSwapVecs; ++u) {
                 const size_t o = base + (size_t)u * kSwapThreads;
-                if (o < block_vecs) tmp[u] = g[o];
+                if (o < block_vecs) arriving[u] = __builtin_nontemporal_load(h_in + o);
+            }
+        }
+        if (b_out >= 0) {
+#pragma unroll
+            for (int u = 0; u < kSwapVecs; ++u) {
+                const size_t o = base + (size_t)u * kSwapThreads;
+                if (o < block_vecs) leaving[u] = g[o];
             }
 #pragma unroll
             for (int u = 0; u < kSwapVecs; ++u) {
                 const size_t o = base + (size_t)u * kSwapThreads;
-                if (o < block_vecs) __builtin_nontemporal_store(tmp[u], h + o);
+                if (o < block_vecs) __builtin_nontemporal_store(leaving[u], h_out + o);
             }
         }
         if (b_in >= 0) {
-            const u32x4* h = host_pool + (size_t)b_in * block_vecs;
 #pragma unroll
             for (int u = 0; u < kSwapVecs; ++u) {
                 const size_t o = base + (size_t)u * kSwapThreads;
-                if (o < block_vecs) tmp[u] = __builtin_nontemporal_load(h + o);
-            }
-#pragma unroll
-            for (int u = 0; u < kSwapVecs; ++u) {
-                const size_t o = base + (size_t)u * kSwapThreads;
-                if (o < block_vecs) g[o] = tmp[u];
+                if (o < block_vecs) g[o] = arriving[u];
             }
         }
     }
