@@ -6,6 +6,9 @@ scores, selection, compaction, Q/V projection, causal GQA attention, output proj
 FFN) on a synthetic workload whose inputs are already in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3] [--no-cpu] [--no-stages]
+
+Other workloads: cfg2, cfg4, cfg6 (single layers), cfg5, cfg7 (whole prefills), decode (the decode-time kernels:
+scores from stored unit keys and the overlap-aware KV swap; a variant line of its own).
 """
 from __future__ import annotations
 
