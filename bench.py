@@ -369,6 +369,9 @@ def main():
                     help="variant: pooled scoring baselines of the ablation instead of TokenUnits")
     ap.add_argument("--placement", choices=["before", "after"], default="before",
                     help="variant: drop the blocks after the pruning layer's attention instead of before it")
+    ap.add_argument("--block", type=int, default=0, help="variant: block size override (the paper's block-size sweep)")
+    ap.add_argument("--unit", type=int, default=0, help="variant: TokenUnit size override")
+    ap.add_argument("--window", type=int, default=0, help="variant: local query window override")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (the pruned prefill layer of one sequence); "
@@ -387,13 +390,16 @@ def main():
     if args.workload == "decode":
         return bench_decode(args, slim, dev)
     wl = inputs.WORKLOADS[args.workload]
+    over = {k: getattr(args, k) for k in ("block", "unit", "window") if getattr(args, k) > 0}
+    if over:
+        wl = inputs.scaled(wl, **over)
     if wl.n_layers > 1:
         return bench_model(args, slim, inputs, wl, dev)
     x = inputs.hidden_states(wl).to(dev)
     wd = {k: v.to(dev) for k, v in inputs.layer_weights(wl).items()}
     pos = inputs.positions(wl).to(dev)
     n_keep = wl.n_keep
-    variant = args.scoring != "unit" or args.placement != "before"
+    variant = args.scoring != "unit" or args.placement != "before" or bool(over)
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
                             wl.window, x.dtype, wl.rope_theta, wl.rms_eps,
                             scoring={"unit": 0, "avg": slim.POOL_AVG, "max": slim.POOL_MAX}[args.scoring],
@@ -440,8 +446,9 @@ def main():
     }
     if variant:
         # not the graded configuration: the flop count above is that of the default placement
-        rec["config"]["variant"] = {"scoring": args.scoring, "placement": args.placement}
-        del rec["layer_tflops"], rec["layer_mfma_frac"]
+        rec["config"]["variant"] = {"scoring": args.scoring, "placement": args.placement, **over}
+        if not over:
+            del rec["layer_tflops"], rec["layer_mfma_frac"]
     if not args.no_stages and wl.dtype == "bf16" and not variant:
         table = stage_table(slim, wl, wd, x, pos, n_keep, reps=max(5, args.steps))
         rec["kernels"] = table
