@@ -155,6 +155,34 @@ int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w
                        int n_out, int k_in, int ldo, int dtype, void* out, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Key-first scoring pipeline: the same Eq. (1)-(2) scores and the same rotated Key/Query states ("QKV
+ * Generation" of Fig. 2), with RoPE and the per-token part of the score folded into the projection's
+ * epilogue so that the Key states are written once and not re-read for scoring.  slim_pruned_layer uses
+ * these kernels for bf16 heads of 128; they are exposed to be checked and timed on their own.
+ *   slim_rope_table:   table[n, head_dim] float; row t = cos of the head_dim/2 rotation angles of position
+ *                      pos[t] (NULL = 0..n-1), then their sines; angle i = pos * theta^(-2i/head_dim), formed and
+ *                      evaluated in double.
+ *   slim_window_query: qt[Hkv*d] float = (1/(window*Hq)) sum over the window rows and over the query heads of
+ *                      each kv group of q_win[window, Hq, d]: Eq. (2)'s q_l with its head mean folded in.
+ *   slim_linear_rope:  out[m, n_heads, 128] = RoPE(a[m, k_in] . w^T + bias) (bias NULL = none), rotation in float
+ *                      on the unrounded projection, one rounding.  With qt != NULL (then n_heads = Hkv) also
+ *                      token_scores[m, n_heads] float = the rounded key of (token, head) dotted with qt's slice.
+ *                      bf16 only; head_dim 128; k_in % 64 == 0; lda, ldo (elements) % 8 == 0; all pointers 16-byte
+ *                      aligned.  UNSUPPORTED otherwise.
+ *   slim_score_blocks_from_token_scores: scores[nb] = max over the block's TokenUnits of the mean over the
+ *                      unit's tokens of sum_h token_scores[t, h]; equal to slim_score_blocks on the same keys up
+ *                      to the order of the float additions.
+ */
+int slim_rope_table(const int* pos, int n, int head_dim, float theta, float* table, void* stream);
+int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_heads, int head_dim, int dtype,
+                      float* qt, void* stream);
+int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m,
+                     int n_heads, int head_dim, int k_in, int ldo, int dtype, void* out, const float* qt,
+                     float* token_scores, void* stream);
+int slim_score_blocks_from_token_scores(const float* token_scores, int n_tokens, int n_kv_heads, int block,
+                                        int unit, float* scores, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * The pruned prefill layer: score -> select -> compact -> attention -> FFN on the kept tokens.
  */
 typedef struct slim_layer_shape {

@@ -24,6 +24,7 @@ EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
     "slim_kv_swap_workspace_bytes", "slim_kv_swap",
+    "slim_rope_table", "slim_window_query", "slim_linear_rope", "slim_score_blocks_from_token_scores",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
@@ -76,6 +77,10 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_kv_swap_workspace_bytes.restype = sz
     lib.slim_kv_swap_workspace_bytes.argtypes = [i, i]
     lib.slim_kv_swap.argtypes = [vp, i, i, C.c_double, vp, vp, vp, i, vp, vp, sz, vp, vp, sz, vp]
+    lib.slim_rope_table.argtypes = [vp, i, i, f, vp, vp]
+    lib.slim_window_query.argtypes = [vp, i, i, i, i, i, vp, vp]
+    lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp]
+    lib.slim_score_blocks_from_token_scores.argtypes = [vp, i, i, i, i, vp, vp]
     lib.slim_select_topk_blocks.argtypes = [vp, i, i, u, vp, vp]
     lib.slim_compact_tokens.argtypes = [vp, vp, vp, i, i, i, i, i, vp, vp, vp]
     lib.slim_prefill_attn.argtypes = [vp, vp, vp, i, i, i, i, f, i, vp, vp]
@@ -206,6 +211,51 @@ def slim_score_blocks_from_unit_keys(q_win: torch.Tensor, k_rep: torch.Tensor, n
                                                 d, block, unit, _dtype_code(q_win), _dev(scores, "scores"),
                                                 _dev(workspace, "workspace"), workspace.numel(), _stream()),
            "slim_score_blocks_from_unit_keys")
+    return scores
+
+
+def slim_rope_table(pos: torch.Tensor | None, n: int, head_dim: int, theta: float,
+                    device=None) -> torch.Tensor:
+    """table[n, head_dim] float32: cos then sin of the rotation angles of every position (None = 0..n-1)."""
+    lib = load_library()
+    dev = pos.device if pos is not None else device
+    table = torch.empty(n, head_dim, dtype=torch.float32, device=dev)
+    _check(lib.slim_rope_table(_dev(pos, "pos"), n, head_dim, theta, _dev(table, "table"), _stream()), "slim_rope_table")
+    return table
+
+
+def slim_window_query(q_win: torch.Tensor, n_kv_heads: int) -> torch.Tensor:
+    """q_win[w,Hq,d] -> qt[Hkv*d] float32: mean over the window, head mean of Eq. (2) folded into kv groups."""
+    lib = load_library()
+    w, Hq, d = q_win.shape
+    qt = torch.empty(n_kv_heads * d, dtype=torch.float32, device=q_win.device)
+    _check(lib.slim_window_query(_dev(q_win, "q_win"), w, Hq, n_kv_heads, d, _dtype_code(q_win), _dev(qt, "qt"), _stream()),
+           "slim_window_query")
+    return qt
+
+
+def slim_linear_rope(a: torch.Tensor, w: torch.Tensor, bias: torch.Tensor | None, table: torch.Tensor, head_dim: int,
+                     qt: torch.Tensor | None = None):
+    """RoPE(a . w^T + bias) as [m, heads, head_dim]; with qt also the per-(token, head) score partials [m, heads]."""
+    lib = load_library()
+    m, k_in = a.shape
+    n_out = w.shape[0]
+    heads = n_out // head_dim
+    out = torch.empty(m, heads, head_dim, dtype=a.dtype, device=a.device)
+    ts = torch.empty(m, heads, dtype=torch.float32, device=a.device) if qt is not None else None
+    _check(lib.slim_linear_rope(_dev(a, "a"), a.stride(0), _dev(w, "w"), _dev(bias, "bias"), _dev(table, "table"), m, heads,
+                                head_dim, k_in, n_out, _dtype_code(a), _dev(out, "out"), _dev(qt, "qt"), _dev(ts, "ts"),
+                                _stream()), "slim_linear_rope")
+    return (out, ts) if qt is not None else out
+
+
+def slim_score_blocks_from_token_scores(token_scores: torch.Tensor, block: int, unit: int) -> torch.Tensor:
+    """token_scores[N, Hkv] float32 -> scores[nb] float32 (unit means, block maximum)."""
+    lib = load_library()
+    N, H = token_scores.shape
+    scores = torch.empty(n_blocks(N, block), dtype=torch.float32, device=token_scores.device)
+    _check(lib.slim_score_blocks_from_token_scores(_dev(token_scores, "token_scores"), N, H, block, unit,
+                                                   _dev(scores, "scores"), _stream()), "slim_score_blocks_from_token_scores")
     return scores
 
 

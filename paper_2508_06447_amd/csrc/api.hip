@@ -22,7 +22,7 @@ static int forced_count(unsigned flags, int nb) {
 
 // Workspace layout of slim_pruned_layer (every region 256-byte aligned).
 struct LayerPlan {
-    size_t h, k_all, q_win, qt, scores, kc, vc, qc, o, o_all, act, total;
+    size_t h, k_all, q_win, qt, scores, table, tscore, kc, vc, qc, o, o_all, act, total;
     int nb, n_out;
     bool prune;
 };
@@ -41,6 +41,8 @@ static LayerPlan plan_layer(const slim_layer_shape* s, int N, int n_keep) {
     p.q_win = take((size_t)s->window * qd * es);
     p.qt = take(slim_score_blocks_workspace_bytes(s->n_kv_heads, s->head_dim));
     p.scores = take((size_t)p.nb * sizeof(float));
+    p.table = take((size_t)N * s->head_dim * sizeof(float));            // cos | sin of every token's rotation angles
+    p.tscore = take((size_t)N * s->n_kv_heads * sizeof(float));         // per-(token, kv head) score partials
     const bool after = p.prune && s->placement == SLIM_PRUNE_AFTER_ATTENTION;
     const size_t n_att = after ? (size_t)N : (size_t)p.n_out;    // rows that go through attention
     p.kc = (p.prune && !after) ? take((size_t)p.n_out * kv * es) : p.k_all;   // compacted keys
@@ -140,6 +142,39 @@ int slim_score_blocks_from_unit_keys(const void* q_win, const float* k_rep, int 
     if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
     return launch_score_from_unit_keys(q_win, k_rep, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit,
                                        dtype, scores, (float*)workspace, (hipStream_t)stream);
+}
+
+int slim_rope_table(const int* pos, int n, int head_dim, float theta, float* table, void* stream) {
+    if (!table || n < 1 || head_dim < 2 || head_dim % 2 != 0 || head_dim > 256 || !(theta > 0.f)) return SLIM_INVALID_ARG;
+    return launch_rope_table(pos, 0, n, head_dim, theta, table, (hipStream_t)stream);
+}
+
+int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_heads, int head_dim, int dtype, float* qt,
+                      void* stream) {
+    if (!q_win || !qt || window < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || n_q_heads % n_kv_heads != 0)
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    return launch_window_query(q_win, window, n_q_heads, n_kv_heads, head_dim, dtype, qt, (hipStream_t)stream);
+}
+
+int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m, int n_heads,
+                     int head_dim, int k_in, int ldo, int dtype, void* out, const float* qt, float* token_scores,
+                     void* stream) {
+    if (!a || !w || !table || !out || m < 1 || n_heads < 1 || head_dim < 1 || k_in < 1 || lda < k_in ||
+        ldo < n_heads * head_dim || (qt && !token_scores))
+        return SLIM_INVALID_ARG;
+    if (dtype != SLIM_BF16 || head_dim != 128 || k_in % 64 != 0 || lda % 8 != 0 || ldo % 8 != 0 || !aligned16(a) ||
+        !aligned16(w) || !aligned16(table) || !aligned16(out) || (bias && !aligned16(bias)) || (qt && !aligned16(qt)))
+        return SLIM_UNSUPPORTED;
+    return launch_linear_rope(a, lda, w, bias, table, qt, qt ? token_scores : nullptr, m, n_heads, k_in, ldo, out,
+                              (hipStream_t)stream);
+}
+
+int slim_score_blocks_from_token_scores(const float* token_scores, int n_tokens, int n_kv_heads, int block, int unit,
+                                        float* scores, void* stream) {
+    if (!token_scores || !scores || n_tokens < 1 || n_kv_heads < 1 || block < 1 || unit < 1 || unit > block)
+        return SLIM_INVALID_ARG;
+    return launch_token_score_blocks(token_scores, n_tokens, n_kv_heads, block, unit, scores, (hipStream_t)stream);
 }
 
 size_t slim_kv_swap_workspace_bytes(int n_blocks, int n_slots) {
@@ -276,26 +311,43 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     float* qt = (float*)(ws + p.qt);
 #define SLIM_TRY(call) do { rc = (call); if (rc) return rc; } while (0)
 
-    // Key states of every incoming token (both paths need them).
+    // Query/Key projection + RoPE at the given positions.  bf16 heads of 128: one kernel, the rotation (and, for the
+    // keys of a pruning layer with TokenUnit scoring, the per-token dot with the window query) in the GEMM epilogue,
+    // so the projected states are written once and never re-read before attention.  Otherwise two kernels.
+    float* table = (float*)(ws + p.table);
+    float* tscore = (float*)(ws + p.tscore);
+    const bool fused = dt == SLIM_BF16 && d == 128 && Hd % 64 == 0;
+    const bool fused_score = fused && p.prune && s->scoring == 0;
+    auto project_rope = [&](const void* a, const void* wmat, const void* bias, const int* pos_, int pos0, int m, int heads,
+                            void* out, const float* tab, const float* qt_, float* ts) -> int {
+        if (fused) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, m, heads, Hd, heads * d, out, st);
+        int r = launch_linear(a, Hd, wmat, nullptr, nullptr, bias, m, heads * d, Hd, heads * d, dt, out, st);
+        return r ? r : launch_rope(out, pos_, pos0, m, heads, d, s->rope_theta, dt, st);
+    };
+    auto block_scores = [&](const void* q_window, int w_eff, float* scores) -> int {
+        if (fused_score) return launch_token_score_blocks(tscore, N, Hkv, s->block, s->unit, scores, st);
+        return launch_score(q_window, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st);
+    };
+
     SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
-    SLIM_TRY(launch_linear(h, Hd, w->wk, nullptr, nullptr, w->bk, N, kvd, Hd, kvd, dt, k_all, st));
-    SLIM_TRY(launch_rope(k_all, pos_in, 0, N, Hkv, d, s->rope_theta, dt, st));
+    if (fused) SLIM_TRY(launch_rope_table(pos_in, 0, N, d, s->rope_theta, table, st));
 
     const void* resid = x_in;          // residual stream entering the attention branch
     const int* pos = pos_in;           // positions of the rows that continue
     const int n = p.n_out;
+    const int w_eff = s->window < N ? s->window : N;
     const bool after = p.prune && s->placement == SLIM_PRUNE_AFTER_ATTENTION;
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
-        SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, w->bq, N, qd, Hd, qd, dt, qc, st));
-        SLIM_TRY(launch_rope(qc, pos_in, 0, N, Hq, d, s->rope_theta, dt, st));
+        SLIM_TRY(project_rope(h, w->wq, w->bq, pos_in, 0, N, Hq, qc, table, nullptr, nullptr));
+        const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
+        if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
+        SLIM_TRY(project_rope(h, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
         SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, w->bv, N, kvd, Hd, kvd, dt, vc, st));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
-        const int w_eff = s->window < N ? s->window : N;
-        const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
-        SLIM_TRY(launch_score(q_last, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st));
+        SLIM_TRY(block_scores(q_last, w_eff, scores));
         SLIM_TRY(launch_select(scores, p.nb, n_keep, s->flags, kept_blocks_out, st));
         // Residual rows + positions into x_out / pos_out, attention output rows into o.
         SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
@@ -303,13 +355,17 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         resid = x_out;
     } else {
     if (p.prune) {
-        // Query states of the local window (last w_eff rows), block scores, selection.
-        const int w_eff = s->window < N ? s->window : N;
+        // Query states of the local window (last w_eff rows) and their head-group-summed mean.
         const unsigned char* h_win = (const unsigned char*)h + (size_t)(N - w_eff) * Hd * es;
-        SLIM_TRY(launch_linear(h_win, Hd, w->wq, nullptr, nullptr, w->bq, w_eff, qd, Hd, qd, dt, q_win, st));
-        SLIM_TRY(launch_rope(q_win, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, d, s->rope_theta, dt, st));
+        SLIM_TRY(project_rope(h_win, w->wq, w->bq, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win,
+                              table + (size_t)(N - w_eff) * d, nullptr, nullptr));
+        if (fused_score) SLIM_TRY(launch_window_query(q_win, w_eff, Hq, Hkv, d, dt, qt, st));
+    }
+    // Key states of every incoming token.
+    SLIM_TRY(project_rope(h, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+    if (p.prune) {
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
-        SLIM_TRY(launch_score(q_win, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st));
+        SLIM_TRY(block_scores(q_win, w_eff, scores));
         SLIM_TRY(launch_select(scores, p.nb, n_keep, s->flags, kept_blocks_out, st));
         // Hidden rows + positions into x_out / pos_out, keys into kc.
         SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
@@ -317,14 +373,14 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         SLIM_TRY(launch_rmsnorm(x_out, w->g_attn, n, Hd, s->rms_eps, dt, h, st));
         resid = x_out;
         pos = pos_out;
+        if (fused) SLIM_TRY(launch_rope_table(pos_out, 0, n, d, s->rope_theta, table, st));
     } else {
         if (kept_blocks_out) SLIM_TRY(launch_select(nullptr, p.nb, p.nb, 0, kept_blocks_out, st));
         if (pos_out) SLIM_TRY(launch_positions(pos_in, pos_out, N, st));
     }
 
     // Q, V of the rows that continue; RoPE on Q at the original positions.
-    SLIM_TRY(launch_linear(h, Hd, w->wq, nullptr, nullptr, w->bq, n, qd, Hd, qd, dt, qc, st));
-    SLIM_TRY(launch_rope(qc, pos, 0, n, Hq, d, s->rope_theta, dt, st));
+    SLIM_TRY(project_rope(h, w->wq, w->bq, pos, 0, n, Hq, qc, table, nullptr, nullptr));
     SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, w->bv, n, kvd, Hd, kvd, dt, vc, st));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
     }

@@ -1,7 +1,8 @@
 // Dense projections of the layer ("QKV Generation", output projection and FFN of Fig. 2):
 //   out[m, n] = sum_k a[m, k] * w[n, k]            (both operands contiguous along k)
-// with four epilogues: plain, + bias[n] (Q/K/V projections of models that have one), + residual, and
-// SwiGLU (two weight matrices, silu(gate) * up).
+// with five epilogues: plain, + bias[n] (Q/K/V projections of models that have one), + residual,
+// SwiGLU (two weight matrices, silu(gate) * up), and RoPE (+ bias, + per-token score partials) for the
+// Query/Key projections of 128-wide heads.
 //
 // bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulation.  The weight tile is the MFMA "A" operand
 // and the activation tile the "B" operand, so a lane ends up with 4 consecutive output features of
@@ -23,7 +24,15 @@
 
 namespace slim {
 
-enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_BIAS = 3 };   // EPI_BIAS: R is a bias vector [N]
+enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_BIAS = 3, EPI_ROPE = 4 };
+// EPI_BIAS: R is a bias vector [N].  EPI_ROPE: R is a bias vector or null, the rest comes in a RopeEpi.
+
+// Extra operands of the RoPE epilogue (heads of 128 features, one head per wave tile).
+struct RopeEpi {
+    const float* table = nullptr;        // [M][128]: cos of the 64 rotation angles of the token, then their sin
+    const float* qt = nullptr;           // [N] float or null: head-group-summed window query (Eq. 2 by linearity)
+    float* token_scores = nullptr;       // [M][N/128]: rotated, rounded key of (token, head) dotted with its part of qt
+};
 
 constexpr int BK = 64;                                   // k-depth of an LDS tile (8 chunks of 16 bytes)
 
@@ -149,6 +158,81 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
     }
 }
 
+// RoPE epilogue.  The wave tile is 128 features wide and starts at a multiple of 128, so it is one head and the
+// rotate-half partner of feature f < 64 (sub-tile i = 0, 1) is the same accumulator element of sub-tile i + 2 in
+// the same lane: the rotation needs no exchange.  out[f] = x[f] cos - x[f+64] sin, out[f+64] = x[f+64] cos +
+// x[f] sin with the angle of (token, f) from the table; x includes the bias.  One rounding to bf16.  With a
+// window query, the rounded values are dotted with it (64 of the head's features per lane, the other half in
+// lane ^ 32) and the per-(token, head) partial goes to token_scores.
+template <int TA>
+__device__ __forceinline__ void store_tile_rope(f32x16 (&acc)[1][4][TA], const bf16_t* bias, bf16_t* C, int ldo, int M,
+                                                int N, int mw, int nw, int lane, unsigned char* region,
+                                                const RopeEpi& re) {
+    constexpr int TW = 4, CPR = TW * 4, RB = TW * 64, ROWS = TA * 32, RPI = 64 / CPR;
+    if (nw >= N) return;                                 // wave-uniform: no head here (N is a multiple of 128)
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int rrow = lane / CPR, rchunk = lane % CPR;
+    auto slot = [&](int row, int chunk) { return row * RB + ((chunk ^ (row & (CPR - 1))) << 4); };
+    const bool score = re.qt != nullptr;
+    float dot[TA];
+#pragma unroll
+    for (int j = 0; j < TA; ++j) dot[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+            const int f = i * 32 + 8 * vg + 4 * hh;      // rotation index of element e = 0
+            float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
+            if (bias) {
+                const uint2 r1 = *reinterpret_cast<const uint2*>(bias + nw + f);
+                const uint2 r2 = *reinterpret_cast<const uint2*>(bias + nw + 64 + f);
+                b1[0] = lo_bf16(r1.x); b1[1] = hi_bf16(r1.x); b1[2] = lo_bf16(r1.y); b1[3] = hi_bf16(r1.y);
+                b2[0] = lo_bf16(r2.x); b2[1] = hi_bf16(r2.x); b2[2] = lo_bf16(r2.y); b2[3] = hi_bf16(r2.y);
+            }
+            float4 q1 = make_float4(0.f, 0.f, 0.f, 0.f), q2 = q1;
+            if (score) {
+                q1 = *reinterpret_cast<const float4*>(re.qt + nw + f);
+                q2 = *reinterpret_cast<const float4*>(re.qt + nw + 64 + f);
+            }
+#pragma unroll
+            for (int j = 0; j < TA; ++j) {
+                const int row = j * 32 + l32;
+                const float* trow = re.table + (size_t)min(mw + row, M - 1) * 128 + f;
+                const float4 c4 = *reinterpret_cast<const float4*>(trow);
+                const float4 s4 = *reinterpret_cast<const float4*>(trow + 64);
+                const float c[4] = {c4.x, c4.y, c4.z, c4.w}, sn[4] = {s4.x, s4.y, s4.z, s4.w};
+                float o1[4], o2[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float x1 = acc[0][i][j][vg * 4 + e] + b1[e], x2 = acc[0][i + 2][j][vg * 4 + e] + b2[e];
+                    o1[e] = x1 * c[e] - x2 * sn[e];
+                    o2[e] = x2 * c[e] + x1 * sn[e];
+                }
+                const uint2 p1 = make_uint2(pack_bf16x2(o1[0], o1[1]), pack_bf16x2(o1[2], o1[3]));
+                const uint2 p2 = make_uint2(pack_bf16x2(o2[0], o2[1]), pack_bf16x2(o2[2], o2[3]));
+                *reinterpret_cast<uint2*>(region + slot(row, i * 4 + vg) + hh * 8) = p1;
+                *reinterpret_cast<uint2*>(region + slot(row, (i + 2) * 4 + vg) + hh * 8) = p2;
+                if (score)
+                    dot[j] += lo_bf16(p1.x) * q1.x + hi_bf16(p1.x) * q1.y + lo_bf16(p1.y) * q1.z + hi_bf16(p1.y) * q1.w +
+                              lo_bf16(p2.x) * q2.x + hi_bf16(p2.x) * q2.y + lo_bf16(p2.y) * q2.z + hi_bf16(p2.y) * q2.w;
+            }
+        }
+    if (score) {
+#pragma unroll
+        for (int j = 0; j < TA; ++j) {
+            const float tot = dot[j] + __shfl_xor(dot[j], 32, 64);
+            const int m = mw + j * 32 + l32;
+            if (hh == 0 && m < M) re.token_scores[(size_t)m * (N >> 7) + (nw >> 7)] = tot;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ROWS / RPI; ++it) {
+        const int row = it * RPI + rrow, m = mw + row, n = nw + rchunk * 8;
+        const uint4 v = *reinterpret_cast<const uint4*>(region + slot(row, rchunk));
+        if (m < M && n < N) *reinterpret_cast<uint4*>(C + (size_t)m * ldo + n) = v;
+    }
+}
+
 // Workgroup -> output tile.  Workgroup ids are dealt round-robin to the 8 XCDs, so each XCD gets a
 // contiguous run of logical tiles; inside the run, bands of GM token-tiles are walked feature-tile by
 // feature-tile, so the workgroups resident on one XCD share few distinct operand tiles in its L2.
@@ -171,8 +255,9 @@ __device__ __forceinline__ void tile_of_workgroup(int L, bool xcd_runs, int tile
 template <int TW, int TA, int WGN, int WGM, int EPI>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
                                           const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
-                                          int N, int K, int m0, int n0, unsigned char* lds) {
+                                          int N, int K, int m0, int n0, unsigned char* lds, const RopeEpi& re) {
     static_assert(WGN * WGM == 8, "8 waves");
+    static_assert(EPI != EPI_ROPE || TW == 4, "the RoPE epilogue needs one 128-wide head per wave");
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM, WROWS = BN * NW;
     constexpr int STAGE = (WROWS + BM) * BK * 2;
@@ -298,11 +383,16 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
     workgroup_barrier();
     const bool wide = (N % 8 == 0) && (ldo % 8 == 0) && (((uintptr_t)C & 15) == 0) &&
                       (EPI != EPI_RESIDUAL || ((uintptr_t)R & 15) == 0) && (EPI != EPI_BIAS || ((uintptr_t)R & 7) == 0);
-    if (wide)
-        store_tile_via_lds<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
-                                        lds + wave * (TA * 32 * TW * 64));
-    else
-        store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+    if constexpr (EPI == EPI_ROPE) {                     // the launcher has checked what `wide` checks
+        store_tile_rope<TA>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+                            lds + wave * (TA * 32 * TW * 64), re);
+    } else {
+        if (wide)
+            store_tile_via_lds<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+                                            lds + wave * (TA * 32 * TW * 64));
+        else
+            store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+    }
 }
 
 // Main kernel: every workgroup computes one tile of the same shape.
@@ -310,20 +400,25 @@ template <int TW, int TA, int WGN, int WGM, int EPI>
 __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
                                                         const bf16_t* __restrict__ W0,
                                                         const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
-                                                        int ldo, int M, int N, int K, int tiles_m, int tiles_n) {
+                                                        int ldo, int M, int N, int K, int tiles_m, int tiles_n,
+                                                        RopeEpi re) {
     extern __shared__ __align__(16) unsigned char lds[];
     int tm, tn;
     tile_of_workgroup(blockIdx.x, true, tiles_m, tiles_n, tm, tn);
-    gemm_tile<TW, TA, WGN, WGM, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds);
+    gemm_tile<TW, TA, WGN, WGM, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds, re);
 }
 
 // Shapes of the two-size launch: 256-token tiles for the first big_tiles_m token-tiles, 128-token tiles
 // (same feature width) for the rest.  Wave tiles: plain 64 tokens x 128 features (big), 64 x 64 (small);
-// SwiGLU 64 tokens x 64 gate + 64 up features (big), 64 x 32 + 32 (small).
+// SwiGLU 64 tokens x 64 gate + 64 up features (big), 64 x 32 + 32 (small); RoPE keeps 128 features (one head)
+// per wave in the small tiles too: 32 tokens x 128 features.
 template <int EPI> struct TileShapes {
-    static constexpr int TW_BIG = EPI == EPI_SWIGLU ? 2 : 4, TW_SMALL = EPI == EPI_SWIGLU ? 1 : 2;
-    static constexpr int BN = 32 * TW_BIG * 2;           // = 32 * TW_SMALL * 4
-    static constexpr int BM_BIG = 256, BM_SMALL = 128;
+    static constexpr int TW_BIG = EPI == EPI_SWIGLU ? 2 : 4;
+    static constexpr int TW_SMALL = EPI == EPI_SWIGLU ? 1 : (EPI == EPI_ROPE ? 4 : 2);
+    static constexpr int TA_SMALL = EPI == EPI_ROPE ? 1 : 2, WGN_SMALL = EPI == EPI_ROPE ? 2 : 4, WGM_SMALL = 8 / WGN_SMALL;
+    static constexpr int BN = 32 * TW_BIG * 2;           // = 32 * TW_SMALL * WGN_SMALL
+    static constexpr int BM_BIG = 256, BM_SMALL = 32 * TA_SMALL * WGM_SMALL;
+    static_assert(BN == 32 * TW_SMALL * WGN_SMALL && BM_SMALL == 128, "both tile sizes share the feature width");
 };
 
 // Two tile sizes in one launch.  Workgroups are started in id order, so the 256-token tiles run first
@@ -334,18 +429,19 @@ __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* _
                                                                  const bf16_t* __restrict__ W0,
                                                                  const bf16_t* __restrict__ W1, const bf16_t* R,
                                                                  bf16_t* C, int ldo, int M, int N, int K,
-                                                                 int big_tiles_m, int small_tiles_m, int tiles_n) {
+                                                                 int big_tiles_m, int small_tiles_m, int tiles_n,
+                                                                 RopeEpi re) {
     using S = TileShapes<EPI>;
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_big = big_tiles_m * tiles_n;
     int tm, tn;
     if ((int)blockIdx.x < n_big) {
         tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
-        gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds);
+        gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
     } else {
         tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
-        gemm_tile<S::TW_SMALL, 2, 4, 2, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K,
-                                             big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds);
+        gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI>(
+            A, lda, W0, W1, R, C, ldo, M, N, K, big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, re);
     }
 }
 
@@ -451,22 +547,26 @@ __global__ void __launch_bounds__(256) gemm_bf16_generic_kernel(const bf16_t* __
 
 template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC>
 static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
-                       int ldo, int M, int N, int K, hipStream_t st) {
+                       int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM;
     constexpr size_t smem = 2 * (size_t)(BN * NW + BM) * BK * 2;
-    void (*kern)(const bf16_t*, int, const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, int, int, int, int, int, int);
-    if constexpr (GENERIC) kern = gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>;
-    else kern = gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
+    const void* kern;
+    if constexpr (GENERIC) kern = (const void*)gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>;
+    else kern = (const void*)gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
     static bool attr_done = false;                       // raising the LDS limit is per function, once
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return set_hip_error(e);
         attr_done = true;
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem, st, A, lda, W0, W1, R, C, ldo, M, N,
-                       K, tiles_m, tiles_n);
+    if constexpr (GENERIC)
+        hipLaunchKernelGGL((gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM),
+                           smem, st, A, lda, W0, W1, R, C, ldo, M, N, K, tiles_m, tiles_n);
+    else
+        hipLaunchKernelGGL((gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem,
+                           st, A, lda, W0, W1, R, C, ldo, M, N, K, tiles_m, tiles_n, re);
     return check_launch();
 }
 
@@ -520,7 +620,8 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
 
 template <int EPI>
 static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
-                           int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st) {
+                           int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st,
+                           const RopeEpi& re = RopeEpi()) {
     using S = TileShapes<EPI>;
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
@@ -534,7 +635,7 @@ static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf1
     const int tiles_n = (N + S::BN - 1) / S::BN;
     const int small_tiles_m = (M - big_tiles_m * S::BM_BIG + S::BM_SMALL - 1) / S::BM_SMALL;
     hipLaunchKernelGGL(kern, dim3((big_tiles_m + small_tiles_m) * tiles_n), dim3(512), smem, st, A, lda, W0, W1, R, C,
-                       ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n);
+                       ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n, re);
     return check_launch();
 }
 
@@ -615,6 +716,21 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
             C[(size_t)m * ldo + n] = o;
         }
     }
+}
+
+// Query/Key projection with the RoPE epilogue (bf16, heads of 128, k_in a multiple of 64; checked by the caller).
+int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, const float* qt,
+                       float* token_scores, int m, int n_heads, int k_in, int ldo, void* out, hipStream_t st) {
+    RopeEpi re;
+    re.table = table;
+    re.qt = qt;
+    re.token_scores = token_scores;
+    const bf16_t *A = (const bf16_t*)a, *W = (const bf16_t*)w, *B = (const bf16_t*)bias;
+    const int N = n_heads * 128;
+    if (m <= 128) return launch_bf16<4, 1, 2, 4, EPI_ROPE, false>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, N, k_in, st, re);
+    const int tiles_n = (N + TileShapes<EPI_ROPE>::BN - 1) / TileShapes<EPI_ROPE>::BN;
+    return launch_two_size<EPI_ROPE>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, N, k_in,
+                                     plan_big_tiles(m, tiles_n, cu_count(), 0.5), st, re);
 }
 
 // At most one of w1 (SwiGLU), residual and bias is set.

@@ -95,4 +95,26 @@ int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float th
     return check_launch();
 }
 
+// cos / sin table for the RoPE epilogue of the projections: table[t][0..half) = cos(pos[t] * inv_freq[i]),
+// table[t][half..2*half) = sin, angles and sincos in double as in rope_kernel, rounded to float.
+__global__ void __launch_bounds__(256) rope_table_kernel(const int* __restrict__ pos, int pos0, int n, int half,
+                                                         RopeFreq fr, float* __restrict__ table) {
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int t = idx / half, i = idx - t * half;
+    if (t >= n) return;
+    double sn, cs;
+    sincos((double)(pos ? pos[t] : pos0 + t) * fr.inv_freq[i], &sn, &cs);
+    table[(size_t)t * 2 * half + i] = (float)cs;
+    table[(size_t)t * 2 * half + half + i] = (float)sn;
+}
+
+int launch_rope_table(const int* pos, int pos0, int n, int d, float theta, float* table, hipStream_t st) {
+    RopeFreq fr;
+    for (int i = 0; i < d / 2; ++i) fr.inv_freq[i] = pow((double)theta, -2.0 * (double)i / (double)d);
+    const long long threads = (long long)n * (d / 2);
+    hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, pos, pos0, n, d / 2, fr,
+                       table);
+    return check_launch();
+}
+
 }  // namespace slim

@@ -250,6 +250,46 @@ __global__ void __launch_bounds__(1024) unit_score_kernel(const float* __restric
     }
 }
 
+// Block scores from per-token partial scores (the K projection's RoPE epilogue leaves, for every token and kv
+// head, the dot of the token's key with that head's part of the window query).  Summing the heads gives
+// k_t . qt; by linearity the mean of those over a TokenUnit is Eq. (1) dotted as in Eq. (2), and the block takes
+// the maximum over its units.  One workgroup per block, one thread per unit (strided), fixed summation order.
+__global__ void __launch_bounds__(256) token_score_blocks_kernel(const float* __restrict__ ts, int N, int H, int block,
+                                                                 int unit, float* __restrict__ scores) {
+    __shared__ float wmax[4];
+    const int j = blockIdx.x, b0 = j * block, b1 = min(b0 + block, N);
+    float best = -INFINITY;
+    for (int u0 = b0 + threadIdx.x * unit; u0 < b1; u0 += 256 * unit) {
+        const int u1 = min(min(u0 + unit, b0 + block), b1);
+        float acc = 0.f;
+        for (int t = u0; t < u1; ++t) {
+            float s = 0.f;
+            for (int h = 0; h < H; ++h) s += ts[(size_t)t * H + h];
+            acc += s;
+        }
+        best = fmaxf(best, acc / (float)(u1 - u0));
+    }
+    best = wave_max(best);
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) scores[j] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+}
+
+int launch_token_score_blocks(const float* token_scores, int N, int H, int block, int unit, float* scores, hipStream_t st) {
+    const int nb = (N + block - 1) / block;
+    hipLaunchKernelGGL(token_score_blocks_kernel, dim3(nb), dim3(256), 0, st, token_scores, N, H, block, unit, scores);
+    return check_launch();
+}
+
+int launch_window_query(const void* q_win, int w, int Hq, int Hkv, int d, int dtype, float* qtilde, hipStream_t st) {
+    dim3 g1((Hkv * d + 63) / 64);
+    if (dtype == SLIM_BF16)
+        hipLaunchKernelGGL(window_query_kernel<bf16_t>, g1, dim3(1024), 0, st, (const bf16_t*)q_win, w, Hq, Hkv, d, qtilde);
+    else
+        hipLaunchKernelGGL(window_query_kernel<float>, g1, dim3(1024), 0, st, (const float*)q_win, w, Hq, Hkv, d, qtilde);
+    return check_launch();
+}
+
 int launch_unit_keys(const void* k, int N, int E, int block, int unit, int dtype, float* k_rep, hipStream_t st) {
     const int nb = (N + block - 1) / block, M = (block + unit - 1) / unit, n_units = nb * M;
     dim3 grid((n_units + 3) / 4);

@@ -41,7 +41,7 @@ def sample_rows(n, block, count=48, seed=0):
     return np.array(sorted(rows))
 
 
-def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", placement="before"):
+def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", placement="before", score_floor=False):
     """Runs the GPU layer and the oracle on one workload; returns the numbers for the log."""
     x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
     n_keep = wl.n_keep
@@ -65,7 +65,13 @@ def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", p
     print(f"{label}: scores max-abs {sc_err:.2e}; kept {len(kept_gpu)} blocks, {band} in the 1e-3 band, "
           f"{ndiff} differ; z max-abs {mx:.3e} mean-abs {mean:.3e} (bf16-rounding oracle: {fl_max:.3e} / "
           f"{fl_mean:.3e}); |z| max {np.abs(z_ref).max():.2f}", flush=True)
-    return dict(sc_err=sc_err, sc_scale=float(np.abs(sc_ref).max()), mx=mx, mean=mean, fl_max=fl_max, fl_mean=fl_mean)
+    out = dict(sc_err=sc_err, sc_scale=float(np.abs(sc_ref).max()), mx=mx, mean=mean, fl_max=fl_max, fl_mean=fl_mean)
+    if score_floor:
+        # what rounding the oracle's own h, K and window Q to bf16 does to its scores (one draw of that noise)
+        sc_rounded, _ = so.layer_scores(s, ow, xs, pos.numpy(), rounding="bf16")
+        out["sc_floor"] = float(np.abs(sc_rounded - sc_ref).max())
+        print(f"{label}: |scores| max {out['sc_scale']:.2f}, bf16-rounding oracle scores max-abs {out['sc_floor']:.2e}", flush=True)
+    return out
 
 
 def test_cfg1_fp32_full(slim):
@@ -158,8 +164,10 @@ def test_reduced_bf16_keep_all_and_prefix_property(slim):
 def test_reduced_qwen_shaped_layer_full_output(slim):
     """Second model family (28 query / 4 kv heads, hidden 3584, FFN 18944, Q/K/V biases, theta 1e6)."""
     wl = inputs.scaled(inputs.WORKLOADS["cfg6"], seq=1000, x_kind="planted", planted=10)
-    r = check_layer(slim, wl, np.float64, label="qwen-shaped seq 1000 keep 0.375")
-    assert r["sc_err"] < 4e-3                             # biases of size 0.5 make the scores larger
+    r = check_layer(slim, wl, np.float64, label="qwen-shaped seq 1000 keep 0.375", score_floor=True)
+    # biases of size 0.5 make the Query/Key states and the scores several times larger than in the LLaMA-shaped
+    # workloads, and with them the bf16 rounding of the states: the gate follows that rounding
+    assert r["sc_err"] < max(2e-3, 3.0 * r["sc_floor"])
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
 
 
@@ -167,6 +175,6 @@ def test_reduced_qwen_shaped_layer_full_output(slim):
 def test_full_size_workloads_sampled_rows(slim, name):
     wl = inputs.WORKLOADS[name]
     print(f"{name}: N={wl.seq} nb={wl.n_blocks} n_keep={wl.n_keep} n'={wl.n_kept_tokens}", flush=True)
-    r = check_layer(slim, wl, np.float32, rows_count=40, label=name)
-    assert r["sc_err"] < (4e-3 if wl.qkv_bias else 2e-3)  # biases of size 0.5 make the scores larger
+    r = check_layer(slim, wl, np.float32, rows_count=40, label=name, score_floor=wl.qkv_bias)
+    assert r["sc_err"] < (max(2e-3, 3.0 * r["sc_floor"]) if wl.qkv_bias else 2e-3)   # see the reduced Qwen-shaped test
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])

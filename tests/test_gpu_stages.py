@@ -208,6 +208,88 @@ def test_linear_with_bias(slim, m, n, k, dtype):
                                atol=rel * np.abs(want).max())
 
 
+# ------------------------------------------------------------- projections with the RoPE / score epilogue
+def test_rope_table_matches_float64_angles(slim):
+    g = np.random.default_rng(3)
+    pos = np.sort(g.choice(131072, 300, replace=False)).astype(np.int32)
+    pos[-1] = 131071
+    for theta in (500000.0, 1000000.0):
+        t = slim.slim_rope_table(dev(torch.from_numpy(pos)), 300, 128, theta)
+        c, s = so.rope_cos_sin(pos, 128, theta, np.float64)
+        np.testing.assert_allclose(f64(t)[:, :64], c, rtol=0, atol=6e-8)      # float rounding of values in [-1, 1]
+        np.testing.assert_allclose(f64(t)[:, 64:], s, rtol=0, atol=6e-8)
+    t0 = slim.slim_rope_table(None, 50, 128, 500000.0, device="cuda")
+    c, s = so.rope_cos_sin(np.arange(50), 128, 500000.0, np.float64)
+    np.testing.assert_allclose(f64(t0), np.concatenate([c, s], axis=1), rtol=0, atol=6e-8)
+
+
+@pytest.mark.parametrize("m,heads,k,with_bias", [
+    (64, 32, 4096, False),          # the window projection: one 128-token tile
+    (1300, 8, 256, True),           # 256- and 128-token tiles, ragged last tile, bias
+    (700, 3, 192, True),            # odd number of heads: the last 256-feature tile is half empty
+    (3000, 4, 64, False),
+    (1, 1, 64, True),
+])
+def test_linear_rope_epilogue_and_token_scores(slim, m, heads, k, with_bias):
+    print(f"linear+rope m={m} heads={heads} k={k} bias={with_bias}", flush=True)
+    bf, d = torch.bfloat16, 128
+    g = np.random.default_rng(m + heads)
+    a, w = rand((m, k), bf, 1), rand((heads * d, k), bf, 2, 0.05)
+    b = rand((heads * d,), bf, 3, 1.0) if with_bias else None
+    pos = np.sort(g.choice(40000, m, replace=False)).astype(np.int32)
+    table = slim.slim_rope_table(dev(torch.from_numpy(pos)), m, d, 500000.0)
+    want = so.project_heads(f64(a), f64(w), heads, d, pos, 500000.0, True, None, None if b is None else f64(b))
+    got = slim.slim_linear_rope(dev(a), dev(w), None if b is None else dev(b), table, d)
+    rel = 2.0 ** -8
+    np.testing.assert_allclose(f64(got), want, rtol=rel, atol=rel * np.abs(want).max())
+    # the two-kernel route (projection rounded to bf16, then rotated) agrees to bf16 rounding
+    two = slim.slim_linear(dev(a), dev(w)) if b is None else slim.slim_linear_bias(dev(a), dev(w), dev(b))
+    two = slim.slim_rope(two.view(m, heads, d), dev(torch.from_numpy(pos)), 500000.0)
+    np.testing.assert_allclose(f64(two), want, rtol=2 * rel, atol=2 * rel * np.abs(want).max())
+    # with a window query: same keys bit for bit, plus per-(token, head) dots of the stored keys with qt
+    qt = torch.from_numpy(g.standard_normal(heads * d).astype(np.float32))
+    got2, ts = slim.slim_linear_rope(dev(a), dev(w), None if b is None else dev(b), table, d, qt=dev(qt))
+    assert torch.equal(got2, got)
+    want_ts = np.einsum("mhd,hd->mh", f64(got), f64(qt).reshape(heads, d))
+    np.testing.assert_allclose(f64(ts), want_ts, rtol=0, atol=2e-5 * max(1.0, np.abs(want_ts).max()))
+
+
+@pytest.mark.parametrize("N,block,unit,w,Hq,Hkv,hidden", [
+    (1024, 64, 8, 64, 32, 8, 512), (1000, 64, 8, 4, 8, 2, 256), (1003, 64, 8, 16, 28, 4, 256), (333, 32, 5, 7, 4, 4, 128),
+])
+def test_key_first_pipeline_scores_match_oracle(slim, N, block, unit, w, Hq, Hkv, hidden):
+    """Window query -> K projection with RoPE and score partials -> block scores, against Eq. 1-2 of the oracle
+    on the oracle's own projections, and against slim_score_blocks on the same stored keys."""
+    print(f"key-first scores N={N} block={block} unit={unit} w={w} Hq={Hq} Hkv={Hkv}", flush=True)
+    bf, d, theta = torch.bfloat16, 128, 500000.0
+    h = rand((N, hidden), bf, 5)
+    wq, wk = rand((Hq * d, hidden), bf, 6, 0.05), rand((Hkv * d, hidden), bf, 7, 0.05)
+    pos = np.arange(N, dtype=np.int32) * 3
+    table = slim.slim_rope_table(dev(torch.from_numpy(pos)), N, d, theta)
+    q_win = slim.slim_linear_rope(dev(h[N - w:]), dev(wq), None, table[N - w:], d)
+    qt = slim.slim_window_query(q_win, Hkv)
+    k, ts = slim.slim_linear_rope(dev(h), dev(wk), None, table, d, qt=qt)
+    scores = slim.slim_score_blocks_from_token_scores(ts, block, unit)
+    # qt against its definition on the GPU's window states
+    ql = so.window_query(f64(q_win))                                         # [Hq, d]
+    want_qt = ql.reshape(Hkv, Hq // Hkv, d).sum(axis=1).reshape(-1) / Hq
+    np.testing.assert_allclose(f64(qt), want_qt, rtol=0, atol=1e-6 * max(1.0, np.abs(want_qt).max()))
+    # scores: Eq. 1-2 on the stored (rounded) states
+    want = so.block_scores(f64(q_win), f64(k), block, unit)
+    scale = max(1.0, float(np.abs(want).max()))
+    assert np.abs(f64(scores) - want).max() < 2e-5 * scale
+    direct = slim.slim_score_blocks(q_win, k, block, unit)
+    assert (scores - direct).abs().max().item() < 2e-5 * scale
+    # and against the exact pipeline (float64 projections): bf16 rounding of the states only
+    qe = so.project_heads(f64(h[N - w:]), f64(wq), Hq, d, pos[N - w:], theta, True)
+    ke = so.project_heads(f64(h), f64(wk), Hkv, d, pos, theta, True)
+    exact = so.block_scores(qe, ke, block, unit)
+    qr = so.project_heads(f64(h[N - w:]), f64(wq), Hq, d, pos[N - w:], theta, True, "bf16")
+    kr = so.project_heads(f64(h), f64(wk), Hkv, d, pos, theta, True, "bf16")
+    floor = np.abs(so.block_scores(qr, kr, block, unit) - exact).max()      # what rounding the states to bf16 costs
+    assert np.abs(f64(scores) - exact).max() < max(2e-3, 3.0 * floor) * max(1.0, float(np.abs(exact).max()))
+
+
 # ------------------------------------------------------------------------------------------ attention
 @pytest.mark.parametrize("n,Hq,Hkv,d,dtype", [
     (1, 4, 1, 128, torch.bfloat16), (37, 4, 2, 128, torch.bfloat16), (128, 8, 8, 128, torch.bfloat16),
