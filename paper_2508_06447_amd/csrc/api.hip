@@ -158,16 +158,46 @@ int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_hea
 }
 
 int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m, int n_heads,
-                     int head_dim, int k_in, int ldo, int dtype, void* out, const float* qt, float* token_scores,
-                     void* stream) {
+                     int head_dim, int k_in, int ldo, int dtype, float norm_eps, void* out, const float* qt,
+                     float* token_scores, void* stream) {
     if (!a || !w || !table || !out || m < 1 || n_heads < 1 || head_dim < 1 || k_in < 1 || lda < k_in ||
-        ldo < n_heads * head_dim || (qt && !token_scores))
+        ldo < n_heads * head_dim || (qt && !token_scores) || norm_eps != norm_eps)
         return SLIM_INVALID_ARG;
     if (dtype != SLIM_BF16 || head_dim != 128 || k_in % 64 != 0 || lda % 8 != 0 || ldo % 8 != 0 || !aligned16(a) ||
         !aligned16(w) || !aligned16(table) || !aligned16(out) || (bias && !aligned16(bias)) || (qt && !aligned16(qt)))
         return SLIM_UNSUPPORTED;
-    return launch_linear_rope(a, lda, w, bias, table, qt, qt ? token_scores : nullptr, m, n_heads, k_in, ldo, out,
-                              (hipStream_t)stream);
+    return launch_linear_rope(a, lda, w, bias, table, qt, qt ? token_scores : nullptr, norm_eps, m, n_heads, k_in, ldo,
+                              out, (hipStream_t)stream);
+}
+
+static int check_norm_linear(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in, int ldo,
+                             int dtype, float eps, const void* out) {
+    if (!a || !w || !out || m < 1 || n_out < 1 || k_in < 1 || lda < k_in || ldo < n_out || !(eps >= 0.f)) return SLIM_INVALID_ARG;
+    if (dtype != SLIM_BF16 || k_in % 64 != 0 || lda % 8 != 0 || !aligned16(a) || !aligned16(w) || (bias && !aligned16(bias)))
+        return SLIM_UNSUPPORTED;
+    return SLIM_OK;
+}
+
+int slim_rmsnorm_linear(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in, int ldo,
+                        float eps, int dtype, void* out, void* stream) {
+    int rc = check_norm_linear(a, lda, w, bias, m, n_out, k_in, ldo, dtype, eps, out);
+    if (rc) return rc;
+    return launch_linear_norm(a, lda, w, nullptr, bias, eps, m, n_out, k_in, ldo, out, (hipStream_t)stream);
+}
+
+int slim_rmsnorm_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m, int n_out, int k_in,
+                               int ldo, float eps, int dtype, void* out, void* stream) {
+    if (!w_up) return SLIM_INVALID_ARG;
+    int rc = check_norm_linear(a, lda, w_gate, nullptr, m, n_out, k_in, ldo, dtype, eps, out);
+    if (rc) return rc;
+    if (!aligned16(w_up)) return SLIM_UNSUPPORTED;
+    return launch_linear_norm(a, lda, w_gate, w_up, nullptr, eps, m, n_out, k_in, ldo, out, (hipStream_t)stream);
+}
+
+int slim_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, void* stream) {
+    if (!w || !gain || !out || n_out < 1 || k_in < 1) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    return launch_fold_gain(w, gain, n_out, k_in, dtype, out, (hipStream_t)stream);
 }
 
 int slim_score_blocks_from_token_scores(const float* token_scores, int n_tokens, int n_kv_heads, int block, int unit,
@@ -286,9 +316,12 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
                       void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_shape(s);
     if (rc) return rc;
-    if (!w || !w->g_attn || !w->wq || !w->wk || !w->wv || !w->wo || !w->g_ffn || !w->w_gate || !w->w_up ||
-        !w->w_down || !x_in || !x_out || !workspace || n_tokens < 1 || n_keep < 1)
+    if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down || !x_in || !x_out ||
+        !workspace || n_tokens < 1 || n_keep < 1)
         return SLIM_INVALID_ARG;
+    // A NULL gain means the gain is already folded into the projections that follow the norm (slim_fold_gain);
+    // the norm then runs inside those projections, which the kernels cover for bf16 and hidden % 64 == 0.
+    if ((!w->g_attn || !w->g_ffn) && (s->dtype != SLIM_BF16 || s->hidden % 64 != 0)) return SLIM_UNSUPPORTED;
     const int N = n_tokens;
     const LayerPlan p = plan_layer(s, N, n_keep);
     if (p.prune) {
@@ -314,14 +347,22 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     // Query/Key projection + RoPE at the given positions.  bf16 heads of 128: one kernel, the rotation (and, for the
     // keys of a pruning layer with TokenUnit scoring, the per-token dot with the window query) in the GEMM epilogue,
     // so the projected states are written once and never re-read before attention.  Otherwise two kernels.
+    // With a folded gain (NULL g_attn / g_ffn) the projections read the residual stream itself and normalise it on
+    // the fly, and no normalised copy is written; otherwise `h` holds RMSNorm(rows) and the projections read that.
     float* table = (float*)(ws + p.table);
     float* tscore = (float*)(ws + p.tscore);
     const bool fused = dt == SLIM_BF16 && d == 128 && Hd % 64 == 0;
     const bool fused_score = fused && p.prune && s->scoring == 0;
+    const bool fold_attn = !w->g_attn, fold_ffn = !w->g_ffn;
+    const float eps_attn = fold_attn ? s->rms_eps : -1.f;
+    auto project = [&](const void* a, const void* wmat, const void* bias, int m, int n_feat, void* out) -> int {
+        if (fold_attn) return launch_linear_norm(a, Hd, wmat, nullptr, bias, s->rms_eps, m, n_feat, Hd, n_feat, out, st);
+        return launch_linear(a, Hd, wmat, nullptr, nullptr, bias, m, n_feat, Hd, n_feat, dt, out, st);
+    };
     auto project_rope = [&](const void* a, const void* wmat, const void* bias, const int* pos_, int pos0, int m, int heads,
                             void* out, const float* tab, const float* qt_, float* ts) -> int {
-        if (fused) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, m, heads, Hd, heads * d, out, st);
-        int r = launch_linear(a, Hd, wmat, nullptr, nullptr, bias, m, heads * d, Hd, heads * d, dt, out, st);
+        if (fused) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, eps_attn, m, heads, Hd, heads * d, out, st);
+        int r = project(a, wmat, bias, m, heads * d, out);
         return r ? r : launch_rope(out, pos_, pos0, m, heads, d, s->rope_theta, dt, st);
     };
     auto block_scores = [&](const void* q_window, int w_eff, float* scores) -> int {
@@ -329,7 +370,11 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         return launch_score(q_window, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st);
     };
 
-    SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
+    const void* rows_in = x_in;        // what the projections of the incoming tokens read
+    if (!fold_attn) {
+        SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
+        rows_in = h;
+    }
     if (fused) SLIM_TRY(launch_rope_table(pos_in, 0, N, d, s->rope_theta, table, st));
 
     const void* resid = x_in;          // residual stream entering the attention branch
@@ -340,11 +385,11 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
-        SLIM_TRY(project_rope(h, w->wq, w->bq, pos_in, 0, N, Hq, qc, table, nullptr, nullptr));
+        SLIM_TRY(project_rope(rows_in, w->wq, w->bq, pos_in, 0, N, Hq, qc, table, nullptr, nullptr));
         const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
         if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
-        SLIM_TRY(project_rope(h, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
-        SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, w->bv, N, kvd, Hd, kvd, dt, vc, st));
+        SLIM_TRY(project_rope(rows_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+        SLIM_TRY(project(rows_in, w->wv, w->bv, N, kvd, vc));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(block_scores(q_last, w_eff, scores));
@@ -356,13 +401,14 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     } else {
     if (p.prune) {
         // Query states of the local window (last w_eff rows) and their head-group-summed mean.
-        const unsigned char* h_win = (const unsigned char*)h + (size_t)(N - w_eff) * Hd * es;
-        SLIM_TRY(project_rope(h_win, w->wq, w->bq, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win,
+        const unsigned char* r_win = (const unsigned char*)rows_in + (size_t)(N - w_eff) * Hd * es;
+        SLIM_TRY(project_rope(r_win, w->wq, w->bq, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win,
                               table + (size_t)(N - w_eff) * d, nullptr, nullptr));
         if (fused_score) SLIM_TRY(launch_window_query(q_win, w_eff, Hq, Hkv, d, dt, qt, st));
     }
     // Key states of every incoming token.
-    SLIM_TRY(project_rope(h, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+    SLIM_TRY(project_rope(rows_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+    const void* rows = rows_in;        // what the Q/V projections of the continuing tokens read
     if (p.prune) {
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(block_scores(q_win, w_eff, scores));
@@ -370,7 +416,11 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         // Hidden rows + positions into x_out / pos_out, keys into kc.
         SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
         SLIM_TRY(launch_compact(k_all, nullptr, kept_blocks_out, n_keep, s->block, N, kvd, dt, kc, nullptr, st));
-        SLIM_TRY(launch_rmsnorm(x_out, w->g_attn, n, Hd, s->rms_eps, dt, h, st));
+        rows = x_out;
+        if (!fold_attn) {
+            SLIM_TRY(launch_rmsnorm(x_out, w->g_attn, n, Hd, s->rms_eps, dt, h, st));
+            rows = h;
+        }
         resid = x_out;
         pos = pos_out;
         if (fused) SLIM_TRY(launch_rope_table(pos_out, 0, n, d, s->rope_theta, table, st));
@@ -380,14 +430,18 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     }
 
     // Q, V of the rows that continue; RoPE on Q at the original positions.
-    SLIM_TRY(project_rope(h, w->wq, w->bq, pos, 0, n, Hq, qc, table, nullptr, nullptr));
-    SLIM_TRY(launch_linear(h, Hd, w->wv, nullptr, nullptr, w->bv, n, kvd, Hd, kvd, dt, vc, st));
+    SLIM_TRY(project_rope(rows, w->wq, w->bq, pos, 0, n, Hq, qc, table, nullptr, nullptr));
+    SLIM_TRY(project(rows, w->wv, w->bv, n, kvd, vc));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
     }
     // y = resid + Wo o  (into x_out);  z = y + Wdown(silu(Wgate r) * Wup r), r = RMSNorm(y)  (in place)
     SLIM_TRY(launch_linear(o, qd, w->wo, nullptr, resid, nullptr, n, Hd, qd, Hd, dt, x_out, st));
-    SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, n, Hd, s->rms_eps, dt, h, st));
-    SLIM_TRY(launch_linear(h, Hd, w->w_gate, w->w_up, nullptr, nullptr, n, s->ffn, Hd, s->ffn, dt, act, st));
+    if (fold_ffn) {
+        SLIM_TRY(launch_linear_norm(x_out, Hd, w->w_gate, w->w_up, nullptr, s->rms_eps, n, s->ffn, Hd, s->ffn, act, st));
+    } else {
+        SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, n, Hd, s->rms_eps, dt, h, st));
+        SLIM_TRY(launch_linear(h, Hd, w->w_gate, w->w_up, nullptr, nullptr, n, s->ffn, Hd, s->ffn, dt, act, st));
+    }
     SLIM_TRY(launch_linear(act, s->ffn, w->w_down, nullptr, x_out, nullptr, n, Hd, s->ffn, Hd, dt, x_out, st));
 #undef SLIM_TRY
     return SLIM_OK;

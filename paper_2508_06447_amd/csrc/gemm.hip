@@ -27,12 +27,14 @@ namespace slim {
 enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_BIAS = 3, EPI_ROPE = 4 };
 // EPI_BIAS: R is a bias vector [N].  EPI_ROPE: R is a bias vector or null, the rest comes in a RopeEpi.
 
-// Extra operands of the RoPE epilogue (heads of 128 features, one head per wave tile).
+// Extra operands: of the RoPE epilogue (heads of 128 features, one head per wave tile), and of the fused RMSNorm.
 struct RopeEpi {
     const float* table = nullptr;        // [M][128]: cos of the 64 rotation angles of the token, then their sin
     const float* qt = nullptr;           // [N] float or null: head-group-summed window query (Eq. 2 by linearity)
     float* token_scores = nullptr;       // [M][N/128]: rotated, rounded key of (token, head) dotted with its part of qt
+    float norm_eps = 0.f;                // NORM kernels: out = acc / sqrt(mean_k a[m,k]^2 + norm_eps)
 };
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BK = 64;                                   // k-depth of an LDS tile (8 chunks of 16 bytes)
 
@@ -252,7 +254,12 @@ __device__ __forceinline__ void tile_of_workgroup(int L, bool xcd_runs, int tile
 
 // One output tile of the main path.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned
 // rows.  The tile starts at token m0, feature n0; M and N bound the loads (clamped) and the stores.
-template <int TW, int TA, int WGN, int WGM, int EPI>
+// NORM: the activation rows are the raw residual stream and the result is that of the projection applied to their
+// RMSNorm (unit gain: a gain vector is folded into the weights beforehand).  Every wave sees all k of its token
+// rows pass through its MFMA B fragments (lane l32 + 32 hh holds 8 of the 16 k of row l32 per step), so it sums
+// their squares with one dot2 per pair on the side and scales its accumulators by 1/sqrt(mean + eps) at the end:
+// the normalised activations are never written to memory.
+template <int TW, int TA, int WGN, int WGM, int EPI, bool NORM>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
                                           const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
                                           int N, int K, int m0, int n0, unsigned char* lds, const RopeEpi& re) {
@@ -335,6 +342,9 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
             for (int i = 0; i < TW; ++i)
                 wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(wfrag[stage][ks] + (w * BN + i * 32) * BK * 2);
     };
+    float ss[TA];
+#pragma unroll
+    for (int j = 0; j < TA; ++j) ss[j] = 0.f;
     auto mfmas = [&](int buf) {
 #pragma unroll
         for (int w = 0; w < NW; ++w)
@@ -343,6 +353,17 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
 #pragma unroll
                 for (int j = 0; j < TA; ++j)
                     acc[w][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][w][i], af[buf][j], acc[w][i][j], 0, 0, 0);
+        if constexpr (NORM) {
+#pragma unroll
+            for (int j = 0; j < TA; ++j)
+            {
+                const bf16x8 a8 = af[buf][j];
+                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 0, 1), __builtin_shufflevector(a8, a8, 0, 1), ss[j], false);
+                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 2, 3), __builtin_shufflevector(a8, a8, 2, 3), ss[j], false);
+                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 4, 5), __builtin_shufflevector(a8, a8, 4, 5), ss[j], false);
+                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 6, 7), __builtin_shufflevector(a8, a8, 6, 7), ss[j], false);
+            }
+        }
     };
     // Two LDS stages.  Fragments are read one k-step ahead of their MFMAs, also across k-tiles: the
     // workgroup barrier of a k-tile sits before its last k-step, when every wave has pulled that step's
@@ -378,6 +399,19 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
         k_tile(kt, Stage0{}, Stage1{});
         if (kt + 1 < KT) k_tile(kt + 1, Stage1{}, Stage0{});
     }
+    if constexpr (NORM) {
+#pragma unroll
+        for (int j = 0; j < TA; ++j) {
+            const float tot = ss[j] + __shfl_xor(ss[j], 32, 64);
+            const float inv = 1.0f / sqrtf(tot / (float)K + re.norm_eps);
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int i = 0; i < TW; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[w][i][j][v] *= inv;
+        }
+    }
     // The epilogue reuses the stage buffers: every wave must be past its last fragment reads.
     __builtin_amdgcn_s_waitcnt(0x0070);
     workgroup_barrier();
@@ -396,7 +430,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
 }
 
 // Main kernel: every workgroup computes one tile of the same shape.
-template <int TW, int TA, int WGN, int WGM, int EPI>
+template <int TW, int TA, int WGN, int WGM, int EPI, bool NORM>
 __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
                                                         const bf16_t* __restrict__ W0,
                                                         const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
@@ -405,7 +439,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict
     extern __shared__ __align__(16) unsigned char lds[];
     int tm, tn;
     tile_of_workgroup(blockIdx.x, true, tiles_m, tiles_n, tm, tn);
-    gemm_tile<TW, TA, WGN, WGM, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds, re);
+    gemm_tile<TW, TA, WGN, WGM, EPI, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds, re);
 }
 
 // Shapes of the two-size launch: 256-token tiles for the first big_tiles_m token-tiles, 128-token tiles
@@ -424,7 +458,7 @@ template <int EPI> struct TileShapes {
 // Two tile sizes in one launch.  Workgroups are started in id order, so the 256-token tiles run first
 // and the 128-token tiles fill the last, partly empty round of workgroups: the tail of the launch costs
 // about half a tile time instead of a whole one, and a ragged last token-tile wastes no MFMA work.
-template <int EPI>
+template <int EPI, bool NORM>
 __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* __restrict__ A, int lda,
                                                                  const bf16_t* __restrict__ W0,
                                                                  const bf16_t* __restrict__ W1, const bf16_t* R,
@@ -437,10 +471,10 @@ __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* _
     int tm, tn;
     if ((int)blockIdx.x < n_big) {
         tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
-        gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
+        gemm_tile<S::TW_BIG, 2, 2, 4, EPI, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
     } else {
         tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
-        gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI>(
+        gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI, NORM>(
             A, lda, W0, W1, R, C, ldo, M, N, K, big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, re);
     }
 }
@@ -545,7 +579,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_generic_kernel(const bf16_t* __
     store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
 }
 
-template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC>
+template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC, bool NORM = false>
 static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                        int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
@@ -553,7 +587,7 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
     constexpr size_t smem = 2 * (size_t)(BN * NW + BM) * BK * 2;
     const void* kern;
     if constexpr (GENERIC) kern = (const void*)gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>;
-    else kern = (const void*)gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
+    else kern = (const void*)gemm_bf16_kernel<TW, TA, WGN, WGM, EPI, NORM>;
     static bool attr_done = false;                       // raising the LDS limit is per function, once
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -565,7 +599,7 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
         hipLaunchKernelGGL((gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM),
                            smem, st, A, lda, W0, W1, R, C, ldo, M, N, K, tiles_m, tiles_n);
     else
-        hipLaunchKernelGGL((gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem,
+        hipLaunchKernelGGL((gemm_bf16_kernel<TW, TA, WGN, WGM, EPI, NORM>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem,
                            st, A, lda, W0, W1, R, C, ldo, M, N, K, tiles_m, tiles_n, re);
     return check_launch();
 }
@@ -618,14 +652,14 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
     return best_mb;
 }
 
-template <int EPI>
+template <int EPI, bool NORM = false>
 static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                            int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st,
                            const RopeEpi& re = RopeEpi()) {
     using S = TileShapes<EPI>;
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
-    auto kern = gemm_bf16_two_size_kernel<EPI>;
+    auto kern = gemm_bf16_two_size_kernel<EPI, NORM>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -651,16 +685,20 @@ static int cu_count() {
     return n;
 }
 
-template <int EPI>
+template <int EPI, bool NORM = false>
 static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
-                         int ldo, int M, int N, int K, hipStream_t st) {
-    if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+                         int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
+    if constexpr (!NORM && EPI != EPI_ROPE) {            // the callers of the other kernels have checked K % 64 == 0
+        if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    }
     if (M <= 128) {
-        if constexpr (EPI == EPI_SWIGLU) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
-        else return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+        if constexpr (EPI == EPI_SWIGLU) return launch_bf16<1, 1, 2, 4, EPI, false, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
+        else if constexpr (EPI == EPI_ROPE) return launch_bf16<4, 1, 2, 4, EPI, false, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
+        else return launch_bf16<2, 1, 2, 4, EPI, false, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
     }
     const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;
-    return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.55 : 0.5), st);
+    return launch_two_size<EPI, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K,
+                                      plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.55 : 0.5), st, re);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
@@ -719,18 +757,31 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 }
 
 // Query/Key projection with the RoPE epilogue (bf16, heads of 128, k_in a multiple of 64; checked by the caller).
+// norm_eps >= 0: the rows of a are the raw residual stream and are RMS-normalised on the fly.
 int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, const float* qt,
-                       float* token_scores, int m, int n_heads, int k_in, int ldo, void* out, hipStream_t st) {
+                       float* token_scores, float norm_eps, int m, int n_heads, int k_in, int ldo, void* out,
+                       hipStream_t st) {
     RopeEpi re;
     re.table = table;
     re.qt = qt;
     re.token_scores = token_scores;
+    re.norm_eps = norm_eps;
     const bf16_t *A = (const bf16_t*)a, *W = (const bf16_t*)w, *B = (const bf16_t*)bias;
-    const int N = n_heads * 128;
-    if (m <= 128) return launch_bf16<4, 1, 2, 4, EPI_ROPE, false>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, N, k_in, st, re);
-    const int tiles_n = (N + TileShapes<EPI_ROPE>::BN - 1) / TileShapes<EPI_ROPE>::BN;
-    return launch_two_size<EPI_ROPE>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, N, k_in,
-                                     plan_big_tiles(m, tiles_n, cu_count(), 0.5), st, re);
+    if (norm_eps >= 0.f) return dispatch_bf16<EPI_ROPE, true>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, n_heads * 128, k_in, st, re);
+    return dispatch_bf16<EPI_ROPE, false>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, n_heads * 128, k_in, st, re);
+}
+
+// RMSNorm (unit gain) of the rows of a fused into a projection: plain, + bias, or SwiGLU (w1).  bf16, k_in a
+// multiple of 64 (checked by the caller).
+int launch_linear_norm(const void* a, int lda, const void* w0, const void* w1, const void* bias, float norm_eps, int m,
+                       int n_out, int k_in, int ldo, void* out, hipStream_t st) {
+    RopeEpi re;
+    re.norm_eps = norm_eps;
+    const bf16_t *A = (const bf16_t*)a, *W0 = (const bf16_t*)w0, *W1 = (const bf16_t*)w1, *B = (const bf16_t*)bias;
+    bf16_t* C = (bf16_t*)out;
+    if (w1) return dispatch_bf16<EPI_SWIGLU, true>(A, lda, W0, W1, nullptr, C, ldo, m, n_out, k_in, st, re);
+    if (bias) return dispatch_bf16<EPI_BIAS, true>(A, lda, W0, nullptr, B, C, ldo, m, n_out, k_in, st, re);
+    return dispatch_bf16<EPI_PLAIN, true>(A, lda, W0, nullptr, nullptr, C, ldo, m, n_out, k_in, st, re);
 }
 
 // At most one of w1 (SwiGLU), residual and bias is set.

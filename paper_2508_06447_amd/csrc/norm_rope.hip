@@ -95,6 +95,26 @@ int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float th
     return check_launch();
 }
 
+// out[n, k] = w[n, k] * gain[k]: folds an RMSNorm gain into the weights of the projection that follows it.
+template <typename T>
+__global__ void __launch_bounds__(256) fold_gain_kernel(const T* __restrict__ w, const T* __restrict__ gain, size_t total,
+                                                        int k_in, T* __restrict__ out) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256)
+        Elem<T>::st(out + i, Elem<T>::ld(w + i) * Elem<T>::ld(gain + (i % k_in)));
+}
+
+int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, hipStream_t st) {
+    const size_t total = (size_t)n_out * k_in;
+    const unsigned grid = (unsigned)((total + 255) / 256 < 65536 ? (total + 255) / 256 : 65536);
+    if (dtype == SLIM_BF16)
+        hipLaunchKernelGGL(fold_gain_kernel<bf16_t>, dim3(grid), dim3(256), 0, st, (const bf16_t*)w, (const bf16_t*)gain, total,
+                           k_in, (bf16_t*)out);
+    else
+        hipLaunchKernelGGL(fold_gain_kernel<float>, dim3(grid), dim3(256), 0, st, (const float*)w, (const float*)gain, total, k_in,
+                           (float*)out);
+    return check_launch();
+}
+
 // cos / sin table for the RoPE epilogue of the projections: table[t][0..half) = cos(pos[t] * inv_freq[i]),
 // table[t][half..2*half) = sin, angles and sincos in double as in rope_kernel, rounded to float.
 __global__ void __launch_bounds__(256) rope_table_kernel(const int* __restrict__ pos, int pos0, int n, int half,

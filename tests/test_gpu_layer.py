@@ -23,11 +23,23 @@ def slim():
 SCORING_CODE = {"unit": 0, "avg": 1, "max": 2}
 
 
-def run_gpu(slim, wl, x, w, pos, n_keep, flags=3, scoring="unit", placement="before"):
+def fold_gains(slim, wd):
+    """The layer's weights with both RMSNorm gains folded into the projections that follow them (gains -> NULL)."""
+    out = {k: v for k, v in wd.items() if k not in ("g_attn", "g_ffn")}
+    for g, names in (("g_attn", ("wq", "wk", "wv")), ("g_ffn", ("w_gate", "w_up"))):
+        if not bool((wd[g] == 1).all()):                 # unit gains: nothing to fold
+            for n in names:
+                out[n] = slim.slim_fold_gain(wd[n], wd[g])
+    return out
+
+
+def run_gpu(slim, wl, x, w, pos, n_keep, flags=3, scoring="unit", placement="before", fold=False):
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
                             wl.window, x.dtype, wl.rope_theta, wl.rms_eps, flags, SCORING_CODE[scoring],
                             1 if placement == "after" else 0)
     wd = {k: v.cuda() for k, v in w.items()}
+    if fold:
+        wd = fold_gains(slim, wd)
     res = slim.slim_pruned_layer(shape, wd, x.cuda(), None if pos is None else pos.cuda(), n_keep)
     torch.cuda.synchronize()
     return res
@@ -41,11 +53,16 @@ def sample_rows(n, block, count=48, seed=0):
     return np.array(sorted(rows))
 
 
-def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", placement="before", score_floor=False):
-    """Runs the GPU layer and the oracle on one workload; returns the numbers for the log."""
+def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", placement="before", score_floor=False,
+                fold=False, gains=None):
+    """Runs the GPU layer and the oracle on one workload; returns the numbers for the log.  fold: the RMSNorm gains
+    are folded into the weights and the norms run inside the projections (the configuration bench.py times);
+    gains: (g_attn, g_ffn) tensors that replace the workload's unit gains."""
     x, w, pos = inputs.hidden_states(wl), inputs.layer_weights(wl), inputs.positions(wl)
+    if gains is not None:
+        w = dict(w, g_attn=gains[0], g_ffn=gains[1])
     n_keep = wl.n_keep
-    res = run_gpu(slim, wl, x, w, pos, n_keep, scoring=scoring, placement=placement)
+    res = run_gpu(slim, wl, x, w, pos, n_keep, scoring=scoring, placement=placement, fold=fold)
     s, ow = oracle_shape(wl, scoring, placement), oracle_weights(w, np_dtype)
     xs = x.to(torch.float32).numpy().astype(np_dtype)
     sc_ref, _ = so.layer_scores(s, ow, xs, pos.numpy())
@@ -93,10 +110,11 @@ def test_cfg1_keep_all_equals_unpruned_layer(slim):
     np.testing.assert_array_equal(res["pos"].cpu().numpy(), pos.numpy())
 
 
+@pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("seq,block,window,keep", [(1024, 64, 64, 0.5), (1000, 64, 64, 0.3), (1536, 128, 128, 0.25)])
-def test_reduced_bf16_layer_full_output(slim, seq, block, window, keep):
+def test_reduced_bf16_layer_full_output(slim, seq, block, window, keep, fold):
     wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=seq, block=block, window=window, keep_ratio=keep, planted=seq // 100)
-    r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq {seq} block {block} keep {keep}")
+    r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq {seq} block {block} keep {keep} fold {fold}", fold=fold)
     assert r["sc_err"] < 2e-3
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
 
@@ -161,10 +179,24 @@ def test_reduced_bf16_keep_all_and_prefix_property(slim):
     assert lead >= 1 and np.abs(a - b).max() <= 2 * MAX_ABS
 
 
+@pytest.mark.parametrize("fold", [False, True])
+def test_layer_with_non_unit_gains(slim, fold):
+    """RMSNorm gains that are not 1: as gain vectors (norm kernels) and folded into the weights by slim_fold_gain
+    (norms inside the projections), both against the oracle with the gains."""
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=1000, keep_ratio=0.3, planted=10)
+    g = np.random.default_rng(17)
+    gains = tuple(torch.from_numpy((1.0 + 0.2 * g.standard_normal(wl.hidden)).astype(np.float32)).to(torch.bfloat16)
+                  for _ in range(2))
+    r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq 1000, random gains, fold {fold}", fold=fold, gains=gains,
+                    score_floor=True)
+    assert r["sc_err"] < max(2e-3, 3.0 * r["sc_floor"])
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+
+
 def test_reduced_qwen_shaped_layer_full_output(slim):
     """Second model family (28 query / 4 kv heads, hidden 3584, FFN 18944, Q/K/V biases, theta 1e6)."""
     wl = inputs.scaled(inputs.WORKLOADS["cfg6"], seq=1000, x_kind="planted", planted=10)
-    r = check_layer(slim, wl, np.float64, label="qwen-shaped seq 1000 keep 0.375", score_floor=True)
+    r = check_layer(slim, wl, np.float64, label="qwen-shaped seq 1000 keep 0.375", score_floor=True, fold=True)
     # biases of size 0.5 make the Query/Key states and the scores several times larger than in the LLaMA-shaped
     # workloads, and with them the bf16 rounding of the states: the gate follows that rounding
     assert r["sc_err"] < max(2e-3, 3.0 * r["sc_floor"])
@@ -175,6 +207,6 @@ def test_reduced_qwen_shaped_layer_full_output(slim):
 def test_full_size_workloads_sampled_rows(slim, name):
     wl = inputs.WORKLOADS[name]
     print(f"{name}: N={wl.seq} nb={wl.n_blocks} n_keep={wl.n_keep} n'={wl.n_kept_tokens}", flush=True)
-    r = check_layer(slim, wl, np.float32, rows_count=40, label=name, score_floor=wl.qkv_bias)
+    r = check_layer(slim, wl, np.float32, rows_count=40, label=name, score_floor=wl.qkv_bias, fold=True)
     assert r["sc_err"] < (max(2e-3, 3.0 * r["sc_floor"]) if wl.qkv_bias else 2e-3)   # see the reduced Qwen-shaped test
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])

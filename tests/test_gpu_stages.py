@@ -290,6 +290,49 @@ def test_key_first_pipeline_scores_match_oracle(slim, N, block, unit, w, Hq, Hkv
     assert np.abs(f64(scores) - exact).max() < max(2e-3, 3.0 * floor) * max(1.0, float(np.abs(exact).max()))
 
 
+@pytest.mark.parametrize("m,n,k", [(64, 512, 256), (1300, 776, 128), (300, 4096, 4096), (1, 8, 64)])
+def test_rmsnorm_fused_into_projections(slim, m, n, k):
+    """out = RMSNorm(a) . w^T with the norm inside the kernel, against the oracle's RMSNorm then projection; with a
+    gain, the weights are folded first."""
+    print(f"rmsnorm+linear m={m} n={n} k={k}", flush=True)
+    bf, eps = torch.bfloat16, 1e-5
+    a, w, w2 = rand((m, k), bf, 1, 3.0), rand((n, k), bf, 2, 0.05), rand((n, k), bf, 3, 0.05)
+    b = rand((n,), bf, 4, 1.0)
+    gain = (1.0 + 0.2 * rand((k,), torch.float32, 5)).to(bf)
+    ones = np.ones(k)
+    rel = 2.0 ** -8
+    hn = so.rmsnorm(f64(a), ones, eps)
+    want = hn @ f64(w).T
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), dev(w), eps)), want, rtol=rel, atol=rel * np.abs(want).max())
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), dev(w), eps, bias=dev(b))), want + f64(b), rtol=rel,
+                               atol=rel * np.abs(want + f64(b)).max())
+    sw = so.silu(want) * (hn @ f64(w2).T)
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_swiglu_linear(dev(a), dev(w), dev(w2), eps)), sw, rtol=rel,
+                               atol=rel * np.abs(sw).max())
+    # gain folded into the weights: exact fold in bf16 rounding, then the same projection
+    wf = slim.slim_fold_gain(dev(w), dev(gain))
+    np.testing.assert_allclose(f64(wf), f64(w) * f64(gain)[None, :], rtol=2.0 ** -8, atol=0)
+    want_g = so.rmsnorm(f64(a), f64(gain), eps) @ f64(w).T
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), wf, eps)), want_g, rtol=2 * rel,
+                               atol=2 * rel * np.abs(want_g).max())
+    # the fold also works in float and in place
+    w32 = f64(w).astype(np.float32)
+    got32 = slim.slim_fold_gain(dev(torch.from_numpy(w32)), dev(gain.to(torch.float32)))
+    np.testing.assert_allclose(got32.cpu().numpy(), w32 * gain.to(torch.float32).numpy()[None, :], rtol=1e-6)
+
+
+def test_rmsnorm_and_rope_in_one_projection(slim):
+    m, heads, k, d, theta, eps = 700, 4, 256, 128, 500000.0, 1e-5
+    bf = torch.bfloat16
+    a, w, b = rand((m, k), bf, 1, 5.0), rand((heads * d, k), bf, 2, 0.05), rand((heads * d,), bf, 3, 1.0)
+    pos = (np.arange(m, dtype=np.int32) * 7) % 5000
+    table = slim.slim_rope_table(dev(torch.from_numpy(pos)), m, d, theta)
+    hn = so.rmsnorm(f64(a), np.ones(k), eps)
+    want = so.project_heads(hn, f64(w), heads, d, pos, theta, True, None, f64(b))
+    got = slim.slim_linear_rope(dev(a), dev(w), dev(b), table, d, norm_eps=eps)
+    np.testing.assert_allclose(f64(got), want, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(want).max())
+
+
 # ------------------------------------------------------------------------------------------ attention
 @pytest.mark.parametrize("n,Hq,Hkv,d,dtype", [
     (1, 4, 1, 128, torch.bfloat16), (37, 4, 2, 128, torch.bfloat16), (128, 8, 8, 128, torch.bfloat16),
