@@ -167,8 +167,9 @@ int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w
  *   slim_linear_rope:  out[m, n_heads, 128] = RoPE(a[m, k_in] . w^T + bias) (bias NULL = none), rotation in float
  *                      on the unrounded projection, one rounding.  With qt != NULL (then n_heads = Hkv) also
  *                      token_scores[m, n_heads] float = the rounded key of (token, head) dotted with qt's slice.
- *                      norm_eps >= 0: a holds raw residual rows and the projection is applied to their RMSNorm
- *                      with unit gain and that eps (see slim_rmsnorm_linear); norm_eps < 0: a is used as it is.
+ *                      rstd != NULL: a holds raw residual rows, rstd[m] their 1/rms from slim_row_rstd, and the
+ *                      projection is that of their RMSNorm with unit gain (see slim_rmsnorm_linear); NULL: a is
+ *                      used as it is.
  *                      bf16 only; head_dim 128; k_in % 64 == 0; lda, ldo (elements) % 8 == 0; all pointers 16-byte
  *                      aligned.  UNSUPPORTED otherwise.
  *   slim_score_blocks_from_token_scores: scores[nb] = max over the block's TokenUnits of the mean over the
@@ -179,25 +180,27 @@ int slim_rope_table(const int* pos, int n, int head_dim, float theta, float* tab
 int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_heads, int head_dim, int dtype,
                       float* qt, void* stream);
 int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m,
-                     int n_heads, int head_dim, int k_in, int ldo, int dtype, float norm_eps, void* out,
+                     int n_heads, int head_dim, int k_in, int ldo, int dtype, const float* rstd, void* out,
                      const float* qt, float* token_scores, void* stream);
 int slim_score_blocks_from_token_scores(const float* token_scores, int n_tokens, int n_kv_heads, int block,
                                         int unit, float* scores, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * RMSNorm fused into the projection that consumes it (the norms in front of "QKV Generation" and "FFN" of
- * Fig. 2).  out = RMSNorm_eps(a) . w^T (+ bias), or silu(RMSNorm(a) . w_gate^T) * (RMSNorm(a) . w_up^T), with a
- * UNIT gain: the kernel sums the squares of each row of a while the row passes through its matrix-core
- * operands and scales the accumulators by 1/sqrt(mean + eps); the normalised rows are never stored (the
- * two-kernel route rounds them to bf16 first, this one does not).  A model's gain vector g is folded into
- * the weights once with slim_fold_gain: out[n, k] = w[n, k] * g[k] (rounded to dtype), since
- * (g * x_hat) . w^T = x_hat . (w * g)^T.  bf16 only, k_in % 64 == 0, lda % 8 == 0, 16-byte aligned pointers:
- * UNSUPPORTED otherwise.  slim_fold_gain takes either dtype; out may alias w.
+ * Fig. 2).  slim_row_rstd reads the rows once and leaves rstd[t] = 1/sqrt(mean(x[t,:]^2) + eps) (float); the
+ * projections then read the RAW rows and scale their accumulators by rstd[m] before the epilogue:
+ *   out = RMSNorm(a) . w^T (+ bias),   or   silu(RMSNorm(a) . w_gate^T) * (RMSNorm(a) . w_up^T),
+ * with a UNIT gain, and the normalised rows are never written or re-read (the two-kernel route also rounds them
+ * to bf16 first; this one does not).  A model's gain vector g is folded into the weights once with
+ * slim_fold_gain: out[n, k] = w[n, k] * g[k] (rounded to dtype), since (g * x_hat) . w^T = x_hat . (w * g)^T.
+ * The projections: bf16 only, k_in % 64 == 0, lda % 8 == 0, 16-byte aligned pointers; UNSUPPORTED otherwise.
+ * slim_row_rstd and slim_fold_gain take either dtype; slim_fold_gain's out may alias w.
  */
-int slim_rmsnorm_linear(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in,
-                        int ldo, float eps, int dtype, void* out, void* stream);
-int slim_rmsnorm_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m, int n_out,
-                               int k_in, int ldo, float eps, int dtype, void* out, void* stream);
+int slim_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, void* stream);
+int slim_rmsnorm_linear(const void* a, int lda, const void* w, const void* bias, const float* rstd, int m,
+                        int n_out, int k_in, int ldo, int dtype, void* out, void* stream);
+int slim_rmsnorm_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, const float* rstd,
+                               int m, int n_out, int k_in, int ldo, int dtype, void* out, void* stream);
 int slim_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
@@ -222,8 +225,9 @@ enum { SLIM_PRUNE_BEFORE_ATTENTION = 0, SLIM_PRUNE_AFTER_ATTENTION = 1 };
 
 typedef struct slim_layer_weights {   /* device pointers, [out_features, in_features] row-major */
     /* g_attn / g_ffn: RMSNorm gains [hidden], or NULL when the gain has been folded into wq, wk, wv / w_gate,
-     * w_up (slim_fold_gain; nothing to fold for unit gains).  With NULL the norm runs inside those projections
-     * and no normalised copy of the hidden states is written (bf16, hidden % 64 == 0; UNSUPPORTED otherwise). */
+     * w_up (slim_fold_gain; nothing to fold for unit gains).  With NULL only the row statistics are computed,
+     * the projections apply them to their accumulators, and no normalised copy of the hidden states is
+     * written (bf16, hidden % 64 == 0; UNSUPPORTED otherwise). */
     const void *g_attn, *wq, *wk, *wv, *wo, *g_ffn, *w_gate, *w_up, *w_down;
     const void *bq, *bk, *bv;         /* biases of the Q/K/V projections ([out_features], 16-byte aligned)
                                          or NULL: the paper's LLaMA models have none, its Qwen2.5 models do */

@@ -25,7 +25,7 @@ EXPORTS = (
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
     "slim_kv_swap_workspace_bytes", "slim_kv_swap",
     "slim_rope_table", "slim_window_query", "slim_linear_rope", "slim_score_blocks_from_token_scores",
-    "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
+    "slim_row_rstd", "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
@@ -80,9 +80,10 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_kv_swap.argtypes = [vp, i, i, C.c_double, vp, vp, vp, i, vp, vp, sz, vp, vp, sz, vp]
     lib.slim_rope_table.argtypes = [vp, i, i, f, vp, vp]
     lib.slim_window_query.argtypes = [vp, i, i, i, i, i, vp, vp]
-    lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, f, vp, vp, vp, vp]
-    lib.slim_rmsnorm_linear.argtypes = [vp, i, vp, vp, i, i, i, i, f, i, vp, vp]
-    lib.slim_rmsnorm_swiglu_linear.argtypes = [vp, i, vp, vp, i, i, i, i, f, i, vp, vp]
+    lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
+    lib.slim_row_rstd.argtypes = [vp, i, i, f, i, vp, vp]
+    lib.slim_rmsnorm_linear.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, vp, vp]
+    lib.slim_rmsnorm_swiglu_linear.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, vp, vp]
     lib.slim_fold_gain.argtypes = [vp, vp, i, i, i, vp, vp]
     lib.slim_score_blocks_from_token_scores.argtypes = [vp, i, i, i, i, vp, vp]
     lib.slim_select_topk_blocks.argtypes = [vp, i, i, u, vp, vp]
@@ -239,9 +240,9 @@ def slim_window_query(q_win: torch.Tensor, n_kv_heads: int) -> torch.Tensor:
 
 
 def slim_linear_rope(a: torch.Tensor, w: torch.Tensor, bias: torch.Tensor | None, table: torch.Tensor, head_dim: int,
-                     qt: torch.Tensor | None = None, norm_eps: float = -1.0):
+                     qt: torch.Tensor | None = None, rstd: torch.Tensor | None = None):
     """RoPE(a . w^T + bias) as [m, heads, head_dim]; with qt also the per-(token, head) score partials [m, heads];
-    with norm_eps >= 0 the rows of a are RMS-normalised (unit gain) inside the kernel."""
+    with rstd (from slim_row_rstd) the rows of a are raw and the projection is that of their RMSNorm (unit gain)."""
     lib = load_library()
     m, k_in = a.shape
     n_out = w.shape[0]
@@ -249,7 +250,7 @@ def slim_linear_rope(a: torch.Tensor, w: torch.Tensor, bias: torch.Tensor | None
     out = torch.empty(m, heads, head_dim, dtype=a.dtype, device=a.device)
     ts = torch.empty(m, heads, dtype=torch.float32, device=a.device) if qt is not None else None
     _check(lib.slim_linear_rope(_dev(a, "a"), a.stride(0), _dev(w, "w"), _dev(bias, "bias"), _dev(table, "table"), m, heads,
-                                head_dim, k_in, n_out, _dtype_code(a), norm_eps, _dev(out, "out"), _dev(qt, "qt"),
+                                head_dim, k_in, n_out, _dtype_code(a), _dev(rstd, "rstd"), _dev(out, "out"), _dev(qt, "qt"),
                                 _dev(ts, "ts"), _stream()), "slim_linear_rope")
     return (out, ts) if qt is not None else out
 
@@ -264,26 +265,35 @@ def slim_score_blocks_from_token_scores(token_scores: torch.Tensor, block: int, 
     return scores
 
 
-def slim_rmsnorm_linear(a: torch.Tensor, w: torch.Tensor, eps: float, bias: torch.Tensor | None = None) -> torch.Tensor:
-    """RMSNorm_eps(a) . w^T (+ bias) with unit gain, the norm inside the projection kernel."""
+def slim_row_rstd(x: torch.Tensor, eps: float) -> torch.Tensor:
+    """rstd[t] = 1/sqrt(mean(x[t,:]^2) + eps), float32."""
+    lib = load_library()
+    n, hidden = x.shape
+    rstd = torch.empty(n, dtype=torch.float32, device=x.device)
+    _check(lib.slim_row_rstd(_dev(x, "x"), n, hidden, eps, _dtype_code(x), _dev(rstd, "rstd"), _stream()), "slim_row_rstd")
+    return rstd
+
+
+def slim_rmsnorm_linear(a: torch.Tensor, w: torch.Tensor, rstd: torch.Tensor, bias: torch.Tensor | None = None) -> torch.Tensor:
+    """RMSNorm(a) . w^T (+ bias) with unit gain: raw rows, their rstd applied to the accumulators."""
     lib = load_library()
     m, k_in = a.shape
     n_out = w.shape[0]
     out = torch.empty(m, n_out, dtype=a.dtype, device=a.device)
-    _check(lib.slim_rmsnorm_linear(_dev(a, "a"), a.stride(0), _dev(w, "w"), _dev(bias, "bias"), m, n_out, k_in, n_out, eps,
-                                   _dtype_code(a), _dev(out, "out"), _stream()), "slim_rmsnorm_linear")
+    _check(lib.slim_rmsnorm_linear(_dev(a, "a"), a.stride(0), _dev(w, "w"), _dev(bias, "bias"), _dev(rstd, "rstd"), m, n_out,
+                                   k_in, n_out, _dtype_code(a), _dev(out, "out"), _stream()), "slim_rmsnorm_linear")
     return out
 
 
-def slim_rmsnorm_swiglu_linear(a: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, eps: float) -> torch.Tensor:
-    """silu(RMSNorm(a) . w_gate^T) * (RMSNorm(a) . w_up^T) with unit gain, the norm inside the kernel."""
+def slim_rmsnorm_swiglu_linear(a: torch.Tensor, w_gate: torch.Tensor, w_up: torch.Tensor, rstd: torch.Tensor) -> torch.Tensor:
+    """silu(RMSNorm(a) . w_gate^T) * (RMSNorm(a) . w_up^T) with unit gain, as slim_rmsnorm_linear."""
     lib = load_library()
     m, k_in = a.shape
     n_out = w_gate.shape[0]
     out = torch.empty(m, n_out, dtype=a.dtype, device=a.device)
-    _check(lib.slim_rmsnorm_swiglu_linear(_dev(a, "a"), a.stride(0), _dev(w_gate, "w_gate"), _dev(w_up, "w_up"), m, n_out,
-                                          k_in, n_out, eps, _dtype_code(a), _dev(out, "out"), _stream()),
-           "slim_rmsnorm_swiglu_linear")
+    _check(lib.slim_rmsnorm_swiglu_linear(_dev(a, "a"), a.stride(0), _dev(w_gate, "w_gate"), _dev(w_up, "w_up"),
+                                          _dev(rstd, "rstd"), m, n_out, k_in, n_out, _dtype_code(a), _dev(out, "out"),
+                                          _stream()), "slim_rmsnorm_swiglu_linear")
     return out
 
 

@@ -22,7 +22,7 @@ static int forced_count(unsigned flags, int nb) {
 
 // Workspace layout of slim_pruned_layer (every region 256-byte aligned).
 struct LayerPlan {
-    size_t h, k_all, q_win, qt, scores, table, tscore, kc, vc, qc, o, o_all, act, total;
+    size_t h, k_all, q_win, qt, scores, table, tscore, rstd, rstd2, kc, vc, qc, o, o_all, act, total;
     int nb, n_out;
     bool prune;
 };
@@ -43,6 +43,8 @@ static LayerPlan plan_layer(const slim_layer_shape* s, int N, int n_keep) {
     p.scores = take((size_t)p.nb * sizeof(float));
     p.table = take((size_t)N * s->head_dim * sizeof(float));            // cos | sin of every token's rotation angles
     p.tscore = take((size_t)N * s->n_kv_heads * sizeof(float));         // per-(token, kv head) score partials
+    p.rstd = take((size_t)N * sizeof(float));                           // 1/rms of the incoming rows (folded gains)
+    p.rstd2 = take((size_t)N * sizeof(float));                          // ... of the rows that continue
     const bool after = p.prune && s->placement == SLIM_PRUNE_AFTER_ATTENTION;
     const size_t n_att = after ? (size_t)N : (size_t)p.n_out;    // rows that go through attention
     p.kc = (p.prune && !after) ? take((size_t)p.n_out * kv * es) : p.k_all;   // compacted keys
@@ -158,40 +160,46 @@ int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_hea
 }
 
 int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m, int n_heads,
-                     int head_dim, int k_in, int ldo, int dtype, float norm_eps, void* out, const float* qt,
+                     int head_dim, int k_in, int ldo, int dtype, const float* rstd, void* out, const float* qt,
                      float* token_scores, void* stream) {
     if (!a || !w || !table || !out || m < 1 || n_heads < 1 || head_dim < 1 || k_in < 1 || lda < k_in ||
-        ldo < n_heads * head_dim || (qt && !token_scores) || norm_eps != norm_eps)
+        ldo < n_heads * head_dim || (qt && !token_scores))
         return SLIM_INVALID_ARG;
     if (dtype != SLIM_BF16 || head_dim != 128 || k_in % 64 != 0 || lda % 8 != 0 || ldo % 8 != 0 || !aligned16(a) ||
         !aligned16(w) || !aligned16(table) || !aligned16(out) || (bias && !aligned16(bias)) || (qt && !aligned16(qt)))
         return SLIM_UNSUPPORTED;
-    return launch_linear_rope(a, lda, w, bias, table, qt, qt ? token_scores : nullptr, norm_eps, m, n_heads, k_in, ldo,
-                              out, (hipStream_t)stream);
+    return launch_linear_rope(a, lda, w, bias, table, qt, qt ? token_scores : nullptr, rstd, m, n_heads, k_in, ldo, out,
+                              (hipStream_t)stream);
 }
 
-static int check_norm_linear(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in, int ldo,
-                             int dtype, float eps, const void* out) {
-    if (!a || !w || !out || m < 1 || n_out < 1 || k_in < 1 || lda < k_in || ldo < n_out || !(eps >= 0.f)) return SLIM_INVALID_ARG;
+int slim_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, void* stream) {
+    if (!x || !rstd || n < 1 || hidden < 1 || !(eps >= 0.f)) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    return launch_row_rstd(x, n, hidden, eps, dtype, rstd, (hipStream_t)stream);
+}
+
+static int check_norm_linear(const void* a, int lda, const void* w, const void* bias, const float* rstd, int m, int n_out,
+                             int k_in, int ldo, int dtype, const void* out) {
+    if (!a || !w || !rstd || !out || m < 1 || n_out < 1 || k_in < 1 || lda < k_in || ldo < n_out) return SLIM_INVALID_ARG;
     if (dtype != SLIM_BF16 || k_in % 64 != 0 || lda % 8 != 0 || !aligned16(a) || !aligned16(w) || (bias && !aligned16(bias)))
         return SLIM_UNSUPPORTED;
     return SLIM_OK;
 }
 
-int slim_rmsnorm_linear(const void* a, int lda, const void* w, const void* bias, int m, int n_out, int k_in, int ldo,
-                        float eps, int dtype, void* out, void* stream) {
-    int rc = check_norm_linear(a, lda, w, bias, m, n_out, k_in, ldo, dtype, eps, out);
+int slim_rmsnorm_linear(const void* a, int lda, const void* w, const void* bias, const float* rstd, int m, int n_out,
+                        int k_in, int ldo, int dtype, void* out, void* stream) {
+    int rc = check_norm_linear(a, lda, w, bias, rstd, m, n_out, k_in, ldo, dtype, out);
     if (rc) return rc;
-    return launch_linear_norm(a, lda, w, nullptr, bias, eps, m, n_out, k_in, ldo, out, (hipStream_t)stream);
+    return launch_linear_scaled(a, lda, w, nullptr, bias, rstd, m, n_out, k_in, ldo, out, (hipStream_t)stream);
 }
 
-int slim_rmsnorm_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, int m, int n_out, int k_in,
-                               int ldo, float eps, int dtype, void* out, void* stream) {
+int slim_rmsnorm_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, const float* rstd, int m,
+                               int n_out, int k_in, int ldo, int dtype, void* out, void* stream) {
     if (!w_up) return SLIM_INVALID_ARG;
-    int rc = check_norm_linear(a, lda, w_gate, nullptr, m, n_out, k_in, ldo, dtype, eps, out);
+    int rc = check_norm_linear(a, lda, w_gate, nullptr, rstd, m, n_out, k_in, ldo, dtype, out);
     if (rc) return rc;
     if (!aligned16(w_up)) return SLIM_UNSUPPORTED;
-    return launch_linear_norm(a, lda, w_gate, w_up, nullptr, eps, m, n_out, k_in, ldo, out, (hipStream_t)stream);
+    return launch_linear_scaled(a, lda, w_gate, w_up, nullptr, rstd, m, n_out, k_in, ldo, out, (hipStream_t)stream);
 }
 
 int slim_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, void* stream) {
@@ -354,15 +362,17 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     const bool fused = dt == SLIM_BF16 && d == 128 && Hd % 64 == 0;
     const bool fused_score = fused && p.prune && s->scoring == 0;
     const bool fold_attn = !w->g_attn, fold_ffn = !w->g_ffn;
-    const float eps_attn = fold_attn ? s->rms_eps : -1.f;
-    auto project = [&](const void* a, const void* wmat, const void* bias, int m, int n_feat, void* out) -> int {
-        if (fold_attn) return launch_linear_norm(a, Hd, wmat, nullptr, bias, s->rms_eps, m, n_feat, Hd, n_feat, out, st);
+    float* rstd_in = (float*)(ws + p.rstd);      // 1/rms of the incoming rows, and of the rows that continue
+    float* rstd_kept = (float*)(ws + p.rstd2);
+    // `sc`: the 1/rms of the rows of `a` when they are raw residual rows (folded gain), null when they are normalised.
+    auto project = [&](const void* a, const float* sc, const void* wmat, const void* bias, int m, int n_feat, void* out) -> int {
+        if (sc) return launch_linear_scaled(a, Hd, wmat, nullptr, bias, sc, m, n_feat, Hd, n_feat, out, st);
         return launch_linear(a, Hd, wmat, nullptr, nullptr, bias, m, n_feat, Hd, n_feat, dt, out, st);
     };
-    auto project_rope = [&](const void* a, const void* wmat, const void* bias, const int* pos_, int pos0, int m, int heads,
-                            void* out, const float* tab, const float* qt_, float* ts) -> int {
-        if (fused) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, eps_attn, m, heads, Hd, heads * d, out, st);
-        int r = project(a, wmat, bias, m, heads * d, out);
+    auto project_rope = [&](const void* a, const float* sc, const void* wmat, const void* bias, const int* pos_, int pos0,
+                            int m, int heads, void* out, const float* tab, const float* qt_, float* ts) -> int {
+        if (fused) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, sc, m, heads, Hd, heads * d, out, st);
+        int r = project(a, sc, wmat, bias, m, heads * d, out);
         return r ? r : launch_rope(out, pos_, pos0, m, heads, d, s->rope_theta, dt, st);
     };
     auto block_scores = [&](const void* q_window, int w_eff, float* scores) -> int {
@@ -371,7 +381,11 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     };
 
     const void* rows_in = x_in;        // what the projections of the incoming tokens read
-    if (!fold_attn) {
+    const float* sc_in = nullptr;
+    if (fold_attn) {
+        SLIM_TRY(launch_row_rstd(x_in, N, Hd, s->rms_eps, dt, rstd_in, st));
+        sc_in = rstd_in;
+    } else {
         SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
         rows_in = h;
     }
@@ -385,11 +399,11 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
-        SLIM_TRY(project_rope(rows_in, w->wq, w->bq, pos_in, 0, N, Hq, qc, table, nullptr, nullptr));
+        SLIM_TRY(project_rope(rows_in, sc_in, w->wq, w->bq, pos_in, 0, N, Hq, qc, table, nullptr, nullptr));
         const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
         if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
-        SLIM_TRY(project_rope(rows_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
-        SLIM_TRY(project(rows_in, w->wv, w->bv, N, kvd, vc));
+        SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+        SLIM_TRY(project(rows_in, sc_in, w->wv, w->bv, N, kvd, vc));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(block_scores(q_last, w_eff, scores));
@@ -402,13 +416,15 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     if (p.prune) {
         // Query states of the local window (last w_eff rows) and their head-group-summed mean.
         const unsigned char* r_win = (const unsigned char*)rows_in + (size_t)(N - w_eff) * Hd * es;
-        SLIM_TRY(project_rope(r_win, w->wq, w->bq, pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win,
+        SLIM_TRY(project_rope(r_win, sc_in ? sc_in + (N - w_eff) : nullptr, w->wq, w->bq,
+                              pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win,
                               table + (size_t)(N - w_eff) * d, nullptr, nullptr));
         if (fused_score) SLIM_TRY(launch_window_query(q_win, w_eff, Hq, Hkv, d, dt, qt, st));
     }
     // Key states of every incoming token.
-    SLIM_TRY(project_rope(rows_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+    SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
     const void* rows = rows_in;        // what the Q/V projections of the continuing tokens read
+    const float* sc = sc_in;
     if (p.prune) {
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(block_scores(q_win, w_eff, scores));
@@ -417,7 +433,10 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
         SLIM_TRY(launch_compact(k_all, nullptr, kept_blocks_out, n_keep, s->block, N, kvd, dt, kc, nullptr, st));
         rows = x_out;
-        if (!fold_attn) {
+        if (fold_attn) {                 // the kept rows' statistics are the compacted ones
+            SLIM_TRY(launch_compact(rstd_in, nullptr, kept_blocks_out, n_keep, s->block, N, 1, SLIM_F32, rstd_kept, nullptr, st));
+            sc = rstd_kept;
+        } else {
             SLIM_TRY(launch_rmsnorm(x_out, w->g_attn, n, Hd, s->rms_eps, dt, h, st));
             rows = h;
         }
@@ -430,14 +449,15 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     }
 
     // Q, V of the rows that continue; RoPE on Q at the original positions.
-    SLIM_TRY(project_rope(rows, w->wq, w->bq, pos, 0, n, Hq, qc, table, nullptr, nullptr));
-    SLIM_TRY(project(rows, w->wv, w->bv, n, kvd, vc));
+    SLIM_TRY(project_rope(rows, sc, w->wq, w->bq, pos, 0, n, Hq, qc, table, nullptr, nullptr));
+    SLIM_TRY(project(rows, sc, w->wv, w->bv, n, kvd, vc));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
     }
     // y = resid + Wo o  (into x_out);  z = y + Wdown(silu(Wgate r) * Wup r), r = RMSNorm(y)  (in place)
     SLIM_TRY(launch_linear(o, qd, w->wo, nullptr, resid, nullptr, n, Hd, qd, Hd, dt, x_out, st));
     if (fold_ffn) {
-        SLIM_TRY(launch_linear_norm(x_out, Hd, w->w_gate, w->w_up, nullptr, s->rms_eps, n, s->ffn, Hd, s->ffn, act, st));
+        SLIM_TRY(launch_row_rstd(x_out, n, Hd, s->rms_eps, dt, rstd_kept, st));
+        SLIM_TRY(launch_linear_scaled(x_out, Hd, w->w_gate, w->w_up, nullptr, rstd_kept, n, s->ffn, Hd, s->ffn, act, st));
     } else {
         SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, n, Hd, s->rms_eps, dt, h, st));
         SLIM_TRY(launch_linear(h, Hd, w->w_gate, w->w_up, nullptr, nullptr, n, s->ffn, Hd, s->ffn, dt, act, st));

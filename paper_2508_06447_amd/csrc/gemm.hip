@@ -32,9 +32,8 @@ struct RopeEpi {
     const float* table = nullptr;        // [M][128]: cos of the 64 rotation angles of the token, then their sin
     const float* qt = nullptr;           // [N] float or null: head-group-summed window query (Eq. 2 by linearity)
     float* token_scores = nullptr;       // [M][N/128]: rotated, rounded key of (token, head) dotted with its part of qt
-    float norm_eps = 0.f;                // NORM kernels: out = acc / sqrt(mean_k a[m,k]^2 + norm_eps)
+    const float* row_scale = nullptr;    // [M] float or null: out row m = row_scale[m] * (a[m,:] . w^T) (fused RMSNorm)
 };
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BK = 64;                                   // k-depth of an LDS tile (8 chunks of 16 bytes)
 
@@ -254,12 +253,10 @@ __device__ __forceinline__ void tile_of_workgroup(int L, bool xcd_runs, int tile
 
 // One output tile of the main path.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned
 // rows.  The tile starts at token m0, feature n0; M and N bound the loads (clamped) and the stores.
-// NORM: the activation rows are the raw residual stream and the result is that of the projection applied to their
-// RMSNorm (unit gain: a gain vector is folded into the weights beforehand).  Every wave sees all k of its token
-// rows pass through its MFMA B fragments (lane l32 + 32 hh holds 8 of the 16 k of row l32 per step), so it sums
-// their squares with one dot2 per pair on the side and scales its accumulators by 1/sqrt(mean + eps) at the end:
-// the normalised activations are never written to memory.
-template <int TW, int TA, int WGN, int WGM, int EPI, bool NORM>
+// With re.row_scale the accumulators of token row m are multiplied by row_scale[m] before the epilogue: with
+// row_scale = 1/sqrt(mean(a[m,:]^2) + eps) and a = the raw residual stream this is the projection of RMSNorm(a)
+// (unit gain; a gain vector is folded into the weights beforehand), and the normalised rows are never stored.
+template <int TW, int TA, int WGN, int WGM, int EPI>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
                                           const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
                                           int N, int K, int m0, int n0, unsigned char* lds, const RopeEpi& re) {
@@ -342,9 +339,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
             for (int i = 0; i < TW; ++i)
                 wf[buf][w][i] = *reinterpret_cast<const bf16x8*>(wfrag[stage][ks] + (w * BN + i * 32) * BK * 2);
     };
-    float ss[TA];
-#pragma unroll
-    for (int j = 0; j < TA; ++j) ss[j] = 0.f;
     auto mfmas = [&](int buf) {
 #pragma unroll
         for (int w = 0; w < NW; ++w)
@@ -353,17 +347,6 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
 #pragma unroll
                 for (int j = 0; j < TA; ++j)
                     acc[w][i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][w][i], af[buf][j], acc[w][i][j], 0, 0, 0);
-        if constexpr (NORM) {
-#pragma unroll
-            for (int j = 0; j < TA; ++j)
-            {
-                const bf16x8 a8 = af[buf][j];
-                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 0, 1), __builtin_shufflevector(a8, a8, 0, 1), ss[j], false);
-                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 2, 3), __builtin_shufflevector(a8, a8, 2, 3), ss[j], false);
-                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 4, 5), __builtin_shufflevector(a8, a8, 4, 5), ss[j], false);
-                ss[j] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a8, a8, 6, 7), __builtin_shufflevector(a8, a8, 6, 7), ss[j], false);
-            }
-        }
     };
     // Two LDS stages.  Fragments are read one k-step ahead of their MFMAs, also across k-tiles: the
     // workgroup barrier of a k-tile sits before its last k-step, when every wave has pulled that step's
@@ -399,11 +382,10 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
         k_tile(kt, Stage0{}, Stage1{});
         if (kt + 1 < KT) k_tile(kt + 1, Stage1{}, Stage0{});
     }
-    if constexpr (NORM) {
+    if (re.row_scale) {
 #pragma unroll
         for (int j = 0; j < TA; ++j) {
-            const float tot = ss[j] + __shfl_xor(ss[j], 32, 64);
-            const float inv = 1.0f / sqrtf(tot / (float)K + re.norm_eps);
+            const float inv = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
 #pragma unroll
             for (int w = 0; w < NW; ++w)
 #pragma unroll
@@ -430,7 +412,7 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
 }
 
 // Main kernel: every workgroup computes one tile of the same shape.
-template <int TW, int TA, int WGN, int WGM, int EPI, bool NORM>
+template <int TW, int TA, int WGN, int WGM, int EPI>
 __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
                                                         const bf16_t* __restrict__ W0,
                                                         const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
@@ -439,7 +421,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict
     extern __shared__ __align__(16) unsigned char lds[];
     int tm, tn;
     tile_of_workgroup(blockIdx.x, true, tiles_m, tiles_n, tm, tn);
-    gemm_tile<TW, TA, WGN, WGM, EPI, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds, re);
+    gemm_tile<TW, TA, WGN, WGM, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * 32 * TA * WGM, tn * 32 * TW * WGN, lds, re);
 }
 
 // Shapes of the two-size launch: 256-token tiles for the first big_tiles_m token-tiles, 128-token tiles
@@ -458,7 +440,7 @@ template <int EPI> struct TileShapes {
 // Two tile sizes in one launch.  Workgroups are started in id order, so the 256-token tiles run first
 // and the 128-token tiles fill the last, partly empty round of workgroups: the tail of the launch costs
 // about half a tile time instead of a whole one, and a ragged last token-tile wastes no MFMA work.
-template <int EPI, bool NORM>
+template <int EPI>
 __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* __restrict__ A, int lda,
                                                                  const bf16_t* __restrict__ W0,
                                                                  const bf16_t* __restrict__ W1, const bf16_t* R,
@@ -471,10 +453,10 @@ __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* _
     int tm, tn;
     if ((int)blockIdx.x < n_big) {
         tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
-        gemm_tile<S::TW_BIG, 2, 2, 4, EPI, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
+        gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
     } else {
         tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
-        gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI, NORM>(
+        gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI>(
             A, lda, W0, W1, R, C, ldo, M, N, K, big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, re);
     }
 }
@@ -579,7 +561,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_generic_kernel(const bf16_t* __
     store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
 }
 
-template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC, bool NORM = false>
+template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC>
 static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                        int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
@@ -587,7 +569,7 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
     constexpr size_t smem = 2 * (size_t)(BN * NW + BM) * BK * 2;
     const void* kern;
     if constexpr (GENERIC) kern = (const void*)gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>;
-    else kern = (const void*)gemm_bf16_kernel<TW, TA, WGN, WGM, EPI, NORM>;
+    else kern = (const void*)gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
     static bool attr_done = false;                       // raising the LDS limit is per function, once
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -599,7 +581,7 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
         hipLaunchKernelGGL((gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM),
                            smem, st, A, lda, W0, W1, R, C, ldo, M, N, K, tiles_m, tiles_n);
     else
-        hipLaunchKernelGGL((gemm_bf16_kernel<TW, TA, WGN, WGM, EPI, NORM>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem,
+        hipLaunchKernelGGL((gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM), smem,
                            st, A, lda, W0, W1, R, C, ldo, M, N, K, tiles_m, tiles_n, re);
     return check_launch();
 }
@@ -652,14 +634,14 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
     return best_mb;
 }
 
-template <int EPI, bool NORM = false>
+template <int EPI>
 static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                            int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st,
                            const RopeEpi& re = RopeEpi()) {
     using S = TileShapes<EPI>;
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
-    auto kern = gemm_bf16_two_size_kernel<EPI, NORM>;
+    auto kern = gemm_bf16_two_size_kernel<EPI>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -685,19 +667,19 @@ static int cu_count() {
     return n;
 }
 
-template <int EPI, bool NORM = false>
+template <int EPI>
 static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                          int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
-    if constexpr (!NORM && EPI != EPI_ROPE) {            // the callers of the other kernels have checked K % 64 == 0
+    if constexpr (EPI != EPI_ROPE) {                     // (row_scale and RoPE callers have checked K % 64 == 0)
         if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
     }
     if (M <= 128) {
-        if constexpr (EPI == EPI_SWIGLU) return launch_bf16<1, 1, 2, 4, EPI, false, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
-        else if constexpr (EPI == EPI_ROPE) return launch_bf16<4, 1, 2, 4, EPI, false, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
-        else return launch_bf16<2, 1, 2, 4, EPI, false, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
+        if constexpr (EPI == EPI_SWIGLU) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
+        else if constexpr (EPI == EPI_ROPE) return launch_bf16<4, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
+        else return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
     }
     const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;
-    return launch_two_size<EPI, NORM>(A, lda, W0, W1, R, C, ldo, M, N, K,
+    return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K,
                                       plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.55 : 0.5), st, re);
 }
 
@@ -757,31 +739,30 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 }
 
 // Query/Key projection with the RoPE epilogue (bf16, heads of 128, k_in a multiple of 64; checked by the caller).
-// norm_eps >= 0: the rows of a are the raw residual stream and are RMS-normalised on the fly.
+// row_scale != null: the rows of a are the raw residual stream and row_scale their 1/rms (fused RMSNorm).
 int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, const float* qt,
-                       float* token_scores, float norm_eps, int m, int n_heads, int k_in, int ldo, void* out,
+                       float* token_scores, const float* row_scale, int m, int n_heads, int k_in, int ldo, void* out,
                        hipStream_t st) {
     RopeEpi re;
     re.table = table;
     re.qt = qt;
     re.token_scores = token_scores;
-    re.norm_eps = norm_eps;
-    const bf16_t *A = (const bf16_t*)a, *W = (const bf16_t*)w, *B = (const bf16_t*)bias;
-    if (norm_eps >= 0.f) return dispatch_bf16<EPI_ROPE, true>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, n_heads * 128, k_in, st, re);
-    return dispatch_bf16<EPI_ROPE, false>(A, lda, W, nullptr, B, (bf16_t*)out, ldo, m, n_heads * 128, k_in, st, re);
+    re.row_scale = row_scale;
+    return dispatch_bf16<EPI_ROPE>((const bf16_t*)a, lda, (const bf16_t*)w, nullptr, (const bf16_t*)bias, (bf16_t*)out, ldo, m,
+                                   n_heads * 128, k_in, st, re);
 }
 
-// RMSNorm (unit gain) of the rows of a fused into a projection: plain, + bias, or SwiGLU (w1).  bf16, k_in a
-// multiple of 64 (checked by the caller).
-int launch_linear_norm(const void* a, int lda, const void* w0, const void* w1, const void* bias, float norm_eps, int m,
-                       int n_out, int k_in, int ldo, void* out, hipStream_t st) {
+// Projection of row-scaled activations: plain, + bias, or SwiGLU (w1).  bf16, k_in a multiple of 64 (checked by
+// the caller).
+int launch_linear_scaled(const void* a, int lda, const void* w0, const void* w1, const void* bias, const float* row_scale,
+                         int m, int n_out, int k_in, int ldo, void* out, hipStream_t st) {
     RopeEpi re;
-    re.norm_eps = norm_eps;
+    re.row_scale = row_scale;
     const bf16_t *A = (const bf16_t*)a, *W0 = (const bf16_t*)w0, *W1 = (const bf16_t*)w1, *B = (const bf16_t*)bias;
     bf16_t* C = (bf16_t*)out;
-    if (w1) return dispatch_bf16<EPI_SWIGLU, true>(A, lda, W0, W1, nullptr, C, ldo, m, n_out, k_in, st, re);
-    if (bias) return dispatch_bf16<EPI_BIAS, true>(A, lda, W0, nullptr, B, C, ldo, m, n_out, k_in, st, re);
-    return dispatch_bf16<EPI_PLAIN, true>(A, lda, W0, nullptr, nullptr, C, ldo, m, n_out, k_in, st, re);
+    if (w1) return dispatch_bf16<EPI_SWIGLU>(A, lda, W0, W1, nullptr, C, ldo, m, n_out, k_in, st, re);
+    if (bias) return dispatch_bf16<EPI_BIAS>(A, lda, W0, nullptr, B, C, ldo, m, n_out, k_in, st, re);
+    return dispatch_bf16<EPI_PLAIN>(A, lda, W0, nullptr, nullptr, C, ldo, m, n_out, k_in, st, re);
 }
 
 // At most one of w1 (SwiGLU), residual and bias is set.

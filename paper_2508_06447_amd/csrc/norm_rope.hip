@@ -95,6 +95,38 @@ int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float th
     return check_launch();
 }
 
+// rstd[t] = 1 / sqrt(mean(x[t, :]^2) + eps): the row statistic of RMSNorm alone, for projections that apply it to
+// their accumulators instead of reading a normalised copy.  One wave per row, 4 rows per workgroup.
+template <typename T>
+__global__ void __launch_bounds__(256) row_rstd_kernel(const T* __restrict__ x, int n, int hidden, float eps,
+                                                       float* __restrict__ rstd) {
+    constexpr int V = Elem<T>::kVec;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= n) return;
+    const T* row = x + (size_t)t * hidden;
+    float ss = 0.f;
+    if (hidden % V == 0 && (((uintptr_t)row) & 15) == 0) {
+        for (int c = lane; c < hidden / V; c += 64) {
+            float f[V];
+            Elem<T>::unpack(*reinterpret_cast<const uint4*>(row + (size_t)c * V), f);
+#pragma unroll
+            for (int i = 0; i < V; ++i) ss += f[i] * f[i];
+        }
+    } else {
+        for (int c = lane; c < hidden; c += 64) { const float v = Elem<T>::ld(row + c); ss += v * v; }
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) rstd[t] = 1.0f / sqrtf(ss / (float)hidden + eps);
+}
+
+int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st) {
+    if (dtype == SLIM_BF16)
+        hipLaunchKernelGGL(row_rstd_kernel<bf16_t>, dim3((n + 3) / 4), dim3(256), 0, st, (const bf16_t*)x, n, hidden, eps, rstd);
+    else
+        hipLaunchKernelGGL(row_rstd_kernel<float>, dim3((n + 3) / 4), dim3(256), 0, st, (const float*)x, n, hidden, eps, rstd);
+    return check_launch();
+}
+
 // out[n, k] = w[n, k] * gain[k]: folds an RMSNorm gain into the weights of the projection that follows it.
 template <typename T>
 __global__ void __launch_bounds__(256) fold_gain_kernel(const T* __restrict__ w, const T* __restrict__ gain, size_t total,

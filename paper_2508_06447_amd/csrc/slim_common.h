@@ -106,10 +106,11 @@ int launch_score(const void* q_win, const void* k, int N, int w, int Hq, int Hkv
                  int pooling, int dtype, float* scores, float* qtilde, hipStream_t st);
 int launch_rope_table(const int* pos, int pos0, int n, int d, float theta, float* table, hipStream_t st);
 int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, const float* qt,
-                       float* token_scores, float norm_eps, int m, int n_heads, int k_in, int ldo, void* out,
+                       float* token_scores, const float* row_scale, int m, int n_heads, int k_in, int ldo, void* out,
                        hipStream_t st);
-int launch_linear_norm(const void* a, int lda, const void* w0, const void* w1, const void* bias, float norm_eps, int m,
-                       int n_out, int k_in, int ldo, void* out, hipStream_t st);
+int launch_linear_scaled(const void* a, int lda, const void* w0, const void* w1, const void* bias, const float* row_scale,
+                         int m, int n_out, int k_in, int ldo, void* out, hipStream_t st);
+int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st);
 int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, hipStream_t st);
 int launch_window_query(const void* q_win, int w, int Hq, int Hkv, int d, int dtype, float* qtilde, hipStream_t st);
 int launch_token_score_blocks(const float* token_scores, int N, int H, int block, int unit, float* scores, hipStream_t st);

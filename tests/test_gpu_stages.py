@@ -292,8 +292,8 @@ def test_key_first_pipeline_scores_match_oracle(slim, N, block, unit, w, Hq, Hkv
 
 @pytest.mark.parametrize("m,n,k", [(64, 512, 256), (1300, 776, 128), (300, 4096, 4096), (1, 8, 64)])
 def test_rmsnorm_fused_into_projections(slim, m, n, k):
-    """out = RMSNorm(a) . w^T with the norm inside the kernel, against the oracle's RMSNorm then projection; with a
-    gain, the weights are folded first."""
+    """out = RMSNorm(a) . w^T from raw rows and their 1/rms applied to the accumulators, against the oracle's RMSNorm
+    then projection; with a gain, the weights are folded first."""
     print(f"rmsnorm+linear m={m} n={n} k={k}", flush=True)
     bf, eps = torch.bfloat16, 1e-5
     a, w, w2 = rand((m, k), bf, 1, 3.0), rand((n, k), bf, 2, 0.05), rand((n, k), bf, 3, 0.05)
@@ -302,18 +302,20 @@ def test_rmsnorm_fused_into_projections(slim, m, n, k):
     ones = np.ones(k)
     rel = 2.0 ** -8
     hn = so.rmsnorm(f64(a), ones, eps)
+    rstd = slim.slim_row_rstd(dev(a), eps)
+    np.testing.assert_allclose(f64(rstd), 1.0 / np.sqrt((f64(a) ** 2).mean(axis=1) + eps), rtol=2e-6)
     want = hn @ f64(w).T
-    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), dev(w), eps)), want, rtol=rel, atol=rel * np.abs(want).max())
-    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), dev(w), eps, bias=dev(b))), want + f64(b), rtol=rel,
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), dev(w), rstd)), want, rtol=rel, atol=rel * np.abs(want).max())
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), dev(w), rstd, bias=dev(b))), want + f64(b), rtol=rel,
                                atol=rel * np.abs(want + f64(b)).max())
     sw = so.silu(want) * (hn @ f64(w2).T)
-    np.testing.assert_allclose(f64(slim.slim_rmsnorm_swiglu_linear(dev(a), dev(w), dev(w2), eps)), sw, rtol=rel,
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_swiglu_linear(dev(a), dev(w), dev(w2), rstd)), sw, rtol=rel,
                                atol=rel * np.abs(sw).max())
     # gain folded into the weights: exact fold in bf16 rounding, then the same projection
     wf = slim.slim_fold_gain(dev(w), dev(gain))
     np.testing.assert_allclose(f64(wf), f64(w) * f64(gain)[None, :], rtol=2.0 ** -8, atol=0)
     want_g = so.rmsnorm(f64(a), f64(gain), eps) @ f64(w).T
-    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), wf, eps)), want_g, rtol=2 * rel,
+    np.testing.assert_allclose(f64(slim.slim_rmsnorm_linear(dev(a), wf, rstd)), want_g, rtol=2 * rel,
                                atol=2 * rel * np.abs(want_g).max())
     # the fold also works in float and in place
     w32 = f64(w).astype(np.float32)
@@ -329,7 +331,7 @@ def test_rmsnorm_and_rope_in_one_projection(slim):
     table = slim.slim_rope_table(dev(torch.from_numpy(pos)), m, d, theta)
     hn = so.rmsnorm(f64(a), np.ones(k), eps)
     want = so.project_heads(hn, f64(w), heads, d, pos, theta, True, None, f64(b))
-    got = slim.slim_linear_rope(dev(a), dev(w), dev(b), table, d, norm_eps=eps)
+    got = slim.slim_linear_rope(dev(a), dev(w), dev(b), table, d, rstd=slim.slim_row_rstd(dev(a), eps))
     np.testing.assert_allclose(f64(got), want, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(want).max())
 
 
