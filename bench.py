@@ -74,22 +74,66 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
         lib.slim_compact_tokens(x.data_ptr(), pos.data_ptr(), kept.data_ptr(), n_keep, wl.block, N, Hd, 1,
                                 xc.data_ptr(), pc.data_ptr(), st)
 
+    # The launches of one pruning layer with folded gains, in order (the layer runs exactly these kernels).
+    rstd_all = torch.empty(N, dtype=torch.float32, device=dev)
+    rstd_kept = torch.empty(n, dtype=torch.float32, device=dev)
+    rope_all = slim.slim_rope_table(pos, N, d, wl.rope_theta)
+    rope_kept = rope_all[:n].contiguous()
+    qt = slim.slim_window_query(q_win, Hkv)
+    tsc = torch.empty(N, Hkv, dtype=torch.float32, device=dev)
+    w0 = N - wl.window
+    nul = None
+
+    def lin_rope(a, w, b, tab, m, heads, rstd, out, q=None, ts=None):
+        rc = lib.slim_linear_rope(a.data_ptr(), Hd, w.data_ptr(), b.data_ptr() if b is not None else nul, tab.data_ptr(), m,
+                                  heads, d, Hd, heads * d, 1, rstd.data_ptr(), out.data_ptr(),
+                                  q.data_ptr() if q is not None else nul, ts.data_ptr() if ts is not None else nul, st)
+        assert rc == 0, rc
+
+    def lin_scaled(a, w, b, rstd, m, n_out, out):
+        rc = lib.slim_rmsnorm_linear(a.data_ptr(), Hd, w.data_ptr(), b.data_ptr() if b is not None else nul, rstd.data_ptr(),
+                                     m, n_out, Hd, n_out, 1, out.data_ptr(), st)
+        assert rc == 0, rc
+
+    def swiglu_scaled():
+        rc = lib.slim_rmsnorm_swiglu_linear(y.data_ptr(), Hd, wd["w_gate"].data_ptr(), wd["w_up"].data_ptr(),
+                                            rstd_kept.data_ptr(), n, F, Hd, F, 1, act.data_ptr(), st)
+        assert rc == 0, rc
+
+    def rstd(xx, m, out):
+        rc = lib.slim_row_rstd(xx.data_ptr(), m, Hd, wl.rms_eps, 1, out.data_ptr(), st)
+        assert rc == 0, rc
+
+    def compact_rstd():
+        lib.slim_compact_tokens(rstd_all.data_ptr(), nul, kept.data_ptr(), n_keep, wl.block, N, 1, 0, rstd_kept.data_ptr(), nul, st)
+
+    def compact_k():
+        lib.slim_compact_tokens(k_all.data_ptr(), nul, kept.data_ptr(), n_keep, wl.block, N, Hkv * d, 1, k.data_ptr(), nul, st)
+
+    bq, bk, bv = wd.get("bq"), wd.get("bk"), wd.get("bv")
     rows = [
-        ("rmsnorm_all", "hbm", 2 * N * Hd * es, lambda: slim.slim_rmsnorm(x, wd["g_attn"], wl.rms_eps, out=h_all)),
-        ("k_proj_all", "mfma", 2 * N * Hd * Hkv * d, lambda: slim.slim_linear(h_all, wd["wk"], out=out_kv)),
-        ("rope_k_all", "hbm", 2 * N * Hkv * d * es, lambda: slim.slim_rope(k_all, pos, wl.rope_theta)),
-        ("score_blocks", "hbm", N * Hkv * d * es + wl.window * Hq * d * es + scores.numel() * 4,
-         lambda: slim.slim_score_blocks(q_win, k_all, wl.block, wl.unit, scores=scores, workspace=sws)),
+        ("row_rstd_all", "hbm", N * Hd * es + N * 4, lambda: rstd(x, N, rstd_all)),
+        ("rope_table_all", "alu", N * d * 4, lambda: slim.slim_rope_table(pos, N, d, wl.rope_theta)),
+        ("window_q_proj_rope", "mfma", 2 * wl.window * Hd * Hq * d,
+         lambda: lin_rope(x[w0:], wd["wq"], bq, rope_all[w0:], wl.window, Hq, rstd_all[w0:], q_win)),
+        ("window_query", "latency", wl.window * Hq * d * es, lambda: slim.slim_window_query(q_win, Hkv)),
+        ("k_proj_all_rope_score", "mfma", 2 * N * Hd * Hkv * d,
+         lambda: lin_rope(x, wd["wk"], bk, rope_all, N, Hkv, rstd_all, k_all, qt, tsc)),
+        ("score_blocks_from_token_scores", "latency", N * Hkv * 4 + scores.numel() * 4,
+         lambda: lib.slim_score_blocks_from_token_scores(tsc.data_ptr(), N, Hkv, wl.block, wl.unit, scores.data_ptr(), st)),
         ("select_topk", "latency", scores.numel() * 4 + n_keep * 4,
          lambda: slim.slim_select_topk_blocks(scores, n_keep, kept=kept)),
         ("compact_x", "hbm", 2 * n * Hd * es + n * 8, compact),
-        ("q_proj", "mfma", 2 * n * Hd * Hq * d, lambda: slim.slim_linear(h, wd["wq"], out=out_q)),
-        ("v_proj", "mfma", 2 * n * Hd * Hkv * d, lambda: slim.slim_linear(h, wd["wv"], out=out_kv[:n])),
+        ("compact_k", "hbm", 2 * n * Hkv * d * es, compact_k),
+        ("compact_rstd", "latency", 2 * n * 4, compact_rstd),
+        ("rope_table_kept", "alu", n * d * 4, lambda: slim.slim_rope_table(pc, n, d, wl.rope_theta)),
+        ("q_proj_rope", "mfma", 2 * n * Hd * Hq * d, lambda: lin_rope(xc, wd["wq"], bq, rope_kept, n, Hq, rstd_kept, q)),
+        ("v_proj", "mfma", 2 * n * Hd * Hkv * d, lambda: lin_scaled(xc, wd["wv"], bv, rstd_kept, n, Hkv * d, v)),
         ("prefill_attn", "mfma", 2 * n * n * d * Hq, lambda: slim.slim_prefill_attn(q, k, v, out=o)),
         ("o_proj_residual", "mfma", 2 * n * Hd * Hq * d,
          lambda: slim.slim_linear(o.view(n, Hq * d), wd["wo"], residual=y, out=out_h)),
-        ("ffn_gate_up_swiglu", "mfma", 4 * n * Hd * F,
-         lambda: slim.slim_swiglu_linear(h, wd["w_gate"], wd["w_up"], out=act)),
+        ("row_rstd_kept", "hbm", n * Hd * es + n * 4, lambda: rstd(y, n, rstd_kept)),
+        ("ffn_gate_up_swiglu", "mfma", 4 * n * Hd * F, swiglu_scaled),
         ("ffn_down_residual", "mfma", 2 * n * Hd * F, lambda: slim.slim_linear(act, wd["w_down"], residual=y, out=out_h)),
     ]
     table = {}
@@ -99,6 +143,8 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
         if bound == "mfma":
             e["tflops"] = round(work / (mean * 1e-3) / 1e12, 1)
             e["frac"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        elif bound in ("latency", "alu"):                # too little work for a bandwidth figure to mean anything
+            pass
         else:
             e["gbs"] = round(work / (mean * 1e-3) / 1e9, 1)
             e["frac"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
@@ -179,7 +225,9 @@ def bench_model(args, slim, inputs, wl, dev):
     import torch
     x = inputs.hidden_states(wl).to(dev)
     pos = inputs.positions(wl).to(dev)
-    w_gpu = [{k: v.to(dev) for k, v in w.items()} for _, w in inputs.model_weights(wl, workers=16)]
+    # unit gains folded into the projection weights (the fold is the identity): NULL gains, norms inside the projections
+    w_gpu = [{k: v.to(dev) for k, v in w.items() if k not in ("g_attn", "g_ffn")}
+             for _, w in inputs.model_weights(wl, workers=16)]
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
                             wl.window, x.dtype, wl.rope_theta, wl.rms_eps)
     keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, wl.schedule)
@@ -396,7 +444,9 @@ def main():
     if wl.n_layers > 1:
         return bench_model(args, slim, inputs, wl, dev)
     x = inputs.hidden_states(wl).to(dev)
-    wd = {k: v.to(dev) for k, v in inputs.layer_weights(wl).items()}
+    # The workloads' RMSNorm gains are exactly 1, so folding them into the projection weights (slim_fold_gain)
+    # leaves the weights as they are: the layer is called with NULL gains and runs the norms inside the projections.
+    wd = {k: v.to(dev) for k, v in inputs.layer_weights(wl).items() if k not in ("g_attn", "g_ffn")}
     pos = inputs.positions(wl).to(dev)
     n_keep = wl.n_keep
     variant = args.scoring != "unit" or args.placement != "before" or bool(over)
@@ -439,7 +489,8 @@ def main():
         "config": {"workload": f"{wl.name}: {wl.family}-shaped pruned prefill layer, seq {wl.seq}, block {wl.block}, "
                                f"window {wl.window}, keep ratio {wl.keep_ratio}",
                    "n_tokens": wl.seq, "n_keep_blocks": n_keep, "n_kept_tokens": n_out, "hidden": Hd,
-                   "heads": f"{Hq}q/{Hkv}kv x {d}", "ffn": F, "seed": wl.seed},
+                   "heads": f"{Hq}q/{Hkv}kv x {d}", "ffn": F, "seed": wl.seed,
+                   "rmsnorm": "unit gains folded into the projection weights; row statistics + scaling inside the projections"},
         "layer_ms": round(ms, 4),
         "layer_tflops": round(layer_flops / (ms * 1e-3) / 1e12, 1),
         "layer_mfma_frac": round(layer_flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),

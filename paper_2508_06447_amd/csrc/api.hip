@@ -352,9 +352,10 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     float* qt = (float*)(ws + p.qt);
 #define SLIM_TRY(call) do { rc = (call); if (rc) return rc; } while (0)
 
-    // Query/Key projection + RoPE at the given positions.  bf16 heads of 128: one kernel, the rotation (and, for the
-    // keys of a pruning layer with TokenUnit scoring, the per-token dot with the window query) in the GEMM epilogue,
-    // so the projected states are written once and never re-read before attention.  Otherwise two kernels.
+    // Query/Key projection + RoPE at the given positions.  Keys of bf16 heads of 128: one kernel, the rotation (and, in
+    // a pruning layer with TokenUnit scoring, the per-token dot with the window query) in the GEMM epilogue, so the
+    // Key states are written once and not re-read for scoring.  Queries: projection, then the RoPE kernel (measured:
+    // the rotation in the epilogue gains nothing for the wider Query projection once its cos/sin table is paid for).
     // With a folded gain (NULL g_attn / g_ffn) the projections read the residual stream itself and normalise it on
     // the fly, and no normalised copy is written; otherwise `h` holds RMSNorm(rows) and the projections read that.
     float* table = (float*)(ws + p.table);
@@ -371,7 +372,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     };
     auto project_rope = [&](const void* a, const float* sc, const void* wmat, const void* bias, const int* pos_, int pos0,
                             int m, int heads, void* out, const float* tab, const float* qt_, float* ts) -> int {
-        if (fused) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, sc, m, heads, Hd, heads * d, out, st);
+        if (tab) return launch_linear_rope(a, Hd, wmat, bias, tab, qt_, ts, sc, m, heads, Hd, heads * d, out, st);
         int r = project(a, sc, wmat, bias, m, heads * d, out);
         return r ? r : launch_rope(out, pos_, pos0, m, heads, d, s->rope_theta, dt, st);
     };
@@ -390,6 +391,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         rows_in = h;
     }
     if (fused) SLIM_TRY(launch_rope_table(pos_in, 0, N, d, s->rope_theta, table, st));
+    const float* ktab = fused ? table : nullptr;   // cos/sin rows of the incoming tokens, for the Key projection
 
     const void* resid = x_in;          // residual stream entering the attention branch
     const int* pos = pos_in;           // positions of the rows that continue
@@ -399,10 +401,10 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
-        SLIM_TRY(project_rope(rows_in, sc_in, w->wq, w->bq, pos_in, 0, N, Hq, qc, table, nullptr, nullptr));
+        SLIM_TRY(project_rope(rows_in, sc_in, w->wq, w->bq, pos_in, 0, N, Hq, qc, nullptr, nullptr, nullptr));
         const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
         if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
-        SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+        SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, ktab, fused_score ? qt : nullptr, tscore));
         SLIM_TRY(project(rows_in, sc_in, w->wv, w->bv, N, kvd, vc));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
@@ -417,12 +419,11 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         // Query states of the local window (last w_eff rows) and their head-group-summed mean.
         const unsigned char* r_win = (const unsigned char*)rows_in + (size_t)(N - w_eff) * Hd * es;
         SLIM_TRY(project_rope(r_win, sc_in ? sc_in + (N - w_eff) : nullptr, w->wq, w->bq,
-                              pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win,
-                              table + (size_t)(N - w_eff) * d, nullptr, nullptr));
+                              pos_in ? pos_in + (N - w_eff) : nullptr, N - w_eff, w_eff, Hq, q_win, nullptr, nullptr, nullptr));
         if (fused_score) SLIM_TRY(launch_window_query(q_win, w_eff, Hq, Hkv, d, dt, qt, st));
     }
     // Key states of every incoming token.
-    SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, table, fused_score ? qt : nullptr, tscore));
+    SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, ktab, fused_score ? qt : nullptr, tscore));
     const void* rows = rows_in;        // what the Q/V projections of the continuing tokens read
     const float* sc = sc_in;
     if (p.prune) {
@@ -442,14 +443,13 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         }
         resid = x_out;
         pos = pos_out;
-        if (fused) SLIM_TRY(launch_rope_table(pos_out, 0, n, d, s->rope_theta, table, st));
     } else {
         if (kept_blocks_out) SLIM_TRY(launch_select(nullptr, p.nb, p.nb, 0, kept_blocks_out, st));
         if (pos_out) SLIM_TRY(launch_positions(pos_in, pos_out, N, st));
     }
 
     // Q, V of the rows that continue; RoPE on Q at the original positions.
-    SLIM_TRY(project_rope(rows, sc, w->wq, w->bq, pos, 0, n, Hq, qc, table, nullptr, nullptr));
+    SLIM_TRY(project_rope(rows, sc, w->wq, w->bq, pos, 0, n, Hq, qc, nullptr, nullptr, nullptr));
     SLIM_TRY(project(rows, sc, w->wv, w->bv, n, kvd, vc));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
     }
