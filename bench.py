@@ -78,7 +78,6 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     rstd_all = torch.empty(N, dtype=torch.float32, device=dev)
     rstd_kept = torch.empty(n, dtype=torch.float32, device=dev)
     rope_all = slim.slim_rope_table(pos, N, d, wl.rope_theta)
-    rope_kept = rope_all[:n].contiguous()
     qt = slim.slim_window_query(q_win, Hkv)
     tsc = torch.empty(N, Hkv, dtype=torch.float32, device=dev)
     w0 = N - wl.window
@@ -114,8 +113,9 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     rows = [
         ("row_rstd_all", "hbm", N * Hd * es + N * 4, lambda: rstd(x, N, rstd_all)),
         ("rope_table_all", "alu", N * d * 4, lambda: slim.slim_rope_table(pos, N, d, wl.rope_theta)),
-        ("window_q_proj_rope", "mfma", 2 * wl.window * Hd * Hq * d,
-         lambda: lin_rope(x[w0:], wd["wq"], bq, rope_all[w0:], wl.window, Hq, rstd_all[w0:], q_win)),
+        ("window_q_proj", "mfma", 2 * wl.window * Hd * Hq * d,
+         lambda: lin_scaled(x[w0:], wd["wq"], bq, rstd_all[w0:], wl.window, Hq * d, q_win)),
+        ("rope_window_q", "latency", 2 * wl.window * Hq * d * es, lambda: slim.slim_rope(q_win, pos[w0:], wl.rope_theta)),
         ("window_query", "latency", wl.window * Hq * d * es, lambda: slim.slim_window_query(q_win, Hkv)),
         ("k_proj_all_rope_score", "mfma", 2 * N * Hd * Hkv * d,
          lambda: lin_rope(x, wd["wk"], bk, rope_all, N, Hkv, rstd_all, k_all, qt, tsc)),
@@ -126,8 +126,8 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
         ("compact_x", "hbm", 2 * n * Hd * es + n * 8, compact),
         ("compact_k", "hbm", 2 * n * Hkv * d * es, compact_k),
         ("compact_rstd", "latency", 2 * n * 4, compact_rstd),
-        ("rope_table_kept", "alu", n * d * 4, lambda: slim.slim_rope_table(pc, n, d, wl.rope_theta)),
-        ("q_proj_rope", "mfma", 2 * n * Hd * Hq * d, lambda: lin_rope(xc, wd["wq"], bq, rope_kept, n, Hq, rstd_kept, q)),
+        ("q_proj", "mfma", 2 * n * Hd * Hq * d, lambda: lin_scaled(xc, wd["wq"], bq, rstd_kept, n, Hq * d, q)),
+        ("rope_q", "hbm", 2 * n * Hq * d * es, lambda: slim.slim_rope(q, pc, wl.rope_theta)),
         ("v_proj", "mfma", 2 * n * Hd * Hkv * d, lambda: lin_scaled(xc, wd["wv"], bv, rstd_kept, n, Hkv * d, v)),
         ("prefill_attn", "mfma", 2 * n * n * d * Hq, lambda: slim.slim_prefill_attn(q, k, v, out=o)),
         ("o_proj_residual", "mfma", 2 * n * Hd * Hq * d,

@@ -674,8 +674,11 @@ static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_
         if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
     }
     if (M <= 128) {
+        // Few rows: the launch streams the weights once and is bound by how many workgroups pull on memory at the same
+        // time, so wide outputs use 64-feature tiles (twice the workgroups of the 128-feature ones).
         if constexpr (EPI == EPI_SWIGLU) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
         else if constexpr (EPI == EPI_ROPE) return launch_bf16<4, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
+        else if (N >= 2048) return launch_bf16<1, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
         else return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
     }
     const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;

@@ -148,16 +148,21 @@ int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int d
 }
 
 // cos / sin table for the RoPE epilogue of the projections: table[t][0..half) = cos(pos[t] * inv_freq[i]),
-// table[t][half..2*half) = sin, angles and sincos in double as in rope_kernel, rounded to float.
+// table[t][half..2*half) = sin.  The angle is formed in double and reduced to [-pi, pi] in double (two-term
+// 2*pi), then evaluated in float: within 3e-7 of the double result, four orders below a bf16 rounding, at a
+// fraction of the cost of a double sincos.
 __global__ void __launch_bounds__(256) rope_table_kernel(const int* __restrict__ pos, int pos0, int n, int half,
                                                          RopeFreq fr, float* __restrict__ table) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int t = idx / half, i = idx - t * half;
     if (t >= n) return;
-    double sn, cs;
-    sincos((double)(pos ? pos[t] : pos0 + t) * fr.inv_freq[i], &sn, &cs);
-    table[(size_t)t * 2 * half + i] = (float)cs;
-    table[(size_t)t * 2 * half + half + i] = (float)sn;
+    const double a = (double)(pos ? pos[t] : pos0 + t) * fr.inv_freq[i];
+    const double k = rint(a * 0.15915494309189535);                       // a / (2 pi)
+    const double r = fma(-k, 2.4492935982947064e-16, fma(-k, 6.283185307179586, a));
+    float sn, cs;
+    sincosf((float)r, &sn, &cs);
+    table[(size_t)t * 2 * half + i] = cs;
+    table[(size_t)t * 2 * half + half + i] = sn;
 }
 
 int launch_rope_table(const int* pos, int pos0, int n, int d, float theta, float* table, hipStream_t st) {
