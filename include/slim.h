@@ -203,6 +203,15 @@ int slim_rmsnorm_linear(const void* a, int lda, const void* w, const void* bias,
 int slim_rmsnorm_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w_up, const float* rstd,
                                int m, int n_out, int k_in, int ldo, int dtype, void* out, void* stream);
 int slim_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, void* stream);
+/* Two projections of the same rows in one launch (the layer's Query and Value projections: one launch of
+ * n_1 + n_2 features fills the chip better than one of n_1 and one of n_2):
+ *   out_1[m, n_1] = s . (a . w_1^T) + bias_1,   out_2[m, n_2] = s . (a . w_2^T) + bias_2,
+ * s = rstd[m] (fused RMSNorm as above) or 1 when rstd is NULL; both biases or neither.  Results are bit-identical
+ * to the two single launches.  bf16 only, m > 128, k_in % 64 == 0, lda % 8 == 0, 16-byte aligned pointers;
+ * UNSUPPORTED otherwise. */
+int slim_linear_pair(const void* a, int lda, const void* w_1, const void* bias_1, int n_1, int ldo_1, void* out_1,
+                     const void* w_2, const void* bias_2, int n_2, int ldo_2, void* out_2, const float* rstd,
+                     int m, int k_in, int dtype, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * The pruned prefill layer: score -> select -> compact -> attention -> FFN on the kept tokens.

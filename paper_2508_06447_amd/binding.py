@@ -25,7 +25,7 @@ EXPORTS = (
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
     "slim_kv_swap_workspace_bytes", "slim_kv_swap",
     "slim_rope_table", "slim_window_query", "slim_linear_rope", "slim_score_blocks_from_token_scores",
-    "slim_row_rstd", "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
+    "slim_linear_pair", "slim_row_rstd", "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
@@ -82,6 +82,7 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_window_query.argtypes = [vp, i, i, i, i, i, vp, vp]
     lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
     lib.slim_row_rstd.argtypes = [vp, i, i, f, i, vp, vp]
+    lib.slim_linear_pair.argtypes = [vp, i, vp, vp, i, i, vp, vp, vp, i, i, vp, vp, i, i, i, vp]
     lib.slim_rmsnorm_linear.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, vp, vp]
     lib.slim_rmsnorm_swiglu_linear.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, vp, vp]
     lib.slim_fold_gain.argtypes = [vp, vp, i, i, i, vp, vp]
@@ -263,6 +264,20 @@ def slim_score_blocks_from_token_scores(token_scores: torch.Tensor, block: int, 
     _check(lib.slim_score_blocks_from_token_scores(_dev(token_scores, "token_scores"), N, H, block, unit,
                                                    _dev(scores, "scores"), _stream()), "slim_score_blocks_from_token_scores")
     return scores
+
+
+def slim_linear_pair(a: torch.Tensor, w_1: torch.Tensor, w_2: torch.Tensor, bias_1: torch.Tensor | None = None,
+                     bias_2: torch.Tensor | None = None, rstd: torch.Tensor | None = None):
+    """(a . w_1^T + bias_1, a . w_2^T + bias_2), rows scaled by rstd if given, in one launch."""
+    lib = load_library()
+    m, k_in = a.shape
+    n1, n2 = w_1.shape[0], w_2.shape[0]
+    o1 = torch.empty(m, n1, dtype=a.dtype, device=a.device)
+    o2 = torch.empty(m, n2, dtype=a.dtype, device=a.device)
+    _check(lib.slim_linear_pair(_dev(a, "a"), a.stride(0), _dev(w_1, "w_1"), _dev(bias_1, "bias_1"), n1, n1, _dev(o1, "o1"),
+                                _dev(w_2, "w_2"), _dev(bias_2, "bias_2"), n2, n2, _dev(o2, "o2"), _dev(rstd, "rstd"), m, k_in,
+                                _dtype_code(a), _stream()), "slim_linear_pair")
+    return o1, o2
 
 
 def slim_row_rstd(x: torch.Tensor, eps: float) -> torch.Tensor:

@@ -172,6 +172,19 @@ int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, co
                               (hipStream_t)stream);
 }
 
+int slim_linear_pair(const void* a, int lda, const void* w_1, const void* bias_1, int n_1, int ldo_1, void* out_1,
+                     const void* w_2, const void* bias_2, int n_2, int ldo_2, void* out_2, const float* rstd, int m,
+                     int k_in, int dtype, void* stream) {
+    if (!a || !w_1 || !w_2 || !out_1 || !out_2 || m < 1 || n_1 < 1 || n_2 < 1 || k_in < 1 || lda < k_in || ldo_1 < n_1 ||
+        ldo_2 < n_2 || !bias_1 != !bias_2)
+        return SLIM_INVALID_ARG;
+    if (dtype != SLIM_BF16 || k_in % 64 != 0 || lda % 8 != 0 || m <= 128 || !aligned16(a) || !aligned16(w_1) ||
+        !aligned16(w_2) || (bias_1 && (!aligned16(bias_1) || !aligned16(bias_2))))
+        return SLIM_UNSUPPORTED;
+    return launch_linear_pair(a, lda, w_1, bias_1, n_1, ldo_1, out_1, w_2, bias_2, n_2, ldo_2, out_2, rstd, m, k_in,
+                              (hipStream_t)stream);
+}
+
 int slim_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, void* stream) {
     if (!x || !rstd || n < 1 || hidden < 1 || !(eps >= 0.f)) return SLIM_INVALID_ARG;
     if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
@@ -376,6 +389,17 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         int r = project(a, sc, wmat, bias, m, heads * d, out);
         return r ? r : launch_rope(out, pos_, pos0, m, heads, d, s->rope_theta, dt, st);
     };
+    // Query (+ RoPE) and Value states of m rows.  One launch for both projections where the kernel covers it.
+    auto project_qv = [&](const void* a, const float* sc, const int* pos_, int m, void* q_out, void* v_out) -> int {
+        int r;
+        if (dt == SLIM_BF16 && Hd % 64 == 0 && m > 128 && !w->bq == !w->bv)
+            r = launch_linear_pair(a, Hd, w->wq, w->bq, qd, qd, q_out, w->wv, w->bv, kvd, kvd, v_out, sc, m, Hd, st);
+        else {
+            r = project(a, sc, w->wq, w->bq, m, qd, q_out);
+            if (!r) r = project(a, sc, w->wv, w->bv, m, kvd, v_out);
+        }
+        return r ? r : launch_rope(q_out, pos_, 0, m, Hq, d, s->rope_theta, dt, st);
+    };
     auto block_scores = [&](const void* q_window, int w_eff, float* scores) -> int {
         if (fused_score) return launch_token_score_blocks(tscore, N, Hkv, s->block, s->unit, scores, st);
         return launch_score(q_window, k_all, N, w_eff, Hq, Hkv, d, s->block, s->unit, s->scoring, dt, scores, qt, st);
@@ -401,11 +425,10 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
-        SLIM_TRY(project_rope(rows_in, sc_in, w->wq, w->bq, pos_in, 0, N, Hq, qc, nullptr, nullptr, nullptr));
+        SLIM_TRY(project_qv(rows_in, sc_in, pos_in, N, qc, vc));
         const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
         if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
         SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, ktab, fused_score ? qt : nullptr, tscore));
-        SLIM_TRY(project(rows_in, sc_in, w->wv, w->bv, N, kvd, vc));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(block_scores(q_last, w_eff, scores));
@@ -449,8 +472,7 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     }
 
     // Q, V of the rows that continue; RoPE on Q at the original positions.
-    SLIM_TRY(project_rope(rows, sc, w->wq, w->bq, pos, 0, n, Hq, qc, nullptr, nullptr, nullptr));
-    SLIM_TRY(project(rows, sc, w->wv, w->bv, n, kvd, vc));
+    SLIM_TRY(project_qv(rows, sc, pos, n, qc, vc));
     SLIM_TRY(launch_attn(qc, kc, vc, n, Hq, Hkv, d, 0.f, dt, o, st));
     }
     // y = resid + Wo o  (into x_out);  z = y + Wdown(silu(Wgate r) * Wup r), r = RMSNorm(y)  (in place)

@@ -25,14 +25,20 @@
 namespace slim {
 
 enum { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_BIAS = 3, EPI_ROPE = 4 };
-// EPI_BIAS: R is a bias vector [N].  EPI_ROPE: R is a bias vector or null, the rest comes in a RopeEpi.
+// EPI_BIAS: R is a bias vector [N].  EPI_ROPE: R is a bias vector or null, the rest comes in a EpiExtra.
 
-// Extra operands: of the RoPE epilogue (heads of 128 features, one head per wave tile), and of the fused RMSNorm.
-struct RopeEpi {
+// Extra operands: of the RoPE epilogue (heads of 128 features, one head per wave tile), of the fused RMSNorm, and
+// of a second projection of the same rows carried by the same launch.
+struct EpiExtra {
     const float* table = nullptr;        // [M][128]: cos of the 64 rotation angles of the token, then their sin
     const float* qt = nullptr;           // [N] float or null: head-group-summed window query (Eq. 2 by linearity)
     float* token_scores = nullptr;       // [M][N/128]: rotated, rounded key of (token, head) dotted with its part of qt
     const float* row_scale = nullptr;    // [M] float or null: out row m = row_scale[m] * (a[m,:] . w^T) (fused RMSNorm)
+    // Second projection (two-size launch only): feature tiles tiles_n1.. belong to it.
+    const bf16_t* w_2 = nullptr;         // [n_2][K]
+    const bf16_t* r_2 = nullptr;         // its bias (EPI_BIAS)
+    bf16_t* c_2 = nullptr;               // [M][ldo_2]
+    int n_2 = 0, ldo_2 = 0, tiles_n1 = 0;
 };
 
 constexpr int BK = 64;                                   // k-depth of an LDS tile (8 chunks of 16 bytes)
@@ -168,7 +174,7 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
 template <int TA>
 __device__ __forceinline__ void store_tile_rope(f32x16 (&acc)[1][4][TA], const bf16_t* bias, bf16_t* C, int ldo, int M,
                                                 int N, int mw, int nw, int lane, unsigned char* region,
-                                                const RopeEpi& re) {
+                                                const EpiExtra& re) {
     constexpr int TW = 4, CPR = TW * 4, RB = TW * 64, ROWS = TA * 32, RPI = 64 / CPR;
     if (nw >= N) return;                                 // wave-uniform: no head here (N is a multiple of 128)
     const int l32 = lane & 31, hh = lane >> 5;
@@ -259,7 +265,7 @@ __device__ __forceinline__ void tile_of_workgroup(int L, bool xcd_runs, int tile
 template <int TW, int TA, int WGN, int WGM, int EPI>
 __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
                                           const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
-                                          int N, int K, int m0, int n0, unsigned char* lds, const RopeEpi& re) {
+                                          int N, int K, int m0, int n0, unsigned char* lds, const EpiExtra& re) {
     static_assert(WGN * WGM == 8, "8 waves");
     static_assert(EPI != EPI_ROPE || TW == 4, "the RoPE epilogue needs one 128-wide head per wave");
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
@@ -417,7 +423,7 @@ __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict
                                                         const bf16_t* __restrict__ W0,
                                                         const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C,
                                                         int ldo, int M, int N, int K, int tiles_m, int tiles_n,
-                                                        RopeEpi re) {
+                                                        EpiExtra re) {
     extern __shared__ __align__(16) unsigned char lds[];
     int tm, tn;
     tile_of_workgroup(blockIdx.x, true, tiles_m, tiles_n, tm, tn);
@@ -446,19 +452,23 @@ __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* _
                                                                  const bf16_t* __restrict__ W1, const bf16_t* R,
                                                                  bf16_t* C, int ldo, int M, int N, int K,
                                                                  int big_tiles_m, int small_tiles_m, int tiles_n,
-                                                                 RopeEpi re) {
+                                                                 EpiExtra re) {
     using S = TileShapes<EPI>;
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_big = big_tiles_m * tiles_n;
+    const bool big = (int)blockIdx.x < n_big;
     int tm, tn;
-    if ((int)blockIdx.x < n_big) {
-        tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
+    if (big) tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
+    else tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
+    if (re.w_2 && tn >= re.tiles_n1) {                   // a feature tile of the second projection
+        W0 = re.w_2; R = re.r_2; C = re.c_2; N = re.n_2; ldo = re.ldo_2;
+        tn -= re.tiles_n1;
+    }
+    if (big)
         gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
-    } else {
-        tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
+    else
         gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI>(
             A, lda, W0, W1, R, C, ldo, M, N, K, big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, re);
-    }
 }
 
 // Generic kernel (any k_in that is a multiple of 8): register-staged loads with k predicates.
@@ -563,7 +573,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_generic_kernel(const bf16_t* __
 
 template <int TW, int TA, int WGN, int WGM, int EPI, bool GENERIC>
 static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
-                       int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
+                       int ldo, int M, int N, int K, hipStream_t st, const EpiExtra& re = EpiExtra()) {
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int BN = 32 * TW * WGN, BM = 32 * TA * WGM;
     constexpr size_t smem = 2 * (size_t)(BN * NW + BM) * BK * 2;
@@ -637,7 +647,7 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
 template <int EPI>
 static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
                            int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st,
-                           const RopeEpi& re = RopeEpi()) {
+                           const EpiExtra& re = EpiExtra()) {
     using S = TileShapes<EPI>;
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
@@ -648,7 +658,7 @@ static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf1
         if (e != hipSuccess) return set_hip_error(e);
         attr_done = true;
     }
-    const int tiles_n = (N + S::BN - 1) / S::BN;
+    const int tiles_n = (N + S::BN - 1) / S::BN + (re.w_2 ? (re.n_2 + S::BN - 1) / S::BN : 0);
     const int small_tiles_m = (M - big_tiles_m * S::BM_BIG + S::BM_SMALL - 1) / S::BM_SMALL;
     hipLaunchKernelGGL(kern, dim3((big_tiles_m + small_tiles_m) * tiles_n), dim3(512), smem, st, A, lda, W0, W1, R, C,
                        ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n, re);
@@ -669,7 +679,7 @@ static int cu_count() {
 
 template <int EPI>
 static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
-                         int ldo, int M, int N, int K, hipStream_t st, const RopeEpi& re = RopeEpi()) {
+                         int ldo, int M, int N, int K, hipStream_t st, const EpiExtra& re = EpiExtra()) {
     if constexpr (EPI != EPI_ROPE) {                     // (row_scale and RoPE callers have checked K % 64 == 0)
         if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
     }
@@ -746,7 +756,7 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const float* __restrict__
 int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, const float* qt,
                        float* token_scores, const float* row_scale, int m, int n_heads, int k_in, int ldo, void* out,
                        hipStream_t st) {
-    RopeEpi re;
+    EpiExtra re;
     re.table = table;
     re.qt = qt;
     re.token_scores = token_scores;
@@ -759,13 +769,41 @@ int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, 
 // the caller).
 int launch_linear_scaled(const void* a, int lda, const void* w0, const void* w1, const void* bias, const float* row_scale,
                          int m, int n_out, int k_in, int ldo, void* out, hipStream_t st) {
-    RopeEpi re;
+    EpiExtra re;
     re.row_scale = row_scale;
     const bf16_t *A = (const bf16_t*)a, *W0 = (const bf16_t*)w0, *W1 = (const bf16_t*)w1, *B = (const bf16_t*)bias;
     bf16_t* C = (bf16_t*)out;
     if (w1) return dispatch_bf16<EPI_SWIGLU>(A, lda, W0, W1, nullptr, C, ldo, m, n_out, k_in, st, re);
     if (bias) return dispatch_bf16<EPI_BIAS>(A, lda, W0, nullptr, B, C, ldo, m, n_out, k_in, st, re);
     return dispatch_bf16<EPI_PLAIN>(A, lda, W0, nullptr, nullptr, C, ldo, m, n_out, k_in, st, re);
+}
+
+// Two projections of the same rows in one launch (the Query and Value projections of the continuing tokens): the
+// second one's feature tiles follow the first one's, so the launch fills the chip as one problem of n_1 + n_2
+// features.  Both with a bias or both without.  bf16, k_in % 64 == 0, m > 128 (checked by the caller).
+int launch_linear_pair(const void* a, int lda, const void* w_1, const void* bias_1, int n_1, int ldo_1, void* out_1,
+                       const void* w_2, const void* bias_2, int n_2, int ldo_2, void* out_2, const float* row_scale,
+                       int m, int k_in, hipStream_t st) {
+    EpiExtra re;
+    re.row_scale = row_scale;
+    re.w_2 = (const bf16_t*)w_2;
+    re.r_2 = (const bf16_t*)bias_2;
+    re.c_2 = (bf16_t*)out_2;
+    re.n_2 = n_2;
+    re.ldo_2 = ldo_2;
+    const bf16_t *A = (const bf16_t*)a, *W = (const bf16_t*)w_1, *B = (const bf16_t*)bias_1;
+    if (bias_1) {
+        using S = TileShapes<EPI_BIAS>;
+        re.tiles_n1 = (n_1 + S::BN - 1) / S::BN;
+        const int tiles_n = re.tiles_n1 + (n_2 + S::BN - 1) / S::BN;
+        return launch_two_size<EPI_BIAS>(A, lda, W, nullptr, B, (bf16_t*)out_1, ldo_1, m, n_1, k_in,
+                                         plan_big_tiles(m, tiles_n, cu_count(), 0.5), st, re);
+    }
+    using S = TileShapes<EPI_PLAIN>;
+    re.tiles_n1 = (n_1 + S::BN - 1) / S::BN;
+    const int tiles_n = re.tiles_n1 + (n_2 + S::BN - 1) / S::BN;
+    return launch_two_size<EPI_PLAIN>(A, lda, W, nullptr, nullptr, (bf16_t*)out_1, ldo_1, m, n_1, k_in,
+                                      plan_big_tiles(m, tiles_n, cu_count(), 0.5), st, re);
 }
 
 // At most one of w1 (SwiGLU), residual and bias is set.

@@ -110,6 +110,9 @@ int launch_linear_rope(const void* a, int lda, const void* w, const void* bias, 
                        hipStream_t st);
 int launch_linear_scaled(const void* a, int lda, const void* w0, const void* w1, const void* bias, const float* row_scale,
                          int m, int n_out, int k_in, int ldo, void* out, hipStream_t st);
+int launch_linear_pair(const void* a, int lda, const void* w_1, const void* bias_1, int n_1, int ldo_1, void* out_1,
+                       const void* w_2, const void* bias_2, int n_2, int ldo_2, void* out_2, const float* row_scale,
+                       int m, int k_in, hipStream_t st);
 int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st);
 int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, hipStream_t st);
 int launch_window_query(const void* q_win, int w, int Hq, int Hkv, int d, int dtype, float* qtilde, hipStream_t st);

@@ -324,6 +324,28 @@ def test_rmsnorm_fused_into_projections(slim, m, n, k):
     np.testing.assert_allclose(got32.cpu().numpy(), w32 * gain.to(torch.float32).numpy()[None, :], rtol=1e-6)
 
 
+@pytest.mark.parametrize("m,n1,n2,k,bias,scaled", [
+    (1300, 4096, 1024, 128, False, True), (700, 3584, 512, 192, True, True), (300, 260, 72, 64, False, False),
+    (2000, 256, 256, 64, True, False),
+])
+def test_two_projections_in_one_launch_are_bit_identical_to_two_launches(slim, m, n1, n2, k, bias, scaled):
+    print(f"linear pair m={m} n1={n1} n2={n2} k={k} bias={bias} scaled={scaled}", flush=True)
+    bf = torch.bfloat16
+    a, w1, w2 = dev(rand((m, k), bf, 1, 2.0)), dev(rand((n1, k), bf, 2, 0.05)), dev(rand((n2, k), bf, 3, 0.05))
+    b1, b2 = (dev(rand((n1,), bf, 4)), dev(rand((n2,), bf, 5))) if bias else (None, None)
+    rstd = slim.slim_row_rstd(a, 1e-5) if scaled else None
+    o1, o2 = slim.slim_linear_pair(a, w1, w2, b1, b2, rstd)
+    if scaled:
+        r1, r2 = slim.slim_rmsnorm_linear(a, w1, rstd, bias=b1), slim.slim_rmsnorm_linear(a, w2, rstd, bias=b2)
+    elif bias:
+        r1, r2 = slim.slim_linear_bias(a, w1, b1), slim.slim_linear_bias(a, w2, b2)
+    else:
+        r1, r2 = slim.slim_linear(a, w1), slim.slim_linear(a, w2)
+    assert torch.equal(o1, r1) and torch.equal(o2, r2)
+    want = (so.rmsnorm(f64(a), np.ones(k), 1e-5) if scaled else f64(a)) @ f64(w2).T + (f64(b2) if bias else 0.0)
+    np.testing.assert_allclose(f64(o2), want, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(want).max())
+
+
 def test_rmsnorm_and_rope_in_one_projection(slim):
     m, heads, k, d, theta, eps = 700, 4, 256, 128, 500000.0, 1e-5
     bf = torch.bfloat16
