@@ -408,13 +408,14 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     const void* rows_in = x_in;        // what the projections of the incoming tokens read
     const float* sc_in = nullptr;
     if (fold_attn) {
-        SLIM_TRY(launch_row_rstd(x_in, N, Hd, s->rms_eps, dt, rstd_in, st));
+        // (the same pass over the rows leaves the cos / sin table of their positions for the Key projection)
+        SLIM_TRY(launch_row_rstd(x_in, N, Hd, s->rms_eps, dt, rstd_in, st, pos_in, d, s->rope_theta, fused ? table : nullptr));
         sc_in = rstd_in;
     } else {
         SLIM_TRY(launch_rmsnorm(x_in, w->g_attn, N, Hd, s->rms_eps, dt, h, st));
         rows_in = h;
     }
-    if (fused) SLIM_TRY(launch_rope_table(pos_in, 0, N, d, s->rope_theta, table, st));
+    if (fused && !fold_attn) SLIM_TRY(launch_rope_table(pos_in, 0, N, d, s->rope_theta, table, st));
     const float* ktab = fused ? table : nullptr;   // cos/sin rows of the incoming tokens, for the Key projection
 
     const void* resid = x_in;          // residual stream entering the attention branch
@@ -453,12 +454,25 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
         SLIM_TRY(block_scores(q_win, w_eff, scores));
         SLIM_TRY(launch_select(scores, p.nb, n_keep, s->flags, kept_blocks_out, st));
-        // Hidden rows + positions into x_out / pos_out, keys into kc.
-        SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
-        SLIM_TRY(launch_compact(k_all, nullptr, kept_blocks_out, n_keep, s->block, N, kvd, dt, kc, nullptr, st));
+        // Hidden rows + positions into x_out / pos_out, keys into kc, and with folded gains the rows' statistics
+        // (those of the kept rows are the compacted ones): one launch.
+        {
+            const void* srcs[3] = {x_in, k_all, rstd_in};
+            void* dsts[3] = {x_out, kc, rstd_kept};
+            const size_t rb[3] = {(size_t)Hd * es, (size_t)kvd * es, sizeof(float)};
+            if ((Hd * es) % 4 == 0 && (kvd * es) % 4 == 0)
+                SLIM_TRY(launch_compact_multi(fold_attn ? 3 : 2, srcs, dsts, rb, pos_in, pos_out, kept_blocks_out, n_keep,
+                                              s->block, N, st));
+            else {
+                SLIM_TRY(launch_compact(x_in, pos_in, kept_blocks_out, n_keep, s->block, N, Hd, dt, x_out, pos_out, st));
+                SLIM_TRY(launch_compact(k_all, nullptr, kept_blocks_out, n_keep, s->block, N, kvd, dt, kc, nullptr, st));
+                if (fold_attn)
+                    SLIM_TRY(launch_compact(rstd_in, nullptr, kept_blocks_out, n_keep, s->block, N, 1, SLIM_F32, rstd_kept,
+                                            nullptr, st));
+            }
+        }
         rows = x_out;
-        if (fold_attn) {                 // the kept rows' statistics are the compacted ones
-            SLIM_TRY(launch_compact(rstd_in, nullptr, kept_blocks_out, n_keep, s->block, N, 1, SLIM_F32, rstd_kept, nullptr, st));
+        if (fold_attn) {
             sc = rstd_kept;
         } else {
             SLIM_TRY(launch_rmsnorm(x_out, w->g_attn, n, Hd, s->rms_eps, dt, h, st));

@@ -95,38 +95,6 @@ int launch_rope(void* x, const int* pos, int pos0, int n, int H, int d, float th
     return check_launch();
 }
 
-// rstd[t] = 1 / sqrt(mean(x[t, :]^2) + eps): the row statistic of RMSNorm alone, for projections that apply it to
-// their accumulators instead of reading a normalised copy.  One wave per row, 4 rows per workgroup.
-template <typename T>
-__global__ void __launch_bounds__(256) row_rstd_kernel(const T* __restrict__ x, int n, int hidden, float eps,
-                                                       float* __restrict__ rstd) {
-    constexpr int V = Elem<T>::kVec;
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (t >= n) return;
-    const T* row = x + (size_t)t * hidden;
-    float ss = 0.f;
-    if (hidden % V == 0 && (((uintptr_t)row) & 15) == 0) {
-        for (int c = lane; c < hidden / V; c += 64) {
-            float f[V];
-            Elem<T>::unpack(*reinterpret_cast<const uint4*>(row + (size_t)c * V), f);
-#pragma unroll
-            for (int i = 0; i < V; ++i) ss += f[i] * f[i];
-        }
-    } else {
-        for (int c = lane; c < hidden; c += 64) { const float v = Elem<T>::ld(row + c); ss += v * v; }
-    }
-    ss = wave_sum(ss);
-    if (lane == 0) rstd[t] = 1.0f / sqrtf(ss / (float)hidden + eps);
-}
-
-int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st) {
-    if (dtype == SLIM_BF16)
-        hipLaunchKernelGGL(row_rstd_kernel<bf16_t>, dim3((n + 3) / 4), dim3(256), 0, st, (const bf16_t*)x, n, hidden, eps, rstd);
-    else
-        hipLaunchKernelGGL(row_rstd_kernel<float>, dim3((n + 3) / 4), dim3(256), 0, st, (const float*)x, n, hidden, eps, rstd);
-    return check_launch();
-}
-
 // out[n, k] = w[n, k] * gain[k]: folds an RMSNorm gain into the weights of the projection that follows it.
 template <typename T>
 __global__ void __launch_bounds__(256) fold_gain_kernel(const T* __restrict__ w, const T* __restrict__ gain, size_t total,
@@ -147,27 +115,86 @@ int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int d
     return check_launch();
 }
 
-// cos / sin table for the RoPE epilogue of the projections: table[t][0..half) = cos(pos[t] * inv_freq[i]),
-// table[t][half..2*half) = sin.  The angle is formed in double and reduced to [-pi, pi] in double (two-term
+// One rotation angle's cos / sin: the angle is formed in double and reduced to [-pi, pi] in double (two-term
 // 2*pi), then evaluated in float: within 3e-7 of the double result, four orders below a bf16 rounding, at a
 // fraction of the cost of a double sincos.
+__device__ __forceinline__ void rope_cos_sin(double pos, double inv_freq, float& cs, float& sn) {
+    const double a = pos * inv_freq;
+    const double k = rint(a * 0.15915494309189535);                      // a / (2 pi)
+    const double r = fma(-k, 2.4492935982947064e-16, fma(-k, 6.283185307179586, a));
+    sincosf((float)r, &sn, &cs);
+}
+
+// rstd[t] = 1 / sqrt(mean(x[t, :]^2) + eps): the row statistic of RMSNorm alone, for projections that apply it to
+// their accumulators instead of reading a normalised copy.  One wave per row, 4 rows per workgroup.  With a table
+// pointer the wave also writes the row's cos / sin table entry (see rope_table_kernel): lane i takes angle i, and
+// the arithmetic hides under the row's memory traffic.
+template <typename T>
+__global__ void __launch_bounds__(256) row_rstd_kernel(const T* __restrict__ x, int n, int hidden, float eps,
+                                                       float* __restrict__ rstd, const int* __restrict__ pos, int half,
+                                                       RopeFreq fr, float* __restrict__ table) {
+    constexpr int V = Elem<T>::kVec;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= n) return;
+    const T* row = x + (size_t)t * hidden;
+    float ss = 0.f;
+    if (hidden % V == 0 && (((uintptr_t)row) & 15) == 0) {
+        for (int c = lane; c < hidden / V; c += 64) {
+            float f[V];
+            Elem<T>::unpack(*reinterpret_cast<const uint4*>(row + (size_t)c * V), f);
+#pragma unroll
+            for (int i = 0; i < V; ++i) ss += f[i] * f[i];
+        }
+    } else {
+        for (int c = lane; c < hidden; c += 64) { const float v = Elem<T>::ld(row + c); ss += v * v; }
+    }
+    if (table) {
+        const double ps = (double)(pos ? pos[t] : t);
+        for (int i = lane; i < half; i += 64) {
+            float cs, sn;
+            rope_cos_sin(ps, fr.inv_freq[i], cs, sn);
+            table[(size_t)t * 2 * half + i] = cs;
+            table[(size_t)t * 2 * half + half + i] = sn;
+        }
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) rstd[t] = 1.0f / sqrtf(ss / (float)hidden + eps);
+}
+
+static RopeFreq rope_freq(int d, float theta) {
+    RopeFreq fr;
+    for (int i = 0; i < d / 2; ++i) fr.inv_freq[i] = pow((double)theta, -2.0 * (double)i / (double)d);
+    return fr;
+}
+
+// table != null: also the cos / sin table of the rows' positions (pos null = 0..n-1) for head_dim d.
+int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st,
+                    const int* pos, int d, float theta, float* table) {
+    const RopeFreq fr = table ? rope_freq(d, theta) : RopeFreq();
+    if (dtype == SLIM_BF16)
+        hipLaunchKernelGGL(row_rstd_kernel<bf16_t>, dim3((n + 3) / 4), dim3(256), 0, st, (const bf16_t*)x, n, hidden, eps, rstd,
+                           pos, d / 2, fr, table);
+    else
+        hipLaunchKernelGGL(row_rstd_kernel<float>, dim3((n + 3) / 4), dim3(256), 0, st, (const float*)x, n, hidden, eps, rstd,
+                           pos, d / 2, fr, table);
+    return check_launch();
+}
+
+// cos / sin table for the RoPE epilogue of the projections: table[t][0..half) = cos(pos[t] * inv_freq[i]),
+// table[t][half..2*half) = sin.
 __global__ void __launch_bounds__(256) rope_table_kernel(const int* __restrict__ pos, int pos0, int n, int half,
                                                          RopeFreq fr, float* __restrict__ table) {
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     const int t = idx / half, i = idx - t * half;
     if (t >= n) return;
-    const double a = (double)(pos ? pos[t] : pos0 + t) * fr.inv_freq[i];
-    const double k = rint(a * 0.15915494309189535);                       // a / (2 pi)
-    const double r = fma(-k, 2.4492935982947064e-16, fma(-k, 6.283185307179586, a));
-    float sn, cs;
-    sincosf((float)r, &sn, &cs);
+    float cs, sn;
+    rope_cos_sin((double)(pos ? pos[t] : pos0 + t), fr.inv_freq[i], cs, sn);
     table[(size_t)t * 2 * half + i] = cs;
     table[(size_t)t * 2 * half + half + i] = sn;
 }
 
 int launch_rope_table(const int* pos, int pos0, int n, int d, float theta, float* table, hipStream_t st) {
-    RopeFreq fr;
-    for (int i = 0; i < d / 2; ++i) fr.inv_freq[i] = pow((double)theta, -2.0 * (double)i / (double)d);
+    const RopeFreq fr = rope_freq(d, theta);
     const long long threads = (long long)n * (d / 2);
     hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, pos, pos0, n, d / 2, fr,
                        table);

@@ -515,4 +515,78 @@ int launch_compact(const void* src, const int* pos_in, const int* kept, int n_ke
     return check_launch();
 }
 
+// Several arrays compacted by the same kept set in one launch (hidden rows + positions, keys, row statistics):
+// grid = (chunks of the widest array's block run, kept blocks, arrays).  Rows are multiples of 4 bytes; a run is
+// moved in 16-byte vectors when it allows, else in words.
+struct CompactSegs {
+    const unsigned char* src[4];
+    unsigned char* dst[4];
+    unsigned long long row_bytes[4];
+    int n;
+};
+
+__global__ void __launch_bounds__(kCopyThreads) compact_multi_kernel(CompactSegs segs, const int* __restrict__ kept,
+                                                                     int block, int N, int nb,
+                                                                     const int* __restrict__ pos_in,
+                                                                     int* __restrict__ pos_out) {
+    const int i = blockIdx.y, a = blockIdx.z;
+    const int kb = kept[i];
+    if ((unsigned)kb >= (unsigned)nb) return;
+    const int rows = min(block, N - kb * block);
+    const size_t rb = segs.row_bytes[a];
+    const size_t run = (size_t)rows * rb;
+    const unsigned char* s = segs.src[a] + (size_t)kb * block * rb;
+    unsigned char* d = segs.dst[a] + (size_t)i * block * rb;
+    if (((rb * block) % 16 == 0) && (run % 16 == 0) && ((((uintptr_t)segs.src[a]) | ((uintptr_t)segs.dst[a])) & 15) == 0) {
+        const u32x4* sv = reinterpret_cast<const u32x4*>(s);
+        u32x4* dv = reinterpret_cast<u32x4*>(d);
+        const size_t seg = run / 16;
+        const size_t base = (size_t)blockIdx.x * (kCopyThreads * kCopyVecs) + threadIdx.x;
+        u32x4 tmp[kCopyVecs];
+#pragma unroll
+        for (int u = 0; u < kCopyVecs; ++u) {
+            const size_t o = base + (size_t)u * kCopyThreads;
+            if (o < seg) tmp[u] = __builtin_nontemporal_load(sv + o);
+        }
+#pragma unroll
+        for (int u = 0; u < kCopyVecs; ++u) {
+            const size_t o = base + (size_t)u * kCopyThreads;
+            if (o < seg) __builtin_nontemporal_store(tmp[u], dv + o);
+        }
+    } else {
+        const uint32_t* sw = reinterpret_cast<const uint32_t*>(s);
+        uint32_t* dw = reinterpret_cast<uint32_t*>(d);
+        const size_t seg = run / 4;
+        for (size_t o = (size_t)blockIdx.x * kCopyThreads + threadIdx.x; o < seg; o += (size_t)gridDim.x * kCopyThreads)
+            dw[o] = sw[o];
+    }
+    if (a == 0 && blockIdx.x == 0 && pos_out) {
+        for (int r = threadIdx.x; r < rows; r += kCopyThreads) {
+            const int t = kb * block + r;
+            pos_out[(size_t)i * block + r] = pos_in ? pos_in[t] : t;
+        }
+    }
+}
+
+// Up to 4 arrays [N, row_bytes[a]] -> [n', row_bytes[a]]; positions ride with array 0.  row_bytes % 4 == 0.
+int launch_compact_multi(int n_arrays, const void* const* src, void* const* dst, const size_t* row_bytes, const int* pos_in,
+                         int* pos_out, const int* kept, int n_keep, int block, int N, hipStream_t st) {
+    CompactSegs segs;
+    size_t widest = 0;
+    segs.n = n_arrays;
+    for (int a = 0; a < 4; ++a) {
+        const bool on = a < n_arrays;
+        segs.src[a] = on ? (const unsigned char*)src[a] : nullptr;
+        segs.dst[a] = on ? (unsigned char*)dst[a] : nullptr;
+        segs.row_bytes[a] = on ? row_bytes[a] : 0;
+        if (on && row_bytes[a] > widest) widest = row_bytes[a];
+    }
+    const size_t per = (size_t)kCopyThreads * kCopyVecs * 16;
+    const size_t chunks = ((size_t)block * widest + per - 1) / per;
+    const int nb = (N + block - 1) / block;
+    hipLaunchKernelGGL(compact_multi_kernel, dim3((unsigned)chunks, n_keep, n_arrays), dim3(kCopyThreads), 0, st, segs, kept,
+                       block, N, nb, pos_in, pos_out);
+    return check_launch();
+}
+
 }  // namespace slim

@@ -113,7 +113,8 @@ int launch_linear_scaled(const void* a, int lda, const void* w0, const void* w1,
 int launch_linear_pair(const void* a, int lda, const void* w_1, const void* bias_1, int n_1, int ldo_1, void* out_1,
                        const void* w_2, const void* bias_2, int n_2, int ldo_2, void* out_2, const float* row_scale,
                        int m, int k_in, hipStream_t st);
-int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st);
+int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, float* rstd, hipStream_t st,
+                    const int* pos = nullptr, int d = 0, float theta = 0.f, float* table = nullptr);
 int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, hipStream_t st);
 int launch_window_query(const void* q_win, int w, int Hq, int Hkv, int d, int dtype, float* qtilde, hipStream_t st);
 int launch_token_score_blocks(const float* token_scores, int N, int H, int block, int unit, float* scores, hipStream_t st);
@@ -127,6 +128,8 @@ int launch_positions(const int* pos_in, int* pos_out, int n, hipStream_t st);
 int launch_select(const float* scores, int nb, int n_keep, unsigned flags, int* kept, hipStream_t st);
 int launch_compact(const void* src, const int* pos_in, const int* kept, int n_keep, int block, int N,
                    int row_elems, int dtype, void* dst, int* pos_out, hipStream_t st);
+int launch_compact_multi(int n_arrays, const void* const* src, void* const* dst, const size_t* row_bytes, const int* pos_in,
+                         int* pos_out, const int* kept, int n_keep, int block, int N, hipStream_t st);
 int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int Hkv, int d, float scale,
                 int dtype, void* out, hipStream_t st);
 
