@@ -70,11 +70,18 @@ def check_layer_local(label, wl, w_cpu, x_in, pos_in, keep, res, np_dtype, rows_
     assert mx <= max(MAX_ABS, 1.5 * fl_max) and mean <= max(MEAN_ABS, 1.5 * fl_mean)
 
 
-def test_small_schedule_every_layer(slim):
+def to_gpu(w, fold):
+    """Layer weights on the GPU; fold: the (unit) RMSNorm gains are folded into the projections, i.e. left out, so
+    the norms run inside the projections as in bench.py."""
+    return {k: v.cuda() for k, v in w.items() if not (fold and k in ("g_attn", "g_ffn"))}
+
+
+@pytest.mark.parametrize("fold", [False, True])
+def test_small_schedule_every_layer(slim, fold):
     wl = inputs.scaled(inputs.WORKLOADS["cfg5"], seq=2048 + 37, n_layers=5, schedule={1: 0.5, 3: 0.25})
     x, pos = inputs.hidden_states(wl).cuda(), inputs.positions(wl).cuda()
     w_cpu = [w for _, w in inputs.model_weights(wl)]
-    w_gpu = [{k: v.cuda() for k, v in w.items()} for w in w_cpu]
+    w_gpu = [to_gpu(w, fold) for w in w_cpu]
     shape = make_shape(slim, wl, x.dtype)
     keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, wl.schedule)
     assert keeps == [0, 17, 0, 5, 0]                       # 33 blocks -> 17 -> 5
@@ -99,7 +106,7 @@ def test_cfg5_full_schedule_layer_local(slim):
     x, pos = inputs.hidden_states(wl).cuda(), inputs.positions(wl).cuda()
     w_gpu, w_cpu = [], {}
     for l, w in inputs.model_weights(wl, workers=16):
-        w_gpu.append({k: v.cuda() for k, v in w.items()})
+        w_gpu.append(to_gpu(w, True))
         if l in check:
             w_cpu[l] = w
     print("weights ready", flush=True)
