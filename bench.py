@@ -99,6 +99,12 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
                                             rstd_kept.data_ptr(), n, F, Hd, F, 1, act.data_ptr(), st)
         assert rc == 0, rc
 
+    def qv_pair():
+        rc = lib.slim_linear_pair(xc.data_ptr(), Hd, wd["wq"].data_ptr(), bq.data_ptr() if bq is not None else nul, Hq * d,
+                                  Hq * d, q.data_ptr(), wd["wv"].data_ptr(), bv.data_ptr() if bv is not None else nul,
+                                  Hkv * d, Hkv * d, v.data_ptr(), rstd_kept.data_ptr(), n, Hd, 1, st)
+        assert rc == 0, rc
+
     def rstd(xx, m, out):
         rc = lib.slim_row_rstd(xx.data_ptr(), m, Hd, wl.rms_eps, 1, out.data_ptr(), st)
         assert rc == 0, rc
@@ -111,8 +117,8 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
 
     bq, bk, bv = wd.get("bq"), wd.get("bk"), wd.get("bv")
     rows = [
-        ("row_rstd_all", "hbm", N * Hd * es + N * 4, lambda: rstd(x, N, rstd_all)),
-        ("rope_table_all", "alu", N * d * 4, lambda: slim.slim_rope_table(pos, N, d, wl.rope_theta)),
+        ("row_rstd_all", "hbm", N * Hd * es + N * 4, lambda: rstd(x, N, rstd_all)),   # in the layer it also writes the
+        ("rope_table_all", "alu", N * d * 4, lambda: slim.slim_rope_table(pos, N, d, wl.rope_theta)),   # cos/sin table
         ("window_q_proj", "mfma", 2 * wl.window * Hd * Hq * d,
          lambda: lin_scaled(x[w0:], wd["wq"], bq, rstd_all[w0:], wl.window, Hq * d, q_win)),
         ("rope_window_q", "latency", 2 * wl.window * Hq * d * es, lambda: slim.slim_rope(q_win, pos[w0:], wl.rope_theta)),
@@ -123,12 +129,11 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
          lambda: lib.slim_score_blocks_from_token_scores(tsc.data_ptr(), N, Hkv, wl.block, wl.unit, scores.data_ptr(), st)),
         ("select_topk", "latency", scores.numel() * 4 + n_keep * 4,
          lambda: slim.slim_select_topk_blocks(scores, n_keep, kept=kept)),
-        ("compact_x", "hbm", 2 * n * Hd * es + n * 8, compact),
+        ("compact_x", "hbm", 2 * n * Hd * es + n * 8, compact),          # one launch in the layer: x, k and rstd
         ("compact_k", "hbm", 2 * n * Hkv * d * es, compact_k),
         ("compact_rstd", "latency", 2 * n * 4, compact_rstd),
-        ("q_proj", "mfma", 2 * n * Hd * Hq * d, lambda: lin_scaled(xc, wd["wq"], bq, rstd_kept, n, Hq * d, q)),
+        ("qv_proj", "mfma", 2 * n * Hd * (Hq + Hkv) * d, qv_pair),
         ("rope_q", "hbm", 2 * n * Hq * d * es, lambda: slim.slim_rope(q, pc, wl.rope_theta)),
-        ("v_proj", "mfma", 2 * n * Hd * Hkv * d, lambda: lin_scaled(xc, wd["wv"], bv, rstd_kept, n, Hkv * d, v)),
         ("prefill_attn", "mfma", 2 * n * n * d * Hq, lambda: slim.slim_prefill_attn(q, k, v, out=o)),
         ("o_proj_residual", "mfma", 2 * n * Hd * Hq * d,
          lambda: slim.slim_linear(o.view(n, Hq * d), wd["wo"], residual=y, out=out_h)),
