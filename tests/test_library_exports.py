@@ -69,6 +69,24 @@ def test_argument_errors_are_reported_before_anything_is_enqueued(lib):
                                                                   one, block_bytes, one, one, ws, null)
     assert swap(0, 0.9, 4096, 4096) == -1 and swap(4, 1.5, 4096, 4096) == -1 and swap(4, float("nan"), 4096, 4096) == -1
     assert swap(4, 0.9, 4100, 4096) == -2 and swap(4, 0.9, 4096, 1024) == -3
+    # key-first pipeline, fused norms, paired projections: checks that need no GPU
+    fl = ctypes.c_float
+    assert lib.slim_rope_table(null, 8, 128, fl(5e5), null, null) == -1                            # no output
+    assert lib.slim_rope_table(null, 8, 127, fl(5e5), one, null) == -1                             # odd head_dim
+    assert lib.slim_window_query(one, 4, 6, 4, 128, 1, one, null) == -1                            # Hq % Hkv
+    rope = lambda head_dim, k_in, dtype: lib.slim_linear_rope(one, k_in, one, null, one, 64, 8, head_dim, k_in, 8 * head_dim,
+                                                              dtype, null, one, null, null, null)
+    assert rope(64, 4096, 1) == -2 and rope(128, 4000, 1) == -2 and rope(128, 4096, 0) == -2       # head_dim, k % 64, fp32
+    assert lib.slim_linear_rope(one, 4096, one, null, one, 64, 8, 128, 4096, 1024, 1, null, one, one, null, null) == -1  # qt without token_scores
+    assert lib.slim_score_blocks_from_token_scores(one, 100, 8, 64, 65, one, null) == -1            # unit > block
+    assert lib.slim_row_rstd(null, 4, 64, fl(1e-5), 1, one, null) == -1
+    assert lib.slim_rmsnorm_linear(one, 4096, one, null, null, 64, 64, 4096, 64, 1, one, null) == -1     # no rstd
+    assert lib.slim_rmsnorm_linear(one, 4096, one, null, one, 64, 64, 4096, 64, 0, one, null) == -2      # fp32
+    assert lib.slim_rmsnorm_swiglu_linear(one, 4096, one, null, one, 64, 64, 4096, 64, 1, one, null) == -1   # no w_up
+    assert lib.slim_fold_gain(one, null, 8, 8, 1, one, null) == -1
+    pair = lambda m, b1, b2: lib.slim_linear_pair(one, 4096, one, b1, 4096, 4096, one, one, b2, 1024, 1024, one, null, m,
+                                                  4096, 1, null)
+    assert pair(512, one, null) == -1 and pair(64, null, null) == -2                               # one bias only; m <= 128
     shape = slim.make_shape(4096, 32, 8, 128, 14336, 64, 8, 64, __import__("torch").bfloat16)
     need = slim.pruned_layer_workspace_bytes(shape, 32768, 154)
     assert need > 32768 * 4096 * 2
