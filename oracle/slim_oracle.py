@@ -271,6 +271,28 @@ def causal_gqa_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: flo
     return out
 
 
+def decode_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float | None = None) -> np.ndarray:
+    """Attention of one new token during decoding (Section 4.1: only the active blocks take part, every response
+    token is retained): q[Hq, d] attends to ALL the keys it is given, k/v[n, Hkv, d] = the prompt tokens of the
+    active blocks followed by the response tokens.  o^h = sum_j softmax_j(scale q^h . k_j^{h//G}) v_j^{h//G}."""
+    Hq, d = q.shape
+    n, Hkv, _ = k.shape
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.empty_like(q)
+    for h in range(Hq):
+        s = (k[:, h // G, :] @ q[h]) * scale
+        p = np.exp(s - s.max())
+        out[h] = (p @ v[:, h // G, :]) / p.sum()
+    return out
+
+
+def active_token_index(active_blocks, block: int, n_prompt: int) -> np.ndarray:
+    """Prompt token rows of a set of active blocks, ascending (the last prompt block can be short)."""
+    return kept_token_index(np.asarray(sorted(active_blocks), dtype=np.int64), block, n_prompt)
+
+
 # --------------------------------------------------------------------------------------------------
 # the pruned prefill layer
 # --------------------------------------------------------------------------------------------------

@@ -604,3 +604,28 @@ def test_schedule_runs_pruning_layers_on_incoming_blocks():
     np.testing.assert_array_equal(p, r2["pos"])
     # the surviving positions are whole original blocks, first and last among them
     assert p[0] == 0 and p[-1] == 63 and all(p[i * 8] % 8 == 0 for i in range(2))
+
+
+# --------------------------------------------------------------------------------------------- decode attention
+def test_decode_attention_is_the_last_row_of_causal_attention_and_brute_force():
+    """A new token sees every key it is given: that is the last row of causal attention over the same sequence
+    (pinned above against scalar loops and torch), a scalar-loop brute force, and it does not depend on key order."""
+    g = np.random.default_rng(21)
+    n, Hq, Hkv, d = 37, 6, 2, 16
+    q, k, v = g.standard_normal((n, Hq, d)), g.standard_normal((n, Hkv, d)), g.standard_normal((n, Hkv, d))
+    full = so.causal_gqa_attention(q, k, v)
+    got = so.decode_attention(q[-1], k, v)
+    np.testing.assert_allclose(got, full[-1], rtol=1e-12, atol=1e-12)
+    G = Hq // Hkv
+    for h in range(Hq):
+        w = [math.exp(sum(q[-1, h, c] * k[j, h // G, c] for c in range(d)) / math.sqrt(d)) for j in range(n)]
+        for c in (0, d - 1):
+            want = sum(w[j] * v[j, h // G, c] for j in range(n)) / sum(w)
+            assert abs(got[h, c] - want) < 1e-12
+    perm = g.permutation(n)
+    np.testing.assert_allclose(so.decode_attention(q[-1], k[perm], v[perm]), got, rtol=1e-12, atol=1e-12)
+    # one key: the output is that key's value; a custom scale of 0 averages the values
+    np.testing.assert_allclose(so.decode_attention(q[-1], k[:1], v[:1]), np.repeat(v[0], G, axis=0), rtol=1e-12)
+    np.testing.assert_allclose(so.decode_attention(q[-1], k, v, scale=0.0), np.repeat(v.mean(axis=0), G, axis=0), rtol=1e-12)
+    # active blocks -> token rows (ragged last block)
+    np.testing.assert_array_equal(so.active_token_index({2, 0, 4}, 8, 37), list(range(0, 8)) + list(range(16, 24)) + list(range(32, 37)))
