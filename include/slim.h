@@ -325,6 +325,30 @@ int slim_kv_swap(const int* candidate, int n_candidates, int n_blocks, double ga
                  size_t block_bytes, int* info, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * Decode-step attention over the active blocks -- Section 4.1: only active blocks take part in attention and
+ * have their KV in GPU memory; every response token is retained.  One new token:
+ *   out[h, :] = sum_j softmax_j(scale * q[h, :] . k_j^{g}) v_j^{g},   g = h / (Hq/Hkv),
+ * j over the prompt tokens of every block that sits in the slot pool (block_of_slot[s] >= 0; the last prompt
+ * block may be short) and over the n_response response tokens.  The pool is read where the KV swap has put the
+ * blocks, through block_of_slot; no gather, no host round trip.
+ *   q, out         [Hq, 128] dtype
+ *   gpu_pool       slot s at byte s*slot_bytes; inside it, at layer_offset, K[block, Hkv, 128] then
+ *                  V[block, Hkv, 128] of the slot's block (dtype)
+ *   block_of_slot  [n_slots] int32 device (as kept by slim_kv_swap)
+ *   k_response, v_response  [n_response, Hkv, 128] dtype (NULL when n_response = 0)
+ *   workspace      >= slim_decode_attn_workspace_bytes(...), 256-byte aligned: per-slot partial results
+ * softmax_scale 0 => 1/sqrt(128).  At least one key must exist (an empty pool without response tokens gives NaN).
+ * Errors: INVALID_ARG (nulls, sizes, Hq % Hkv, slot too small for the payload), UNSUPPORTED (head_dim != 128,
+ * more than 8 query heads per kv head, alignment), WORKSPACE_TOO_SMALL.
+ */
+size_t slim_decode_attn_workspace_bytes(int n_slots, int n_response, int n_q_heads);
+int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, size_t layer_offset,
+                     const int* block_of_slot, int n_slots, int block, int n_prompt_tokens, const void* k_response,
+                     const void* v_response, int n_response, int n_q_heads, int n_kv_heads, int head_dim,
+                     float softmax_scale, int dtype, void* out, void* workspace, size_t workspace_bytes,
+                     void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Measurement probes (no counterpart in the paper): measured ceilings to set beside the nameplate
  * rooflines.  slim_probe_mfma runs a register-only loop of v_mfma_f32_32x32x16_bf16 (n_workgroups
  * workgroups of 8 waves, `iters` rounds of 8 independent MFMAs per wave) and slim_probe_mfma_flops

@@ -23,7 +23,7 @@ FORCE_FIRST, FORCE_LAST = 1, 2
 EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
-    "slim_kv_swap_workspace_bytes", "slim_kv_swap",
+    "slim_kv_swap_workspace_bytes", "slim_kv_swap", "slim_decode_attn_workspace_bytes", "slim_decode_attn",
     "slim_rope_table", "slim_window_query", "slim_linear_rope", "slim_score_blocks_from_token_scores",
     "slim_linear_pair", "slim_row_rstd", "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
@@ -78,6 +78,9 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_kv_swap_workspace_bytes.restype = sz
     lib.slim_kv_swap_workspace_bytes.argtypes = [i, i]
     lib.slim_kv_swap.argtypes = [vp, i, i, C.c_double, vp, vp, vp, i, vp, vp, sz, vp, vp, sz, vp]
+    lib.slim_decode_attn_workspace_bytes.restype = sz
+    lib.slim_decode_attn_workspace_bytes.argtypes = [i, i, i]
+    lib.slim_decode_attn.argtypes = [vp, vp, sz, sz, vp, i, i, i, vp, vp, i, i, i, i, f, i, vp, vp, sz, vp]
     lib.slim_rope_table.argtypes = [vp, i, i, f, vp, vp]
     lib.slim_window_query.argtypes = [vp, i, i, i, i, i, vp, vp]
     lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
@@ -218,6 +221,30 @@ def slim_score_blocks_from_unit_keys(q_win: torch.Tensor, k_rep: torch.Tensor, n
                                                 _dev(workspace, "workspace"), workspace.numel(), _stream()),
            "slim_score_blocks_from_unit_keys")
     return scores
+
+
+def slim_decode_attn(q: torch.Tensor, gpu_pool: torch.Tensor, block_of_slot: torch.Tensor, block: int, n_prompt_tokens: int,
+                     n_kv_heads: int, k_response: torch.Tensor | None = None, v_response: torch.Tensor | None = None,
+                     layer_offset: int = 0, softmax_scale: float = 0.0, out: torch.Tensor | None = None,
+                     workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """q[Hq,d] attends to the prompt tokens of the blocks in the slot pool and to the response tokens.
+    gpu_pool[n_slots, ...]: per slot K[block,Hkv,d] then V[block,Hkv,d] at byte layer_offset."""
+    lib = load_library()
+    Hq, d = q.shape
+    ns = block_of_slot.numel()
+    slot_bytes = gpu_pool[0].numel() * gpu_pool.element_size() if ns else 0
+    n_resp = 0 if k_response is None else k_response.shape[0]
+    if out is None:
+        out = torch.empty_like(q)
+    need = lib.slim_decode_attn_workspace_bytes(ns, n_resp, Hq)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib.slim_decode_attn(_dev(q, "q"), _dev(gpu_pool, "gpu_pool"), slot_bytes, layer_offset,
+                                _dev(block_of_slot, "block_of_slot"), ns, block, n_prompt_tokens, _dev(k_response, "k_response"),
+                                _dev(v_response, "v_response"), n_resp, Hq, n_kv_heads, d, softmax_scale, _dtype_code(q),
+                                _dev(out, "out"), _dev(workspace, "workspace"), workspace.numel(), _stream()),
+           "slim_decode_attn")
+    return out
 
 
 def slim_rope_table(pos: torch.Tensor | None, n: int, head_dim: int, theta: float,

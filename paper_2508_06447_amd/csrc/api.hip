@@ -1,6 +1,7 @@
 // C entry points of libslim: argument checks, workspace carving and the order of kernel launches of
 // the pruned prefill layer.  No kernel lives here.
 #include "slim_common.h"
+#include <math.h>
 #include <string.h>
 
 namespace slim {
@@ -144,6 +145,33 @@ int slim_score_blocks_from_unit_keys(const void* q_win, const float* k_rep, int 
     if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
     return launch_score_from_unit_keys(q_win, k_rep, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit,
                                        dtype, scores, (float*)workspace, (hipStream_t)stream);
+}
+
+size_t slim_decode_attn_workspace_bytes(int n_slots, int n_response, int n_q_heads) {
+    if (n_slots < 0 || n_response < 0 || n_q_heads < 1 || n_slots + n_response < 1) return 0;
+    return align_up(((size_t)n_slots + (size_t)(n_response + 63) / 64) * n_q_heads * 130 * sizeof(float), 256);
+}
+
+int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot,
+                     int n_slots, int block, int n_prompt_tokens, const void* k_response, const void* v_response,
+                     int n_response, int n_q_heads, int n_kv_heads, int head_dim, float softmax_scale, int dtype, void* out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !out || !workspace || n_slots < 0 || n_response < 0 || n_slots + n_response < 1 || n_q_heads < 1 ||
+        n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 || head_dim < 1 || (n_slots > 0 && (!gpu_pool || !block_of_slot ||
+        block < 1 || n_prompt_tokens < 1)) || (n_response > 0 && (!k_response || !v_response)))
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const size_t kv_bytes = (size_t)n_kv_heads * head_dim * elem_size(dtype);
+    if (n_slots > 0 && layer_offset + 2 * (size_t)block * kv_bytes > slot_bytes) return SLIM_INVALID_ARG;
+    if (head_dim != 128 || n_q_heads / n_kv_heads > 8 || slot_bytes % 16 != 0 || layer_offset % 16 != 0 ||
+        (n_slots > 0 && !aligned16(gpu_pool)) || (n_response > 0 && (!aligned16(k_response) || !aligned16(v_response))) ||
+        n_slots + (n_response + 63) / 64 > 65535 * 32)
+        return SLIM_UNSUPPORTED;
+    if (workspace_bytes < slim_decode_attn_workspace_bytes(n_slots, n_response, n_q_heads)) return SLIM_WORKSPACE_TOO_SMALL;
+    if (softmax_scale == 0.f) softmax_scale = 1.0f / sqrtf((float)head_dim);
+    return launch_decode_attn(q, gpu_pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, n_prompt_tokens,
+                              k_response, v_response, n_response, n_q_heads, n_kv_heads, softmax_scale, dtype, out,
+                              (float*)workspace, (hipStream_t)stream);
 }
 
 int slim_rope_table(const int* pos, int n, int head_dim, float theta, float* table, void* stream) {

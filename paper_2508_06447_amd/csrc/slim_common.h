@@ -130,6 +130,9 @@ int launch_compact(const void* src, const int* pos_in, const int* kept, int n_ke
                    int row_elems, int dtype, void* dst, int* pos_out, hipStream_t st);
 int launch_compact_multi(int n_arrays, const void* const* src, void* const* dst, const size_t* row_bytes, const int* pos_in,
                          int* pos_out, const int* kept, int n_keep, int block, int N, hipStream_t st);
+int launch_decode_attn(const void* q, const void* pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot,
+                       int n_slots, int block, int n_prompt, const void* k_resp, const void* v_resp, int n_resp, int Hq,
+                       int Hkv, float scale, int dtype, void* out, float* part, hipStream_t st);
 int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int Hkv, int d, float scale,
                 int dtype, void* out, hipStream_t st);
 

@@ -244,3 +244,106 @@ def test_kv_swap_on_a_second_stream_beside_compute(slim):
     st.check_consistent()
     for o in outs:
         assert torch.equal(o, ref)
+
+
+# --------------------------------------------------------------------------------------- decode-step attention
+def build_pool(k, v, active, n_slots, block, dtype, seed, layers=1, layer=0):
+    """GPU slot pool holding K then V of the active blocks at random slots (NaN everywhere else), and its map."""
+    g = np.random.default_rng(seed)
+    n, Hkv, d = k.shape
+    pool = torch.full((n_slots, layers, 2, block, Hkv, d), float("nan"), dtype=dtype)
+    bos = np.full(n_slots, -1, np.int32)
+    slots = g.permutation(n_slots)[:len(active)]
+    for b, s in zip(sorted(active), slots):
+        rows = min(block, n - b * block)
+        pool[s, layer, 0, :rows] = k[b * block:b * block + rows]
+        pool[s, layer, 1, :rows] = v[b * block:b * block + rows]
+        bos[s] = b
+    return pool, torch.from_numpy(bos)
+
+
+@pytest.mark.parametrize("n_prompt,block,n_slots,n_active,n_resp,Hq,Hkv,dtype", [
+    (1000, 64, 12, 9, 5, 32, 8, torch.bfloat16),         # ragged last prompt block, free slots, a few response tokens
+    (2048, 128, 8, 8, 130, 8, 2, torch.bfloat16),        # two 64-key chunks per slot, three response chunks
+    (333, 16, 21, 21, 0, 28, 4, torch.bfloat16),         # 7 query heads per kv head, no response tokens yet
+    (512, 64, 8, 3, 64, 4, 4, torch.float32),            # one query head per kv head, fp32
+    (64, 64, 0, 0, 77, 16, 2, torch.bfloat16),           # nothing in the pool: response tokens only
+    (4096, 64, 64, 64, 1, 32, 8, torch.bfloat16),
+])
+def test_decode_attention_over_active_slots_matches_oracle(slim, n_prompt, block, n_slots, n_active, n_resp, Hq, Hkv, dtype):
+    print(f"decode attn n={n_prompt} block={block} slots={n_slots} active={n_active} resp={n_resp} Hq={Hq} Hkv={Hkv} {dtype}",
+          flush=True)
+    d = 128
+    g = np.random.default_rng(n_prompt + n_resp)
+    k, v = rand((n_prompt, Hkv, d), dtype, 1), rand((n_prompt, Hkv, d), dtype, 2)
+    kr, vr = rand((max(n_resp, 1), Hkv, d), dtype, 3)[:n_resp], rand((max(n_resp, 1), Hkv, d), dtype, 4)[:n_resp]
+    q = rand((Hq, d), dtype, 5, 2.0)
+    nb = (n_prompt + block - 1) // block
+    active = set(g.choice(nb, n_active, replace=False).tolist()) if n_active else set()
+    if n_active and n_prompt % block:
+        active = set(list(active)[:-1]) | {nb - 1}        # the short last block among them
+    layers, layer = (3, 1) if n_slots == 12 else (1, 0)
+    pool, bos = build_pool(k, v, active, max(n_slots, 1), block, dtype, seed=7, layers=layers, layer=layer)
+    pool, bos = pool[:n_slots], bos[:n_slots]
+    T = so.active_token_index(active, block, n_prompt)
+    k_all = np.concatenate([f64(k)[T], f64(kr)]) if n_resp else f64(k)[T]
+    v_all = np.concatenate([f64(v)[T], f64(vr)]) if n_resp else f64(v)[T]
+    want = so.decode_attention(f64(q), k_all, v_all)
+    off = layer * 2 * block * Hkv * d * pool.element_size()
+    got = slim.slim_decode_attn(q.cuda(), pool.cuda(), bos.cuda(), block, n_prompt, Hkv,
+                                kr.cuda() if n_resp else None, vr.cuda() if n_resp else None, layer_offset=off)
+    tol = 2.0 ** -8 if dtype == torch.bfloat16 else 2e-5
+    np.testing.assert_allclose(f64(got), want, rtol=tol, atol=tol * np.abs(want).max())
+    assert torch.isfinite(got.float()).all()              # nothing outside the active rows was read (it is NaN)
+
+
+def test_a_decode_step_scores_selects_swaps_and_attends(slim):
+    """One decode step of a layer through the C ABI: scores from stored unit keys and the window of recent Query
+    states, top-k candidate set, overlap-aware swap of the K/V payloads, attention of the new token over what is
+    then active -- each stage against the oracle's."""
+    n_prompt, block, unit, Hq, Hkv, d, n_slots, n_keep = 2048 + 40, 64, 8, 32, 8, 128, 12, 10
+    bf = torch.bfloat16
+    nb = (n_prompt + block - 1) // block
+    k, v = rand((n_prompt, Hkv, d), bf, 11), rand((n_prompt, Hkv, d), bf, 12)
+    words = 2 * block * Hkv * d // 2                      # K then V rows of a block as int32 words
+    payload = torch.zeros(nb, 2, block, Hkv, d, dtype=bf)
+    for b in range(nb):
+        rows = min(block, n_prompt - b * block)
+        payload[b, 0, :rows], payload[b, 1, :rows] = k[b * block:b * block + rows], v[b * block:b * block + rows]
+    payload_words = payload.view(torch.int32).reshape(nb, words)
+    active0 = {0, 3, 4, 9, 10, 17, 20, 25, 30, nb - 1}
+    st = SwapState(nb, n_slots, words, active0, seed=13)
+    st.data = payload_words                               # the payloads are the real K/V rows
+    st.host_pool.copy_(payload_words)
+    gpu = torch.zeros(n_slots, words, dtype=torch.int32)
+    sob = st.slot_of_block.cpu().numpy()
+    for b in active0:
+        gpu[sob[b]] = payload_words[b]
+    st.gpu_pool = gpu.cuda()
+    st.in_memory.fill_(1)
+    k_rep = slim.slim_unit_keys(k.cuda(), block, unit)
+    want_rep = so.all_unit_keys(f64(k), block, unit)
+    kr, vr = rand((6, Hkv, d), bf, 14), rand((6, Hkv, d), bf, 15)
+    n_swaps = 0
+    for step, gamma in enumerate((0.9, 0.9, 0.3)):
+        q_win = rand((4, Hq, d), bf, 20 + step, 1.5)      # Query states of the most recent tokens
+        q_new = q_win[-1]
+        scores = slim.slim_score_blocks_from_unit_keys(q_win.cuda(), k_rep, n_prompt, Hkv, block, unit)
+        sc_ref = so.block_scores_from_unit_keys(f64(q_win), want_rep)
+        assert np.abs(f64(scores) - sc_ref).max() < 2e-5 * max(1.0, np.abs(sc_ref).max())
+        cand = slim.slim_select_topk_blocks(scores, n_keep)
+        cand_ref = so.select_blocks(sc_ref, n_keep)
+        np.testing.assert_array_equal(cand.cpu().numpy(), cand_ref)
+        active_prev, memory = st.sets()
+        want = so.kv_swap_step(active_prev, cand_ref.tolist(), memory, gamma)
+        info = slim.slim_kv_swap(cand, gamma, st.slot_of_block, st.block_of_slot, st.in_memory, st.gpu_pool, st.host_pool)
+        out = slim.slim_decode_attn(q_new.cuda(), st.gpu_pool.view(torch.bfloat16).view(n_slots, 2, block, Hkv, d),
+                                    st.block_of_slot, block, n_prompt, Hkv, kr.cuda(), vr.cuda())
+        torch.cuda.synchronize()
+        assert bool(info.cpu()[2]) == want["swapped"] and st.sets()[0] == want["active"]
+        st.check_consistent()
+        T = so.active_token_index(want["active"], block, n_prompt)
+        ref = so.decode_attention(f64(q_new), np.concatenate([f64(k)[T], f64(kr)]), np.concatenate([f64(v)[T], f64(vr)]))
+        np.testing.assert_allclose(f64(out), ref, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(ref).max())
+        n_swaps += want["swapped"]
+    assert n_swaps >= 1
