@@ -320,6 +320,19 @@ def bench_decode(args, slim, dev):
     b = N * E * 2
     rec_k["score_from_keys"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1)}
 
+    # attention of one new token over 128 active blocks (8192 prompt tokens) and 16 response tokens
+    n_act = 128
+    pool = torch.randn(n_act, 2, block, Hkv, d, device=dev).to(bf)
+    bos_a = torch.randperm(nb, device=dev)[:n_act].to(torch.int32)
+    kr, vr = torch.randn(16, Hkv, d, device=dev).to(bf), torch.randn(16, Hkv, d, device=dev).to(bf)
+    q1 = torch.randn(Hq, d, device=dev).to(bf)
+    o1 = torch.empty_like(q1)
+    wsa = torch.empty(slim.load_library().slim_decode_attn_workspace_bytes(n_act, 16, Hq), dtype=torch.uint8, device=dev)
+    _, t = time_gpu(lambda: slim.slim_decode_attn(q1, pool, bos_a, block, N, Hkv, kr, vr, out=o1, workspace=wsa), reps)
+    b = pool.numel() * 2 + (kr.numel() + vr.numel()) * 2
+    rec_k["decode_attn"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1), "frac_hbm": round(b / t / 1e6 / PEAK_HBM_GBS, 4),
+                            "note": "two launches (per-slot partials, merge); 128 active blocks of 64 tokens + 16 response tokens"}
+
     n_slots, n_swap = 128, 32
     swaps = {}
     h = torch.randn(9856, wl.hidden, device=dev).to(bf)

@@ -15,17 +15,22 @@ constexpr int DCH = 64;          // keys per chunk
 constexpr int DGMAX = 8;         // query heads per kv head
 constexpr int DPART = DD + 2;    // floats of a partial: values, max (base-2 domain), sum
 
-template <typename T>
+// A wave owns 16 keys of a 64-key chunk and keeps its own running (max, sum, values): no workgroup barrier until
+// the four waves' states are merged at the end.  Scores: 4 lanes per key, 32 dims each (16-byte loads), reduced
+// with two shuffles.  Values: a lane owns dims 2 l, 2 l + 1 of all 16 keys (4-byte loads, a row is read by the
+// whole wave), the probabilities go through a wave-private LDS strip.
+template <typename T, int G>
 __global__ void __launch_bounds__(256) decode_attn_partial_kernel(
     const T* __restrict__ q, const unsigned char* __restrict__ pool, size_t slot_bytes, size_t layer_offset,
     const int* __restrict__ block_of_slot, int n_slots, int block, int n_prompt, const T* __restrict__ k_resp,
     const T* __restrict__ v_resp, int n_resp, int Hq, int Hkv, float scale_log2e, float* __restrict__ part) {
     constexpr int V = Elem<T>::kVec;
-    __shared__ float qs[DGMAX][DD];                      // query heads of this kv head, times scale * log2(e)
-    __shared__ float ss[DCH][DGMAX];                     // logits, then probabilities, of the chunk
-    __shared__ float m_run[DGMAX], l_run[DGMAX], alpha[DGMAX];
-    __shared__ float red[4][DGMAX][DD];
-    const int item = blockIdx.x, g = blockIdx.y, G = Hq / Hkv, tid = threadIdx.x;
+    __shared__ float qs[G][DD];                      // query heads of this kv head, times scale * log2(e)
+    __shared__ float ps[4][16][G];                   // per wave: probabilities of its 16 keys
+    __shared__ float ws_m[4][G], ws_l[4][G];     // per wave: running max and sum
+    __shared__ float red[4][G][DD];                  // per wave: weighted values
+    const int item = blockIdx.x, g = blockIdx.y, tid = threadIdx.x;   // G = Hq / Hkv query heads per kv head
+    const int wave = tid >> 6, lane = tid & 63;
     const size_t row_stride = (size_t)Hkv * DD;
     const int nb = (n_prompt + block - 1) / block;
 
@@ -43,136 +48,197 @@ __global__ void __launch_bounds__(256) decode_attn_partial_kernel(
         vp = v_resp + (size_t)j * DCH * row_stride;
     }
     for (int i = tid; i < G * DD; i += 256) qs[i / DD][i % DD] = Elem<T>::ld(q + (size_t)(g * G + i / DD) * DD + i % DD) * scale_log2e;
-    if (tid < DGMAX) { m_run[tid] = -INFINITY; l_run[tid] = 0.f; }
-    float oacc[DGMAX][2];
-#pragma unroll
-    for (int h = 0; h < DGMAX; ++h) oacc[h][0] = oacc[h][1] = 0.f;
     __syncthreads();
 
-    const int key = tid >> 2, prt = tid & 3;             // scores: 4 threads per key, 32 dims each
-    const int dp = tid & 63, kq = tid >> 6;              // values: thread owns dims 2 dp, 2 dp + 1 of 16 keys
-    for (int c0 = 0; c0 < rows; c0 += DCH) {
-        const int cr = min(DCH, rows - c0);
-        // ---- logits of the chunk
-        float dot[DGMAX];
+    float m_run[G], l_run[G], oacc[G][2];
 #pragma unroll
-        for (int h = 0; h < DGMAX; ++h) dot[h] = 0.f;
-        if (key < cr) {
-            const T* kr = kp + (size_t)(c0 + key) * row_stride + (size_t)g * DD + prt * 32;
+    for (int h = 0; h < G; ++h) { m_run[h] = -INFINITY; l_run[h] = 0.f; oacc[h][0] = oacc[h][1] = 0.f; }
+    const int kl = lane >> 2, prt = lane & 3;            // scores: key kl of the wave's 16, dims 32 prt ..
+    for (int c0 = wave * 16; c0 < rows; c0 += DCH) {     // this wave's keys c0 .. c0 + 15 (wave-uniform bounds)
+        const int cr = min(16, rows - c0);
+        float dot[G];
 #pragma unroll
-            for (int c = 0; c < 32 / V; ++c) {
-                float f[V];
-                Elem<T>::unpack(*reinterpret_cast<const uint4*>(kr + c * V), f);
+        for (int h = 0; h < G; ++h) dot[h] = 0.f;
+        // rows past the end are clamped to the last one (their logit is masked below), so no load is conditional;
+        // all loads of the chunk are requested before any arithmetic
+        uint4 raw[32 / V];
+        {
+            const T* kr = kp + (size_t)(c0 + min(kl, cr - 1)) * row_stride + (size_t)g * DD + prt * 32;
 #pragma unroll
-                for (int h = 0; h < DGMAX; ++h)
-                    if (h < G) {
-#pragma unroll
-                        for (int i = 0; i < V; ++i) dot[h] += f[i] * qs[h][prt * 32 + c * V + i];
-                    }
-            }
+            for (int c = 0; c < 32 / V; ++c) raw[c] = *reinterpret_cast<const uint4*>(kr + c * V);
         }
+        float v0[16], v1[16];
 #pragma unroll
-        for (int h = 0; h < DGMAX; ++h) {
-            dot[h] += __shfl_xor(dot[h], 1, 64);
-            dot[h] += __shfl_xor(dot[h], 2, 64);
-        }
-        if (prt == 0) {
-#pragma unroll
-            for (int h = 0; h < DGMAX; ++h) ss[key][h] = key < cr ? dot[h] : -INFINITY;
-        }
-        __syncthreads();
-        // ---- running maximum and rescale factor per head (wave 0: lane = key)
-        if (tid < 64) {
-            for (int h = 0; h < G; ++h) {
-                const float cm = wave_max(ss[tid][h]);
-                if (tid == 0) {
-                    const float mn = fmaxf(m_run[h], cm);                // finite: the chunk has at least one key
-                    alpha[h] = __builtin_amdgcn_exp2f(m_run[h] - mn);    // exp2(-inf) = 0 for the first chunk
-                    m_run[h] = mn;
+        for (int kk = 0; kk < 16; ++kk) {
+            {   // clamped like the keys: a row past the end gets probability 0
+                const T* vr = vp + (size_t)(c0 + min(kk, cr - 1)) * row_stride + (size_t)g * DD + 2 * lane;
+                if constexpr (sizeof(T) == 2) {          // one 4-byte load for the bf16 pair
+                    const uint32_t pr = *reinterpret_cast<const uint32_t*>(vr);
+                    v0[kk] = lo_bf16(pr);
+                    v1[kk] = hi_bf16(pr);
+                } else {
+                    v0[kk] = Elem<T>::ld(vr);
+                    v1[kk] = Elem<T>::ld(vr + 1);
                 }
             }
         }
-        __syncthreads();
-        for (int i = tid; i < DCH * G; i += 256) {
-            const int kk = i / G, h = i - kk * G;
-            ss[kk][h] = __builtin_amdgcn_exp2f(ss[kk][h] - m_run[h]);
-        }
-        __syncthreads();
-        if (tid < 64) {
+#pragma unroll
+        for (int c = 0; c < 32 / V; ++c) {
+            float f[V];
+            Elem<T>::unpack(raw[c], f);
+#pragma unroll
             for (int h = 0; h < G; ++h) {
-                const float sum = wave_sum(ss[tid][h]);
-                if (tid == 0) l_run[h] = l_run[h] * alpha[h] + sum;
+#pragma unroll
+                for (int i = 0; i < V; ++i) dot[h] += f[i] * qs[h][prt * 32 + c * V + i];
             }
         }
-        // ---- values: this thread's 16 keys of the chunk
 #pragma unroll
-        for (int h = 0; h < DGMAX; ++h) { oacc[h][0] *= alpha[h < G ? h : 0]; oacc[h][1] *= alpha[h < G ? h : 0]; }
-        for (int kk = kq * 16; kk < min(kq * 16 + 16, cr); ++kk) {
-            const T* vr = vp + (size_t)(c0 + kk) * row_stride + (size_t)g * DD + 2 * dp;
-            float v0, v1;
-            if constexpr (sizeof(T) == 2) {              // one 4-byte load for the bf16 pair
-                const uint32_t pr = *reinterpret_cast<const uint32_t*>(vr);
-                v0 = lo_bf16(pr);
-                v1 = hi_bf16(pr);
-            } else {
-                v0 = Elem<T>::ld(vr);
-                v1 = Elem<T>::ld(vr + 1);
-            }
+        for (int h = 0; h < G; ++h) {
+            float sc = dot[h] + __shfl_xor(dot[h], 1, 64);
+            sc += __shfl_xor(sc, 2, 64);
+            sc = kl < cr ? sc : -INFINITY;
+            float cm = sc;                               // maximum over the 16 keys (lanes 4 apart)
 #pragma unroll
-            for (int h = 0; h < DGMAX; ++h)
-                if (h < G) { oacc[h][0] += ss[kk][h] * v0; oacc[h][1] += ss[kk][h] * v1; }
+            for (int o = 4; o < 64; o <<= 1) cm = fmaxf(cm, __shfl_xor(cm, o, 64));
+            const float mn = fmaxf(m_run[h], cm);        // finite: the wave has at least one key here
+            const float al = __builtin_amdgcn_exp2f(m_run[h] - mn);
+            const float p = __builtin_amdgcn_exp2f(sc - mn);
+            float sum = p;
+#pragma unroll
+            for (int o = 4; o < 64; o <<= 1) sum += __shfl_xor(sum, o, 64);
+            m_run[h] = mn;
+            l_run[h] = l_run[h] * al + sum;
+            oacc[h][0] *= al;
+            oacc[h][1] *= al;
+            if (prt == 0) ps[wave][kl][h] = p;
         }
-        __syncthreads();                                 // ss and alpha are rewritten by the next chunk
+        __builtin_amdgcn_wave_barrier();                 // the strip is written and read by this wave only
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk)
+#pragma unroll
+            for (int h = 0; h < G; ++h)
+                {
+                    const float p = ps[wave][kk][h];
+                    oacc[h][0] += p * v0[kk];
+                    oacc[h][1] += p * v1[kk];
+                }
+        __builtin_amdgcn_wave_barrier();
     }
-    // ---- the four key quarters are summed, and the partial is written
+    // ---- the four waves' states are merged, and the partial is written
 #pragma unroll
-    for (int h = 0; h < DGMAX; ++h)
-        if (h < G) { red[kq][h][2 * dp] = oacc[h][0]; red[kq][h][2 * dp + 1] = oacc[h][1]; }
+    for (int h = 0; h < G; ++h)
+        {
+            red[wave][h][2 * lane] = oacc[h][0];
+            red[wave][h][2 * lane + 1] = oacc[h][1];
+            if (lane == 0) { ws_m[wave][h] = m_run[h]; ws_l[wave][h] = l_run[h]; }
+        }
     __syncthreads();
     for (int i = tid; i < G * DD; i += 256) {
         const int h = i / DD, dd = i - h * DD;
+        const float M = fmaxf(fmaxf(ws_m[0][h], ws_m[1][h]), fmaxf(ws_m[2][h], ws_m[3][h]));
+        float o = 0.f, l = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float sc = ws_l[w][h] > 0.f ? __builtin_amdgcn_exp2f(ws_m[w][h] - M) : 0.f;
+            o += sc * red[w][h][dd];
+            l += sc * ws_l[w][h];
+        }
         float* dst = part + ((size_t)item * Hq + g * G + h) * DPART;
-        dst[dd] = red[0][h][dd] + red[1][h][dd] + red[2][h][dd] + red[3][h][dd];
-        if (dd == 0) { dst[DD] = m_run[h]; dst[DD + 1] = l_run[h]; }
+        dst[dd] = o;
+        if (dd == 0) { dst[DD] = M; dst[DD + 1] = l; }
     }
 }
 
-// One workgroup per query head: out = sum_i 2^(m_i - M) o_i / sum_i 2^(m_i - M) l_i over the partials with keys.
+// One workgroup per query head: out = sum_i 2^(m_i - M) o_i / sum_i 2^(m_i - M) l_i over the partials.  1024
+// threads = 8 groups of 128 dims; the weights of up to 1024 partials at a time are formed in parallel and kept in
+// LDS, then group j takes the partials j, j + 8, ... so that the loads of a thread do not depend on each other.
+// A partial without keys has sum 0 and zero values, and gets weight 0.
+constexpr int DMT = 1024;
 template <typename T>
-__global__ void __launch_bounds__(DD) decode_attn_merge_kernel(const float* __restrict__ part, int n_items, int Hq,
-                                                               T* __restrict__ out) {
-    const int h = blockIdx.x, dd = threadIdx.x;
-    float M = -INFINITY;
-    for (int i = 0; i < n_items; ++i) M = fmaxf(M, part[((size_t)i * Hq + h) * DPART + DD]);
-    float acc = 0.f, l = 0.f;
-    for (int i = 0; i < n_items; ++i) {
-        const float* p = part + ((size_t)i * Hq + h) * DPART;
-        if (p[DD + 1] > 0.f) {
-            const float w = __builtin_amdgcn_exp2f(p[DD] - M);
-            acc += w * p[dd];
-            l += w * p[DD + 1];
+__global__ void __launch_bounds__(DMT) decode_attn_merge_kernel(const float* __restrict__ part, int n_items, int Hq,
+                                                                T* __restrict__ out) {
+    __shared__ float wts[DMT];
+    __shared__ float wred[DMT / 64];
+    __shared__ float accs[DMT / DD][DD];
+    const int h = blockIdx.x, tid = threadIdx.x, grp = tid >> 7, dd = tid & (DD - 1);
+    auto item = [&](int i) { return part + ((size_t)i * Hq + h) * DPART; };
+    float m = -INFINITY;
+    for (int i = tid; i < n_items; i += DMT) m = fmaxf(m, item(i)[DD]);
+    m = wave_max(m);
+    if ((tid & 63) == 0) wred[tid >> 6] = m;
+    __syncthreads();
+    float M = wred[0];
+#pragma unroll
+    for (int i = 1; i < DMT / 64; ++i) M = fmaxf(M, wred[i]);
+    __syncthreads();
+    float lsum = 0.f, acc = 0.f;
+    for (int base = 0; base < n_items; base += DMT) {
+        const int i = base + tid;
+        float w = 0.f;
+        if (i < n_items) {
+            const float* p = item(i);
+            if (p[DD + 1] > 0.f) {
+                w = __builtin_amdgcn_exp2f(p[DD] - M);
+                lsum += w * p[DD + 1];
+            }
         }
+        wts[tid] = w;
+        __syncthreads();
+        const int cnt = min(DMT, n_items - base);
+#pragma unroll 4
+        for (int j = grp; j < cnt; j += DMT / DD) acc += wts[j] * item(base + j)[dd];
+        __syncthreads();
     }
-    Elem<T>::st(out + (size_t)h * DD + dd, acc / l);
+    lsum = wave_sum(lsum);
+    if ((tid & 63) == 0) wred[tid >> 6] = lsum;
+    accs[grp][dd] = acc;
+    __syncthreads();
+    if (grp == 0) {
+        float L = 0.f, a = 0.f;
+#pragma unroll
+        for (int i = 0; i < DMT / 64; ++i) L += wred[i];
+#pragma unroll
+        for (int i = 0; i < DMT / DD; ++i) a += accs[i][dd];
+        Elem<T>::st(out + (size_t)h * DD + dd, a / L);
+    }
+}
+
+template <typename T, int G>
+static void launch_decode_partial(const void* q, const void* pool, size_t slot_bytes, size_t layer_offset,
+                                  const int* block_of_slot, int n_slots, int block, int n_prompt, const void* k_resp,
+                                  const void* v_resp, int n_resp, int Hq, int Hkv, float sl, float* part, int n_items,
+                                  hipStream_t st) {
+    hipLaunchKernelGGL((decode_attn_partial_kernel<T, G>), dim3(n_items, Hkv), dim3(256), 0, st, (const T*)q,
+                       (const unsigned char*)pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, n_prompt,
+                       (const T*)k_resp, (const T*)v_resp, n_resp, Hq, Hkv, sl, part);
+}
+
+template <typename T>
+static int launch_decode_attn_t(const void* q, const void* pool, size_t slot_bytes, size_t layer_offset,
+                                const int* block_of_slot, int n_slots, int block, int n_prompt, const void* k_resp,
+                                const void* v_resp, int n_resp, int Hq, int Hkv, float sl, void* out, float* part,
+                                hipStream_t st) {
+    const int n_items = n_slots + (n_resp + DCH - 1) / DCH;
+#define SLIM_DEC(GG) case GG: launch_decode_partial<T, GG>(q, pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, \
+                                                            n_prompt, k_resp, v_resp, n_resp, Hq, Hkv, sl, part, n_items, st); break
+    switch (Hq / Hkv) {
+        SLIM_DEC(1); SLIM_DEC(2); SLIM_DEC(3); SLIM_DEC(4); SLIM_DEC(5); SLIM_DEC(6); SLIM_DEC(7); SLIM_DEC(8);
+        default: return SLIM_UNSUPPORTED;
+    }
+#undef SLIM_DEC
+    hipLaunchKernelGGL(decode_attn_merge_kernel<T>, dim3(Hq), dim3(DMT), 0, st, part, n_items, Hq, (T*)out);
+    return check_launch();
 }
 
 int launch_decode_attn(const void* q, const void* pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot,
                        int n_slots, int block, int n_prompt, const void* k_resp, const void* v_resp, int n_resp, int Hq,
                        int Hkv, float scale, int dtype, void* out, float* part, hipStream_t st) {
-    const int n_items = n_slots + (n_resp + DCH - 1) / DCH;
     const float sl = scale * 1.4426950408889634f;
-    if (dtype == SLIM_BF16) {
-        hipLaunchKernelGGL(decode_attn_partial_kernel<bf16_t>, dim3(n_items, Hkv), dim3(256), 0, st, (const bf16_t*)q,
-                           (const unsigned char*)pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, n_prompt,
-                           (const bf16_t*)k_resp, (const bf16_t*)v_resp, n_resp, Hq, Hkv, sl, part);
-        hipLaunchKernelGGL(decode_attn_merge_kernel<bf16_t>, dim3(Hq), dim3(DD), 0, st, part, n_items, Hq, (bf16_t*)out);
-    } else {
-        hipLaunchKernelGGL(decode_attn_partial_kernel<float>, dim3(n_items, Hkv), dim3(256), 0, st, (const float*)q,
-                           (const unsigned char*)pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, n_prompt,
-                           (const float*)k_resp, (const float*)v_resp, n_resp, Hq, Hkv, sl, part);
-        hipLaunchKernelGGL(decode_attn_merge_kernel<float>, dim3(Hq), dim3(DD), 0, st, part, n_items, Hq, (float*)out);
-    }
-    return check_launch();
+    if (dtype == SLIM_BF16)
+        return launch_decode_attn_t<bf16_t>(q, pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, n_prompt, k_resp,
+                                            v_resp, n_resp, Hq, Hkv, sl, out, part, st);
+    return launch_decode_attn_t<float>(q, pool, slot_bytes, layer_offset, block_of_slot, n_slots, block, n_prompt, k_resp,
+                                       v_resp, n_resp, Hq, Hkv, sl, out, part, st);
 }
 
 }  // namespace slim
