@@ -163,7 +163,7 @@ int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, siz
     if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
     const size_t kv_bytes = (size_t)n_kv_heads * head_dim * elem_size(dtype);
     if (n_slots > 0 && layer_offset + 2 * (size_t)block * kv_bytes > slot_bytes) return SLIM_INVALID_ARG;
-    if (head_dim != 128 || n_q_heads / n_kv_heads > 8 || slot_bytes % 16 != 0 || layer_offset % 16 != 0 ||
+    if (head_dim != 128 || n_q_heads / n_kv_heads > 8 || slot_bytes % 16 != 0 || layer_offset % 16 != 0 || !aligned16(q) ||
         (n_slots > 0 && !aligned16(gpu_pool)) || (n_response > 0 && (!aligned16(k_response) || !aligned16(v_response))) ||
         n_slots + (n_response + 63) / 64 > 65535 * 32)
         return SLIM_UNSUPPORTED;

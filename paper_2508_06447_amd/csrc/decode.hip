@@ -25,7 +25,9 @@ __global__ void __launch_bounds__(256) decode_attn_partial_kernel(
     const int* __restrict__ block_of_slot, int n_slots, int block, int n_prompt, const T* __restrict__ k_resp,
     const T* __restrict__ v_resp, int n_resp, int Hq, int Hkv, float scale_log2e, float* __restrict__ part) {
     constexpr int V = Elem<T>::kVec;
-    __shared__ float qs[G][DD];                      // query heads of this kv head, times scale * log2(e)
+    // Query heads of this kv head: floats times scale * log2(e) (fp32 path), or the bf16 pairs as they are, for
+    // v_dot2_f32_bf16 (half the registers; the scale is then applied to the dot products).
+    __shared__ float qs[G][sizeof(T) == 2 ? DD / 2 : DD];
     __shared__ float ps[4][16][G];                   // per wave: probabilities of its 16 keys
     __shared__ float ws_m[4][G], ws_l[4][G];     // per wave: running max and sum
     __shared__ float red[4][G][DD];                  // per wave: weighted values
@@ -47,7 +49,12 @@ __global__ void __launch_bounds__(256) decode_attn_partial_kernel(
         kp = k_resp + (size_t)j * DCH * row_stride;
         vp = v_resp + (size_t)j * DCH * row_stride;
     }
-    for (int i = tid; i < G * DD; i += 256) qs[i / DD][i % DD] = Elem<T>::ld(q + (size_t)(g * G + i / DD) * DD + i % DD) * scale_log2e;
+    if constexpr (sizeof(T) == 2) {
+        for (int i = tid; i < G * DD / 2; i += 256)
+            qs[i / (DD / 2)][i % (DD / 2)] = __builtin_bit_cast(float, reinterpret_cast<const uint32_t*>(q + (size_t)g * G * DD)[i]);
+    } else {
+        for (int i = tid; i < G * DD; i += 256) qs[i / DD][i % DD] = Elem<T>::ld(q + (size_t)(g * G + i / DD) * DD + i % DD) * scale_log2e;
+    }
     __syncthreads();
 
     float m_run[G], l_run[G], oacc[G][2];
@@ -82,14 +89,30 @@ __global__ void __launch_bounds__(256) decode_attn_partial_kernel(
                 }
             }
         }
+        if constexpr (sizeof(T) == 2) {
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-        for (int c = 0; c < 32 / V; ++c) {
-            float f[V];
-            Elem<T>::unpack(raw[c], f);
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t kw[4] = {raw[c].x, raw[c].y, raw[c].z, raw[c].w};
 #pragma unroll
-            for (int h = 0; h < G; ++h) {
+                for (int h = 0; h < G; ++h)
 #pragma unroll
-                for (int i = 0; i < V; ++i) dot[h] += f[i] * qs[h][prt * 32 + c * V + i];
+                    for (int i = 0; i < 4; ++i)
+                        dot[h] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, kw[i]),
+                                                                 __builtin_bit_cast(bf16x2, qs[h][prt * 16 + c * 4 + i]), dot[h], false);
+            }
+#pragma unroll
+            for (int h = 0; h < G; ++h) dot[h] *= scale_log2e;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 32 / V; ++c) {
+                float f[V];
+                Elem<T>::unpack(raw[c], f);
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+#pragma unroll
+                    for (int i = 0; i < V; ++i) dot[h] += f[i] * qs[h][prt * 32 + c * V + i];
+                }
             }
         }
 #pragma unroll
