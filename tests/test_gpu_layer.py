@@ -65,11 +65,15 @@ def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", p
     res = run_gpu(slim, wl, x, w, pos, n_keep, scoring=scoring, placement=placement, fold=fold)
     s, ow = oracle_shape(wl, scoring, placement), oracle_weights(w, np_dtype)
     xs = x.to(torch.float32).numpy().astype(np_dtype)
-    sc_ref, _ = so.layer_scores(s, ow, xs, pos.numpy())
-    sc_gpu = f64(res["scores"])
-    sc_err = float(np.abs(sc_gpu - sc_ref).max())
     kept_gpu = res["kept"].cpu().numpy()
-    want, band, ndiff = assert_selection_matches(kept_gpu, sc_ref.astype(np.float64), n_keep)
+    if n_keep < wl.n_blocks:
+        sc_ref, _ = so.layer_scores(s, ow, xs, pos.numpy())
+        sc_gpu = f64(res["scores"])
+        sc_err = float(np.abs(sc_gpu - sc_ref).max())
+        want, band, ndiff = assert_selection_matches(kept_gpu, sc_ref.astype(np.float64), n_keep)
+    else:                                                # a Preserve layer: nothing is scored, every block continues
+        np.testing.assert_array_equal(kept_gpu, np.arange(wl.n_blocks))
+        sc_ref, sc_err, band, ndiff = np.zeros(1), 0.0, 0, 0
     n_out = slim.kept_tokens(wl.seq, wl.block, n_keep)
     assert res["x"].shape[0] == n_out
     # positions and (teacher-forced on the GPU's set) the layer output
@@ -83,7 +87,7 @@ def check_layer(slim, wl, np_dtype, rows_count=None, label="", scoring="unit", p
           f"{ndiff} differ; z max-abs {mx:.3e} mean-abs {mean:.3e} (bf16-rounding oracle: {fl_max:.3e} / "
           f"{fl_mean:.3e}); |z| max {np.abs(z_ref).max():.2f}", flush=True)
     out = dict(sc_err=sc_err, sc_scale=float(np.abs(sc_ref).max()), mx=mx, mean=mean, fl_max=fl_max, fl_mean=fl_mean)
-    if score_floor:
+    if score_floor and n_keep < wl.n_blocks:
         # what rounding the oracle's own h, K and window Q to bf16 does to its scores (one draw of that noise)
         sc_rounded, _ = so.layer_scores(s, ow, xs, pos.numpy(), rounding="bf16")
         out["sc_floor"] = float(np.abs(sc_rounded - sc_ref).max())
@@ -190,6 +194,27 @@ def test_layer_with_non_unit_gains(slim, fold):
     r = check_layer(slim, wl, np.float64, label=f"llama-shaped seq 1000, random gains, fold {fold}", fold=fold, gains=gains,
                     score_floor=True)
     assert r["sc_err"] < max(2e-3, 3.0 * r["sc_floor"])
+    assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
+
+
+@pytest.mark.parametrize("fold", [False, True])
+@pytest.mark.parametrize("seq,block,window,keep", [
+    (5, 64, 64, 1.0),        # fewer tokens than a block and than the window: one short block, nothing to drop
+    (64, 64, 64, 1.0),       # exactly one block
+    (70, 64, 64, 0.5),       # two blocks, both forced (first, short last): n_keep = 2 = nb, a Preserve layer
+    (130, 64, 64, 0.1),      # three blocks, only the two forced ones kept: no slot left for the scored block
+    (200, 16, 300, 0.3),     # window longer than the sequence: every token is in the window
+    (257, 1, 4, 0.25),       # blocks of one token (unit 1): token-level pruning
+    (300, 32, 1, 0.5),       # window of one token
+])
+def test_degenerate_small_sequences(slim, seq, block, window, keep, fold):
+    """Edge shapes of the layer on a narrow bf16 model (2 kv heads of 128), against the oracle in full."""
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=seq, block=block, unit=min(8, block), window=window, keep_ratio=keep,
+                       hidden=256, n_q_heads=4, n_kv_heads=2, ffn=512, planted=max(1, seq // 50))
+    r = check_layer(slim, wl, np.float64, label=f"narrow model seq {seq} block {block} window {window} keep {keep} fold {fold}",
+                    fold=fold, score_floor=wl.n_keep < wl.n_blocks)
+    if wl.n_keep < wl.n_blocks:
+        assert r["sc_err"] < max(2e-3, 3.0 * r["sc_floor"])
     assert r["mx"] <= max(MAX_ABS, 1.5 * r["fl_max"]) and r["mean"] <= max(MEAN_ABS, 1.5 * r["fl_mean"])
 
 
