@@ -347,3 +347,54 @@ def test_a_decode_step_scores_selects_swaps_and_attends(slim):
         np.testing.assert_allclose(f64(out), ref, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(ref).max())
         n_swaps += want["swapped"]
     assert n_swaps >= 1
+
+
+def test_decode_step_at_the_full_size_of_the_32k_workload(slim):
+    """The decode-time kernels in the configuration bench.py --workload decode times: 32768 prompt tokens = 512
+    blocks of 64, 8 kv heads of 128, 128 GPU slots, K+V payloads of 256 KiB per block, 32 of the 128 active blocks
+    replaced by one swap.  Scores and candidate set in full, swap sets and every payload byte, attention output."""
+    n_prompt, block, unit, Hq, Hkv, d, n_slots = 32768, 64, 8, 32, 8, 128, 128
+    bf = torch.bfloat16
+    nb = n_prompt // block
+    g = np.random.default_rng(41)
+    k, v = rand((n_prompt, Hkv, d), bf, 31), rand((n_prompt, Hkv, d), bf, 32)
+    words = 2 * block * Hkv * d // 2
+    payload_words = torch.stack([k.view(nb, block, Hkv, d), v.view(nb, block, Hkv, d)], dim=1).contiguous() \
+        .view(torch.int32).reshape(nb, words)
+    # scores from stored unit keys with a window of 4 recent tokens; candidates = top 128 blocks (first and last forced)
+    q_win = rand((4, Hq, d), bf, 33, 1.5)
+    k_rep = slim.slim_unit_keys(k.cuda(), block, unit)
+    scores = slim.slim_score_blocks_from_unit_keys(q_win.cuda(), k_rep, n_prompt, Hkv, block, unit)
+    sc_ref = so.block_scores_from_unit_keys(f64(q_win), so.all_unit_keys(f64(k), block, unit))
+    assert np.abs(f64(scores) - sc_ref).max() < 2e-5 * max(1.0, np.abs(sc_ref).max())
+    cand = slim.slim_select_topk_blocks(scores, n_slots)
+    cand_ref = so.select_blocks(sc_ref, n_slots)
+    np.testing.assert_array_equal(cand.cpu().numpy(), cand_ref)
+    # previous active set: 96 of the candidates + 32 other blocks -> overlap 0.75 < 0.9: a swap of 32 blocks
+    others = [b for b in range(nb) if b not in set(cand_ref.tolist())]
+    active0 = set(g.permutation(cand_ref)[:96].tolist()) | set(g.permutation(others)[:32].tolist())
+    st = SwapState(nb, n_slots, words, active0, seed=43)
+    st.data = payload_words
+    in_pool = st.in_memory.cpu().bool()
+    st.host_pool.fill_(-1)
+    st.host_pool[in_pool] = payload_words[in_pool]        # what is on the GPU has not been written to the CPU pool
+    gpu = torch.zeros(n_slots, words, dtype=torch.int32)
+    sob = st.slot_of_block.cpu().numpy()
+    for b in active0:
+        gpu[sob[b]] = payload_words[b]
+    st.gpu_pool = gpu.cuda()
+    active_prev, memory = st.sets()
+    want = so.kv_swap_step(active_prev, cand_ref.tolist(), memory, 0.9)
+    assert want["swapped"] and len(want["load"]) == 32 and len(want["offload"]) == 32
+    info = slim.slim_kv_swap(cand, 0.9, st.slot_of_block, st.block_of_slot, st.in_memory, st.gpu_pool, st.host_pool)
+    kr, vr = rand((16, Hkv, d), bf, 34), rand((16, Hkv, d), bf, 35)
+    out = slim.slim_decode_attn(q_win[-1].cuda(), st.gpu_pool.view(torch.bfloat16).view(n_slots, 2, block, Hkv, d),
+                                st.block_of_slot, block, n_prompt, Hkv, kr.cuda(), vr.cuda())
+    torch.cuda.synchronize()
+    inf = info.cpu().numpy()
+    assert inf[2] == 1 and inf[3] == 32 and inf[4] == 32 and inf[5] == 0
+    assert st.sets() == (want["active"], want["memory"])
+    st.check_consistent()
+    T = so.active_token_index(want["active"], block, n_prompt)
+    ref = so.decode_attention(f64(q_win[-1]), np.concatenate([f64(k)[T], f64(kr)]), np.concatenate([f64(v)[T], f64(vr)]))
+    np.testing.assert_allclose(f64(out), ref, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(ref).max())
