@@ -426,6 +426,26 @@ def pruned_layer(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
     return dict(z=z, pos=posk, kept_blocks=kept, scores=scores)
 
 
+def decode_layer(s: LayerShape, w: LayerWeights, x_new: np.ndarray, pos_new: int, k_ctx: np.ndarray, v_ctx: np.ndarray,
+                 rounding=None):
+    """One layer for one newly decoded token (Fig. 2, decoding phase): QKV generation for the token, attention of its
+    Query over the context it is given -- the Key/Value states of the prompt tokens of the active blocks and of the
+    earlier response tokens, k_ctx/v_ctx[n, Hkv, d] -- plus its own Key/Value, output projection and FFN.
+    x_new[hidden], pos_new = the token's position.  Returns (z[hidden], k_new[Hkv, d], v_new[Hkv, d])."""
+    x = x_new[None, :]
+    pos = np.asarray([pos_new])
+    h = _rnd(rmsnorm(x, w.g_attn, s.rms_eps), rounding)
+    q = project_heads(h, w.wq, s.n_q_heads, s.head_dim, pos, s.rope_theta, True, rounding, w.bq)
+    k = project_heads(h, w.wk, s.n_kv_heads, s.head_dim, pos, s.rope_theta, True, rounding, w.bk)
+    v = project_heads(h, w.wv, s.n_kv_heads, s.head_dim, pos, s.rope_theta, False, rounding, w.bv)
+    o = _rnd(decode_attention(q[0], np.concatenate([k_ctx, k]), np.concatenate([v_ctx, v])), rounding)
+    y = _rnd(x + linear(o.reshape(1, -1), w.wo), rounding)
+    r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
+    act = _rnd(silu(linear(r, w.w_gate)) * linear(r, w.w_up), rounding)
+    z = _rnd(y + linear(act, w.w_down), rounding)
+    return z[0], k[0], v[0]
+
+
 def prefill_model(s: LayerShape, weights_of_layer, n_layers: int, x: np.ndarray, pos: np.ndarray,
                   schedule: dict, rounding=None):
     """Preserve/Slim schedule (Section 4.1): layers run in order; layer l in `schedule` prunes its

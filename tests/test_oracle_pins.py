@@ -629,3 +629,28 @@ def test_decode_attention_is_the_last_row_of_causal_attention_and_brute_force():
     np.testing.assert_allclose(so.decode_attention(q[-1], k, v, scale=0.0), np.repeat(v.mean(axis=0), G, axis=0), rtol=1e-12)
     # active blocks -> token rows (ragged last block)
     np.testing.assert_array_equal(so.active_token_index({2, 0, 4}, 8, 37), list(range(0, 8)) + list(range(16, 24)) + list(range(32, 37)))
+
+
+def test_decode_layer_is_the_last_row_of_the_prefill_layer():
+    """Decoding token n-1 with the Key/Value states of tokens 0..n-2 as its context is the unpruned prefill layer's
+    last row (that layer is pinned above against a torch composition); the token's own K/V are those rows too."""
+    g = np.random.default_rng(31)
+    n, hidden, Hq, Hkv, d, ffn = 21, 48, 4, 2, 16, 80
+    s = so.LayerShape(hidden, Hq, Hkv, d, ffn, 8, 4, 4, 10000.0, 1e-5)
+    mk = lambda *shape: g.standard_normal(shape) * 0.2
+    w = so.LayerWeights(1.0 + 0.1 * g.standard_normal(hidden), mk(Hq * d, hidden), mk(Hkv * d, hidden), mk(Hkv * d, hidden),
+                        mk(hidden, Hq * d), 1.0 + 0.1 * g.standard_normal(hidden), mk(ffn, hidden), mk(ffn, hidden),
+                        mk(hidden, ffn), mk(Hq * d), mk(Hkv * d), mk(Hkv * d))
+    x = g.standard_normal((n, hidden))
+    pos = np.sort(g.choice(500, n, replace=False))
+    full = so.pruned_layer(s, w, x, pos, n_keep=99)                       # Preserve layer: every row
+    h = so.rmsnorm(x, w.g_attn, s.rms_eps)
+    k_all = so.project_heads(h, w.wk, Hkv, d, pos, s.rope_theta, True, None, w.bk)
+    v_all = so.project_heads(h, w.wv, Hkv, d, pos, s.rope_theta, False, None, w.bv)
+    z, k_new, v_new = so.decode_layer(s, w, x[-1], int(pos[-1]), k_all[:-1], v_all[:-1])
+    np.testing.assert_allclose(z, full["z"][-1], rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(k_new, k_all[-1], rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(v_new, v_all[-1], rtol=1e-12, atol=1e-12)
+    # with no context the token attends to itself only: attention output = its own value
+    z0, _, v0 = so.decode_layer(s, w, x[0], int(pos[0]), k_all[:0], v_all[:0])
+    np.testing.assert_allclose(z0, full["z"][0], rtol=1e-10, atol=1e-10)
