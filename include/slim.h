@@ -349,6 +349,32 @@ int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, siz
                      void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * One layer for one newly decoded token -- the decoding phase of Fig. 2 with the KV cache of Section 4.3: "QKV
+ * Generation" for the token, attention of its Query over the active blocks in the slot pool, the earlier response
+ * tokens and itself, output projection, FFN.
+ *   slim_gemv: the single-token projection, out[n] = s * (w[n, :] . x) + bias[n] + residual[n] (NULL = absent), or
+ *              with w_up: silu(s * w . x) * (s * w_up . x);  s = *scale (device float, e.g. the token's 1/rms from
+ *              slim_row_rstd for a folded gain) or 1 when scale is NULL.  Every weight is read once.  out may alias
+ *              residual.  k_in % 8 == 0 (bf16) / % 4 (fp32), k_in <= 16384, 16-byte aligned w, w_up, x.
+ *   slim_decode_layer:
+ *     x_new [hidden], position = the token's position (for RoPE), x_out [hidden] (may not alias x_new)
+ *     gpu_pool / slot_bytes / layer_offset / block_of_slot / n_slots / n_prompt_tokens: as slim_decode_attn
+ *     k_response, v_response [>= n_response + 1, Hkv, 128]: rows 0..n_response-1 are the earlier response tokens;
+ *                    the call WRITES the token's own Key (post-RoPE) and Value states into row n_response
+ *     q_out [Hq, 128] or NULL: the token's Query states (post-RoPE), e.g. for the scoring window of the next steps
+ *     workspace >= slim_decode_layer_workspace_bytes(...), 256-byte aligned
+ *   Weights as slim_pruned_layer (NULL gains = folded).  head_dim 128, at most 8 query heads per kv head, hidden,
+ *   ffn, Hq*128 <= 16384.  13 launches, no host synchronisation.  Errors as the stage calls.
+ */
+int slim_gemv(const void* w, const void* w_up, const void* x, const float* scale, const void* bias,
+              const void* residual, int n_out, int k_in, int dtype, void* out, void* stream);
+size_t slim_decode_layer_workspace_bytes(const slim_layer_shape* s, int n_slots, int n_response);
+int slim_decode_layer(const slim_layer_shape* s, const slim_layer_weights* w, const void* x_new, int position,
+                      const void* gpu_pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot,
+                      int n_slots, int n_prompt_tokens, void* k_response, void* v_response, int n_response,
+                      void* x_out, void* q_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Measurement probes (no counterpart in the paper): measured ceilings to set beside the nameplate
  * rooflines.  slim_probe_mfma runs a register-only loop of v_mfma_f32_32x32x16_bf16 (n_workgroups
  * workgroups of 8 waves, `iters` rounds of 8 independent MFMAs per wave) and slim_probe_mfma_flops

@@ -23,7 +23,8 @@ FORCE_FIRST, FORCE_LAST = 1, 2
 EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
-    "slim_kv_swap_workspace_bytes", "slim_kv_swap", "slim_decode_attn_workspace_bytes", "slim_decode_attn",
+    "slim_kv_swap_workspace_bytes", "slim_kv_swap", "slim_decode_attn_workspace_bytes", "slim_decode_attn", "slim_gemv", "slim_decode_layer_workspace_bytes",
+    "slim_decode_layer",
     "slim_rope_table", "slim_window_query", "slim_linear_rope", "slim_score_blocks_from_token_scores",
     "slim_linear_pair", "slim_row_rstd", "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
@@ -81,6 +82,11 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_decode_attn_workspace_bytes.restype = sz
     lib.slim_decode_attn_workspace_bytes.argtypes = [i, i, i]
     lib.slim_decode_attn.argtypes = [vp, vp, sz, sz, vp, i, i, i, vp, vp, i, i, i, i, f, i, vp, vp, sz, vp]
+    lib.slim_gemv.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp, vp]
+    lib.slim_decode_layer_workspace_bytes.restype = sz
+    lib.slim_decode_layer_workspace_bytes.argtypes = [C.POINTER(LayerShape), i, i]
+    lib.slim_decode_layer.argtypes = [C.POINTER(LayerShape), C.POINTER(LayerWeights), vp, i, vp, sz, sz, vp, i, i, vp, vp, i, vp, vp,
+                                      vp, sz, vp]
     lib.slim_rope_table.argtypes = [vp, i, i, f, vp, vp]
     lib.slim_window_query.argtypes = [vp, i, i, i, i, i, vp, vp]
     lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
@@ -245,6 +251,40 @@ def slim_decode_attn(q: torch.Tensor, gpu_pool: torch.Tensor, block_of_slot: tor
                                 _dev(out, "out"), _dev(workspace, "workspace"), workspace.numel(), _stream()),
            "slim_decode_attn")
     return out
+
+
+def slim_gemv(w: torch.Tensor, x: torch.Tensor, w_up: torch.Tensor | None = None, scale: torch.Tensor | None = None,
+              bias: torch.Tensor | None = None, residual: torch.Tensor | None = None, out: torch.Tensor | None = None):
+    """Single-token projection w . x (scaled, + bias, + residual) or silu(w . x) * (w_up . x); x[k_in] -> [n_out]."""
+    lib = load_library()
+    n_out, k_in = w.shape
+    if out is None:
+        out = torch.empty(n_out, dtype=x.dtype, device=x.device)
+    _check(lib.slim_gemv(_dev(w, "w"), _dev(w_up, "w_up"), _dev(x, "x"), _dev(scale, "scale"), _dev(bias, "bias"),
+                         _dev(residual, "residual"), n_out, k_in, _dtype_code(x), _dev(out, "out"), _stream()), "slim_gemv")
+    return out
+
+
+def slim_decode_layer(shape: LayerShape, weights: dict, x_new: torch.Tensor, position: int, gpu_pool: torch.Tensor,
+                      block_of_slot: torch.Tensor, n_prompt_tokens: int, k_response: torch.Tensor, v_response: torch.Tensor,
+                      n_response: int, layer_offset: int = 0, workspace: torch.Tensor | None = None):
+    """One layer for one decoded token.  k_response/v_response[>= n_response+1, Hkv, d]: row n_response is written.
+    Returns (x_out[hidden], q[Hq, d])."""
+    lib = load_library()
+    ns = block_of_slot.numel()
+    slot_bytes = gpu_pool[0].numel() * gpu_pool.element_size() if ns else 0
+    x_out = torch.empty_like(x_new)
+    q = torch.empty(shape.n_q_heads, shape.head_dim, dtype=x_new.dtype, device=x_new.device)
+    need = lib.slim_decode_layer_workspace_bytes(C.byref(shape), ns, n_response)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x_new.device)
+    wstruct = make_weights(weights)
+    _check(lib.slim_decode_layer(C.byref(shape), C.byref(wstruct), _dev(x_new, "x_new"), position, _dev(gpu_pool, "gpu_pool"),
+                                 slot_bytes, layer_offset, _dev(block_of_slot, "block_of_slot"), ns, n_prompt_tokens,
+                                 _dev(k_response, "k_response"), _dev(v_response, "v_response"), n_response,
+                                 _dev(x_out, "x_out"), _dev(q, "q"), _dev(workspace, "workspace"), workspace.numel(),
+                                 _stream()), "slim_decode_layer")
+    return x_out, q
 
 
 def slim_rope_table(pos: torch.Tensor | None, n: int, head_dim: int, theta: float,

@@ -174,6 +174,92 @@ int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, siz
                               (float*)workspace, (hipStream_t)stream);
 }
 
+int slim_gemv(const void* w, const void* w_up, const void* x, const float* scale, const void* bias, const void* residual,
+              int n_out, int k_in, int dtype, void* out, void* stream) {
+    if (!w || !x || !out || n_out < 1 || k_in < 1) return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    if (k_in % (dtype == SLIM_BF16 ? 8 : 4) != 0 || k_in > 16384 || !aligned16(w) || !aligned16(x) || (w_up && !aligned16(w_up)))
+        return SLIM_UNSUPPORTED;
+    return launch_gemv(w, w_up, x, scale, bias, residual, n_out, k_in, dtype, out, (hipStream_t)stream);
+}
+
+// Workspace of slim_decode_layer: h | rstd | q | o | act | attention partials
+struct DecodePlan { size_t h, rstd, q, o, act, attn, total; };
+static DecodePlan plan_decode(const slim_layer_shape* s, int n_slots, int n_response) {
+    DecodePlan p{};
+    const size_t es = elem_size(s->dtype), qd = (size_t)s->n_q_heads * s->head_dim;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+    p.h = take((size_t)s->hidden * es);
+    p.rstd = take(2 * sizeof(float));
+    p.q = take(qd * es);
+    p.o = take(qd * es);
+    p.act = take((size_t)s->ffn * es);
+    p.attn = take(slim_decode_attn_workspace_bytes(n_slots, n_response + 1, s->n_q_heads));
+    p.total = off;
+    return p;
+}
+
+size_t slim_decode_layer_workspace_bytes(const slim_layer_shape* s, int n_slots, int n_response) {
+    if (check_shape(s) != SLIM_OK || n_slots < 0 || n_response < 0) return 0;
+    return plan_decode(s, n_slots, n_response).total;
+}
+
+int slim_decode_layer(const slim_layer_shape* s, const slim_layer_weights* w, const void* x_new, int position,
+                      const void* gpu_pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot, int n_slots,
+                      int n_prompt_tokens, void* k_response, void* v_response, int n_response, void* x_out, void* q_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_shape(s);
+    if (rc) return rc;
+    if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down || !x_new || !x_out ||
+        !k_response || !v_response || !workspace || position < 0 || n_slots < 0 || n_response < 0 ||
+        (n_slots > 0 && (!gpu_pool || !block_of_slot || n_prompt_tokens < 1)))
+        return SLIM_INVALID_ARG;
+    const int dt = s->dtype, Hd = s->hidden, Hq = s->n_q_heads, Hkv = s->n_kv_heads, d = s->head_dim;
+    const int qd = Hq * d, kvd = Hkv * d, vec = dt == SLIM_BF16 ? 8 : 4;
+    const size_t es = elem_size(dt);
+    if (d != 128 || Hq / Hkv > 8 || Hd % vec != 0 || s->ffn % vec != 0 || Hd > 16384 || s->ffn > 16384 || qd > 16384 ||
+        !aligned16(x_new) || !aligned16(x_out) || !aligned16(k_response) || !aligned16(v_response) ||
+        ((uintptr_t)workspace & 255u) || slot_bytes % 16 != 0 || layer_offset % 16 != 0 || (n_slots > 0 && !aligned16(gpu_pool)) ||
+        (q_out && !aligned16(q_out)))
+        return SLIM_UNSUPPORTED;
+    if (n_slots > 0 && layer_offset + 2 * (size_t)s->block * kvd * es > slot_bytes) return SLIM_INVALID_ARG;
+    const DecodePlan p = plan_decode(s, n_slots, n_response);
+    if (workspace_bytes < p.total) return SLIM_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    unsigned char* ws = (unsigned char*)workspace;
+    void *h = ws + p.h, *q = q_out ? q_out : (void*)(ws + p.q), *o = ws + p.o, *act = ws + p.act;
+    float* rstd = (float*)(ws + p.rstd);
+    void* k_new = (unsigned char*)k_response + (size_t)n_response * kvd * es;
+    void* v_new = (unsigned char*)v_response + (size_t)n_response * kvd * es;
+#define SLIM_TRY(call) do { rc = (call); if (rc) return rc; } while (0)
+    // QKV generation for the token: norm (a row statistic with folded gain, else a normalised copy), three projections,
+    // RoPE at the token's position; its Key/Value states become row n_response of the response buffers.
+    const void* a = x_new;
+    const float* sc = nullptr;
+    if (w->g_attn) { SLIM_TRY(launch_rmsnorm(x_new, w->g_attn, 1, Hd, s->rms_eps, dt, h, st)); a = h; }
+    else { SLIM_TRY(launch_row_rstd(x_new, 1, Hd, s->rms_eps, dt, rstd, st)); sc = rstd; }
+    SLIM_TRY(launch_gemv(w->wq, nullptr, a, sc, w->bq, nullptr, qd, Hd, dt, q, st));
+    SLIM_TRY(launch_gemv(w->wk, nullptr, a, sc, w->bk, nullptr, kvd, Hd, dt, k_new, st));
+    SLIM_TRY(launch_gemv(w->wv, nullptr, a, sc, w->bv, nullptr, kvd, Hd, dt, v_new, st));
+    SLIM_TRY(launch_rope(q, nullptr, position, 1, Hq, d, s->rope_theta, dt, st));
+    SLIM_TRY(launch_rope(k_new, nullptr, position, 1, Hkv, d, s->rope_theta, dt, st));
+    // attention over the active blocks, the earlier response tokens and the token itself
+    SLIM_TRY(launch_decode_attn(q, gpu_pool, slot_bytes, layer_offset, block_of_slot, n_slots, s->block, n_prompt_tokens,
+                                k_response, v_response, n_response + 1, Hq, Hkv, 1.0f / sqrtf((float)d), dt, o,
+                                (float*)(ws + p.attn), st));
+    // output projection + residual, FFN + residual
+    SLIM_TRY(launch_gemv(w->wo, nullptr, o, nullptr, nullptr, x_new, Hd, qd, dt, x_out, st));
+    a = x_out;
+    sc = nullptr;
+    if (w->g_ffn) { SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, 1, Hd, s->rms_eps, dt, h, st)); a = h; }
+    else { SLIM_TRY(launch_row_rstd(x_out, 1, Hd, s->rms_eps, dt, rstd + 1, st)); sc = rstd + 1; }
+    SLIM_TRY(launch_gemv(w->w_gate, w->w_up, a, sc, nullptr, nullptr, s->ffn, Hd, dt, act, st));
+    SLIM_TRY(launch_gemv(w->w_down, nullptr, act, nullptr, nullptr, x_out, Hd, s->ffn, dt, x_out, st));
+#undef SLIM_TRY
+    return SLIM_OK;
+}
+
 int slim_rope_table(const int* pos, int n, int head_dim, float theta, float* table, void* stream) {
     if (!table || n < 1 || head_dim < 2 || head_dim % 2 != 0 || head_dim > 256 || !(theta > 0.f)) return SLIM_INVALID_ARG;
     return launch_rope_table(pos, 0, n, head_dim, theta, table, (hipStream_t)stream);

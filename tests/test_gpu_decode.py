@@ -5,7 +5,8 @@ import pytest
 import torch
 
 from oracle import slim_oracle as so
-from tests.helpers import f64
+from paper_2508_06447_amd import inputs
+from tests.helpers import errs, f64
 
 pytestmark = pytest.mark.gpu
 
@@ -398,3 +399,84 @@ def test_decode_step_at_the_full_size_of_the_32k_workload(slim):
     T = so.active_token_index(want["active"], block, n_prompt)
     ref = so.decode_attention(f64(q_win[-1]), np.concatenate([f64(k)[T], f64(kr)]), np.concatenate([f64(v)[T], f64(vr)]))
     np.testing.assert_allclose(f64(out), ref, rtol=2.0 ** -8, atol=2.0 ** -8 * np.abs(ref).max())
+
+
+# ------------------------------------------------------------------------------ single-token projections and layer
+@pytest.mark.parametrize("n,k,dtype", [(4096, 4096, torch.bfloat16), (1024, 4096, torch.bfloat16), (70, 256, torch.bfloat16),
+                                       (13, 64, torch.float32), (3584, 18944, torch.bfloat16)])
+def test_gemv_all_epilogues(slim, n, k, dtype):
+    print(f"gemv n={n} k={k} {dtype}", flush=True)
+    if k > 16384:
+        with pytest.raises(slim.SlimError):
+            slim.slim_gemv(rand((8, k), dtype, 1).cuda(), rand((k,), dtype, 2).cuda())
+        return
+    w, w2, x = rand((n, k), dtype, 1, 0.05), rand((n, k), dtype, 2, 0.05), rand((k,), dtype, 3)
+    b, r = rand((n,), dtype, 4), rand((n,), dtype, 5)
+    sc = torch.tensor([0.37], dtype=torch.float32)
+    W, W2, X = f64(w), f64(w2), f64(x)
+    rel = 2.0 ** -8 if dtype == torch.bfloat16 else 1e-5
+    def close(got, want):
+        np.testing.assert_allclose(f64(got), want, rtol=rel, atol=rel * max(1e-6, np.abs(want).max()))
+    close(slim.slim_gemv(w.cuda(), x.cuda()), W @ X)
+    close(slim.slim_gemv(w.cuda(), x.cuda(), scale=sc.cuda(), bias=b.cuda()), 0.37 * (W @ X) + f64(b))
+    rd = r.cuda().clone()
+    slim.slim_gemv(w.cuda(), x.cuda(), residual=rd, out=rd)                 # in place
+    close(rd, W @ X + f64(r))
+    close(slim.slim_gemv(w.cuda(), x.cuda(), w_up=w2.cuda(), scale=sc.cuda()), so.silu(0.37 * (W @ X)) * (0.37 * (W2 @ X)))
+
+
+def decode_case(slim, wl, n_slots, n_active, n_resp, fold, seed, np_dtype=np.float64):
+    """One decoded token through slim_decode_layer against the oracle's decode_layer on the gathered context."""
+    bf = torch.bfloat16
+    Hq, Hkv, d, block, n_prompt = wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block, wl.seq
+    g = np.random.default_rng(seed)
+    w = inputs.layer_weights(wl)
+    k, v = rand((n_prompt, Hkv, d), bf, seed + 1), rand((n_prompt, Hkv, d), bf, seed + 2)
+    nb = (n_prompt + block - 1) // block
+    active = set(g.choice(nb - 1, n_active - 1, replace=False).tolist()) | {nb - 1}
+    pool, bos = build_pool(k, v, active, n_slots, block, bf, seed=seed + 3)
+    kr = torch.zeros(n_resp + 1, Hkv, d, dtype=bf)
+    vr = torch.zeros(n_resp + 1, Hkv, d, dtype=bf)
+    kr[:n_resp], vr[:n_resp] = rand((n_resp, Hkv, d), bf, seed + 4), rand((n_resp, Hkv, d), bf, seed + 5)
+    x_new = rand((wl.hidden,), bf, seed + 6, 1.5)
+    position = n_prompt + n_resp
+    shape = slim.make_shape(wl.hidden, Hq, Hkv, d, wl.ffn, block, wl.unit, wl.window, bf, wl.rope_theta, wl.rms_eps)
+    wd = {kk: vv.cuda() for kk, vv in w.items() if not (fold and kk in ("g_attn", "g_ffn"))}
+    krd, vrd = kr.cuda(), vr.cuda()
+    z, q = slim.slim_decode_layer(shape, wd, x_new.cuda(), position, pool.cuda(), bos.cuda(), n_prompt, krd, vrd, n_resp)
+    torch.cuda.synchronize()
+    s = so.LayerShape(wl.hidden, Hq, Hkv, d, wl.ffn, block, wl.unit, wl.window, wl.rope_theta, wl.rms_eps)
+    ow = so.LayerWeights(**{kk: vv.to(torch.float32).numpy().astype(np_dtype) for kk, vv in w.items()})
+    T = so.active_token_index(active, block, n_prompt)
+    k_ctx = np.concatenate([f64(k)[T], f64(kr[:n_resp])]).astype(np_dtype)
+    v_ctx = np.concatenate([f64(v)[T], f64(vr[:n_resp])]).astype(np_dtype)
+    xs = f64(x_new).astype(np_dtype)
+    z_ref, k_ref, v_ref = so.decode_layer(s, ow, xs, position, k_ctx, v_ctx)
+    z_b, _, _ = so.decode_layer(s, ow, xs, position, k_ctx, v_ctx, rounding="bf16")
+    fl_max, fl_mean = np.abs(z_b - z_ref).max(), np.abs(z_b - z_ref).mean()
+    rel = 2.0 ** -8
+    np.testing.assert_allclose(f64(krd[n_resp]), k_ref, rtol=rel, atol=rel * np.abs(k_ref).max())
+    np.testing.assert_allclose(f64(vrd[n_resp]), v_ref, rtol=rel, atol=rel * np.abs(v_ref).max())
+    assert torch.equal(krd[:n_resp].cpu(), kr[:n_resp]) and torch.equal(vrd[:n_resp].cpu(), vr[:n_resp])
+    h = so.rmsnorm(xs[None], ow.g_attn, s.rms_eps)
+    q_ref = so.project_heads(h, ow.wq, Hq, d, np.asarray([position]), s.rope_theta, True, None, ow.bq)[0]
+    np.testing.assert_allclose(f64(q), q_ref, rtol=rel, atol=rel * np.abs(q_ref).max())
+    mx, mean = errs(z, z_ref.astype(np.float64))
+    print(f"decode layer {wl.family} hidden {wl.hidden} slots {n_slots} active {n_active} resp {n_resp} fold {fold}: z max-abs "
+          f"{mx:.3e} mean-abs {mean:.3e} (bf16-rounding oracle {fl_max:.3e} / {fl_mean:.3e}); |z| max {np.abs(z_ref).max():.2f}",
+          flush=True)
+    assert mx <= max(2e-2, 1.5 * fl_max) and mean <= max(2e-3, 1.5 * fl_mean)
+
+
+@pytest.mark.parametrize("fold", [False, True])
+def test_decode_layer_reduced_shapes(slim, fold):
+    llama = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=1000, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024)
+    decode_case(slim, llama, n_slots=12, n_active=9, n_resp=5, fold=fold, seed=50)
+    decode_case(slim, llama, n_slots=4, n_active=4, n_resp=0, fold=fold, seed=60)          # first decoded token
+    qwen = inputs.scaled(inputs.WORKLOADS["cfg6"], seq=777, hidden=448, n_q_heads=14, n_kv_heads=2, ffn=1184, x_kind="normal")
+    decode_case(slim, qwen, n_slots=10, n_active=7, n_resp=70, fold=fold, seed=70)         # biases, 7 heads per kv head
+
+
+def test_decode_layer_full_llama_shape(slim):
+    """LLaMA-3.1-8B-shaped layer, 32768-token prompt, 128 active blocks (8192 tokens), 16 response tokens, folded gains."""
+    decode_case(slim, inputs.WORKLOADS["cfg3"], n_slots=128, n_active=128, n_resp=16, fold=True, seed=80, np_dtype=np.float32)
