@@ -333,6 +333,36 @@ def bench_decode(args, slim, dev):
     rec_k["decode_attn"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1), "frac_hbm": round(b / t / 1e6 / PEAK_HBM_GBS, 4),
                             "note": "two launches (per-slot partials, merge); 128 active blocks of 64 tokens + 16 response tokens"}
 
+    # one layer for one decoded token at the LLaMA-3.1-8B shape (weights read once: HBM-bound), and its projections
+    wts = {kk: vv.to(dev) for kk, vv in inputs.layer_weights(wl).items() if kk not in ("g_attn", "g_ffn")}
+    shape = slim.make_shape(wl.hidden, Hq, Hkv, d, wl.ffn, block, unit, wl.window, bf, wl.rope_theta, wl.rms_eps)
+    x1 = torch.randn(wl.hidden, device=dev).to(bf)
+    krb, vrb = torch.zeros(17, Hkv, d, device=dev, dtype=bf), torch.zeros(17, Hkv, d, device=dev, dtype=bf)
+    krb[:16], vrb[:16] = kr, vr
+    wsl = torch.empty(slim.load_library().slim_decode_layer_workspace_bytes(__import__("ctypes").byref(shape), n_act, 16),
+                      dtype=torch.uint8, device=dev)
+    _, t = time_gpu(lambda: slim.slim_decode_layer(shape, wts, x1, N + 16, pool, bos_a, N, krb, vrb, 16, workspace=wsl), reps)
+    wbytes = sum(vv.numel() * 2 for vv in wts.values())
+    b = wbytes + pool.numel() * 2
+    rec_k["decode_layer"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1), "frac_hbm": round(b / t / 1e6 / PEAK_HBM_GBS, 4),
+                             "note": "6 launches; weights of the layer + K/V of 128 active blocks, each read once"}
+    # the same call captured once into a HIP graph and replayed (the library only enqueues kernels, so a caller can)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        slim.slim_decode_layer(shape, wts, x1, N + 16, pool, bos_a, N, krb, vrb, 16, workspace=wsl)
+    _, t = time_gpu(graph.replay, reps)
+    rec_k["decode_layer_graph_replay"] = {"ms": round(t, 4), "bytes": b, "gbs": round(b / t / 1e6, 1),
+                                          "frac_hbm": round(b / t / 1e6 / PEAK_HBM_GBS, 4)}
+    act1 = torch.randn(wl.ffn, device=dev).to(bf)
+    for name, fn, nbytes in (
+            ("gemv_q_4096x4096", lambda: slim.slim_gemv(wts["wq"], x1), wts["wq"].numel() * 2),
+            ("gemv_swiglu_2x14336x4096", lambda: slim.slim_gemv(wts["w_gate"], x1, w_up=wts["w_up"]), 2 * wts["w_gate"].numel() * 2),
+            ("gemv_down_4096x14336", lambda: slim.slim_gemv(wts["w_down"], act1), wts["w_down"].numel() * 2)):
+        _, t = time_gpu(fn, reps)
+        rec_k[name] = {"ms": round(t, 4), "bytes": nbytes, "gbs": round(nbytes / t / 1e6, 1), "frac_hbm": round(nbytes / t / 1e6 / PEAK_HBM_GBS, 4)}
+    del wts
+
     n_slots, n_swap = 128, 32
     swaps = {}
     h = torch.randn(9856, wl.hidden, device=dev).to(bf)

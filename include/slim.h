@@ -364,7 +364,8 @@ int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, siz
  *     q_out [Hq, 128] or NULL: the token's Query states (post-RoPE), e.g. for the scoring window of the next steps
  *     workspace >= slim_decode_layer_workspace_bytes(...), 256-byte aligned
  *   Weights as slim_pruned_layer (NULL gains = folded).  head_dim 128, at most 8 query heads per kv head, hidden,
- *   ffn, Hq*128 <= 16384.  13 launches, no host synchronisation.  Errors as the stage calls.
+ *   ffn, Hq*128 <= 16384.  6 launches with folded gains (8 otherwise), no host synchronisation.  Errors as the stage
+ *   calls.
  */
 int slim_gemv(const void* w, const void* w_up, const void* x, const float* scale, const void* bias,
               const void* residual, int n_out, int k_in, int dtype, void* out, void* stream);

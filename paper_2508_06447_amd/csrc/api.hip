@@ -180,7 +180,7 @@ int slim_gemv(const void* w, const void* w_up, const void* x, const float* scale
     if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
     if (k_in % (dtype == SLIM_BF16 ? 8 : 4) != 0 || k_in > 16384 || !aligned16(w) || !aligned16(x) || (w_up && !aligned16(w_up)))
         return SLIM_UNSUPPORTED;
-    return launch_gemv(w, w_up, x, scale, bias, residual, n_out, k_in, dtype, out, (hipStream_t)stream);
+    return launch_gemv(w, w_up, x, scale, -1.f, bias, residual, n_out, k_in, dtype, out, (hipStream_t)stream);
 }
 
 // Workspace of slim_decode_layer: h | rstd | q | o | act | attention partials
@@ -229,33 +229,28 @@ int slim_decode_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     hipStream_t st = (hipStream_t)stream;
     unsigned char* ws = (unsigned char*)workspace;
     void *h = ws + p.h, *q = q_out ? q_out : (void*)(ws + p.q), *o = ws + p.o, *act = ws + p.act;
-    float* rstd = (float*)(ws + p.rstd);
     void* k_new = (unsigned char*)k_response + (size_t)n_response * kvd * es;
     void* v_new = (unsigned char*)v_response + (size_t)n_response * kvd * es;
 #define SLIM_TRY(call) do { rc = (call); if (rc) return rc; } while (0)
-    // QKV generation for the token: norm (a row statistic with folded gain, else a normalised copy), three projections,
-    // RoPE at the token's position; its Key/Value states become row n_response of the response buffers.
+    // QKV generation for the token in one launch: the norm (with a folded gain: a statistic that the kernel forms from
+    // its own copy of the token; else a normalised copy first), the three projections with their biases, RoPE at the
+    // token's position.  Its Key/Value states become row n_response of the response buffers.
     const void* a = x_new;
-    const float* sc = nullptr;
-    if (w->g_attn) { SLIM_TRY(launch_rmsnorm(x_new, w->g_attn, 1, Hd, s->rms_eps, dt, h, st)); a = h; }
-    else { SLIM_TRY(launch_row_rstd(x_new, 1, Hd, s->rms_eps, dt, rstd, st)); sc = rstd; }
-    SLIM_TRY(launch_gemv(w->wq, nullptr, a, sc, w->bq, nullptr, qd, Hd, dt, q, st));
-    SLIM_TRY(launch_gemv(w->wk, nullptr, a, sc, w->bk, nullptr, kvd, Hd, dt, k_new, st));
-    SLIM_TRY(launch_gemv(w->wv, nullptr, a, sc, w->bv, nullptr, kvd, Hd, dt, v_new, st));
-    SLIM_TRY(launch_rope(q, nullptr, position, 1, Hq, d, s->rope_theta, dt, st));
-    SLIM_TRY(launch_rope(k_new, nullptr, position, 1, Hkv, d, s->rope_theta, dt, st));
+    float eps = s->rms_eps;
+    if (w->g_attn) { SLIM_TRY(launch_rmsnorm(x_new, w->g_attn, 1, Hd, s->rms_eps, dt, h, st)); a = h; eps = -1.f; }
+    SLIM_TRY(launch_gemv_qkv(w->wq, w->wk, w->wv, w->bq, w->bk, w->bv, a, eps, qd, kvd, Hd, position, s->rope_theta, dt, q,
+                             k_new, v_new, st));
     // attention over the active blocks, the earlier response tokens and the token itself
     SLIM_TRY(launch_decode_attn(q, gpu_pool, slot_bytes, layer_offset, block_of_slot, n_slots, s->block, n_prompt_tokens,
                                 k_response, v_response, n_response + 1, Hq, Hkv, 1.0f / sqrtf((float)d), dt, o,
                                 (float*)(ws + p.attn), st));
     // output projection + residual, FFN + residual
-    SLIM_TRY(launch_gemv(w->wo, nullptr, o, nullptr, nullptr, x_new, Hd, qd, dt, x_out, st));
+    SLIM_TRY(launch_gemv(w->wo, nullptr, o, nullptr, -1.f, nullptr, x_new, Hd, qd, dt, x_out, st));
     a = x_out;
-    sc = nullptr;
-    if (w->g_ffn) { SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, 1, Hd, s->rms_eps, dt, h, st)); a = h; }
-    else { SLIM_TRY(launch_row_rstd(x_out, 1, Hd, s->rms_eps, dt, rstd + 1, st)); sc = rstd + 1; }
-    SLIM_TRY(launch_gemv(w->w_gate, w->w_up, a, sc, nullptr, nullptr, s->ffn, Hd, dt, act, st));
-    SLIM_TRY(launch_gemv(w->w_down, nullptr, act, nullptr, nullptr, x_out, Hd, s->ffn, dt, x_out, st));
+    eps = s->rms_eps;
+    if (w->g_ffn) { SLIM_TRY(launch_rmsnorm(x_out, w->g_ffn, 1, Hd, s->rms_eps, dt, h, st)); a = h; eps = -1.f; }
+    SLIM_TRY(launch_gemv(w->w_gate, w->w_up, a, nullptr, eps, nullptr, nullptr, s->ffn, Hd, dt, act, st));
+    SLIM_TRY(launch_gemv(w->w_down, nullptr, act, nullptr, -1.f, nullptr, x_out, Hd, s->ffn, dt, x_out, st));
 #undef SLIM_TRY
     return SLIM_OK;
 }

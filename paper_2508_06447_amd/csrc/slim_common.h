@@ -133,8 +133,11 @@ int launch_compact_multi(int n_arrays, const void* const* src, void* const* dst,
 int launch_decode_attn(const void* q, const void* pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot,
                        int n_slots, int block, int n_prompt, const void* k_resp, const void* v_resp, int n_resp, int Hq,
                        int Hkv, float scale, int dtype, void* out, float* part, hipStream_t st);
-int launch_gemv(const void* w0, const void* w1, const void* x, const float* scale, const void* bias, const void* residual,
-                int n_out, int k_in, int dtype, void* out, hipStream_t st);
+int launch_gemv(const void* w0, const void* w1, const void* x, const float* scale, float norm_eps, const void* bias,
+                const void* residual, int n_out, int k_in, int dtype, void* out, hipStream_t st);
+int launch_gemv_qkv(const void* wq, const void* wk, const void* wv, const void* bq, const void* bk, const void* bv,
+                    const void* x, float norm_eps, int n_q, int n_kv, int k_in, int position, float theta, int dtype,
+                    void* q, void* k, void* v, hipStream_t st);
 int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int Hkv, int d, float scale,
                 int dtype, void* out, hipStream_t st);
 

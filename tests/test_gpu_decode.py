@@ -480,3 +480,40 @@ def test_decode_layer_reduced_shapes(slim, fold):
 def test_decode_layer_full_llama_shape(slim):
     """LLaMA-3.1-8B-shaped layer, 32768-token prompt, 128 active blocks (8192 tokens), 16 response tokens, folded gains."""
     decode_case(slim, inputs.WORKLOADS["cfg3"], n_slots=128, n_active=128, n_resp=16, fold=True, seed=80, np_dtype=np.float32)
+
+
+def test_decode_layer_replayed_from_a_hip_graph(slim):
+    """The layer only enqueues kernels on the caller's stream (no allocation, no memset, no host synchronisation), so
+    a caller can capture it into a HIP graph.  Every replay, with eager work and synchronisation in between and a new
+    input each time, must equal the eager call bit for bit."""
+    bf = torch.bfloat16
+    wl = inputs.scaled(inputs.WORKLOADS["cfg2"], seq=1000, hidden=512, n_q_heads=8, n_kv_heads=2, ffn=1024)
+    Hq, Hkv, d, block = wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.block
+    w = {kk: vv.cuda() for kk, vv in inputs.layer_weights(wl).items() if kk not in ("g_attn", "g_ffn")}
+    k, v = rand((wl.seq, Hkv, d), bf, 1), rand((wl.seq, Hkv, d), bf, 2)
+    pool, bos = build_pool(k, v, {0, 2, 5, 7, 11, 15}, 8, block, bf, seed=3)
+    pool, bos = pool.cuda(), bos.cuda()
+    n_resp = 3
+    kr, vr = torch.zeros(n_resp + 1, Hkv, d, dtype=bf).cuda(), torch.zeros(n_resp + 1, Hkv, d, dtype=bf).cuda()
+    kr[:n_resp], vr[:n_resp] = rand((n_resp, Hkv, d), bf, 4).cuda(), rand((n_resp, Hkv, d), bf, 5).cuda()
+    shape = slim.make_shape(wl.hidden, Hq, Hkv, d, wl.ffn, block, wl.unit, wl.window, bf, wl.rope_theta, wl.rms_eps)
+    import ctypes
+    ws = torch.empty(slim.load_library().slim_decode_layer_workspace_bytes(ctypes.byref(shape), 8, n_resp), dtype=torch.uint8,
+                     device="cuda")
+    x_in = rand((wl.hidden,), bf, 6).cuda()
+    slim.slim_decode_layer(shape, w, x_in, wl.seq + n_resp, pool, bos, wl.seq, kr, vr, n_resp, workspace=ws)   # warm-up
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        z_g, q_g = slim.slim_decode_layer(shape, w, x_in, wl.seq + n_resp, pool, bos, wl.seq, kr, vr, n_resp, workspace=ws)
+    a, wt = rand((300, 512), bf, 7).cuda(), rand((256, 512), bf, 8, 0.05).cuda()
+    for step in range(4):
+        x_in.copy_(rand((wl.hidden,), bf, 10 + step).cuda())
+        graph.replay()
+        torch.cuda.synchronize()
+        z_r, q_r, k_r = z_g.clone(), q_g.clone(), kr[n_resp].clone()
+        slim.slim_linear(a, wt)                          # eager work between the replays
+        z_e, q_e = slim.slim_decode_layer(shape, w, x_in, wl.seq + n_resp, pool, bos, wl.seq, kr, vr, n_resp, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(z_r, z_e) and torch.equal(q_r, q_e) and torch.equal(k_r, kr[n_resp]), f"replay {step} differs"
+        assert torch.isfinite(z_r.float()).all()
