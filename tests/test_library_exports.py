@@ -84,6 +84,13 @@ def test_argument_errors_are_reported_before_anything_is_enqueued(lib):
     assert lib.slim_rmsnorm_linear(one, 4096, one, null, one, 64, 64, 4096, 64, 0, one, null) == -2      # fp32
     assert lib.slim_rmsnorm_swiglu_linear(one, 4096, one, null, one, 64, 64, 4096, 64, 1, one, null) == -1   # no w_up
     assert lib.slim_fold_gain(one, null, 8, 8, 1, one, null) == -1
+    assert lib.slim_gemv(one, null, one, null, null, null, 64, 4100, 1, one, null) == -2            # k % 8
+    assert lib.slim_gemv(one, null, one, null, null, null, 64, 32768, 1, one, null) == -2           # token does not fit LDS
+    assert lib.slim_gemv(null, null, one, null, null, null, 64, 4096, 1, one, null) == -1
+    assert lib.slim_decode_attn_workspace_bytes(128, 16, 32) == (128 + 1) * 32 * 130 * 4 and lib.slim_decode_attn_workspace_bytes(0, 0, 32) == 0
+    assert lib.slim_decode_attn(one, one, 262144, 0, one, 128, 64, 32768, null, null, 0, 32, 8, 96, fl(0), 1, one, one, 1 << 30, null) == -2   # head_dim
+    assert lib.slim_decode_attn(one, one, 1024, 0, one, 128, 64, 32768, null, null, 0, 32, 8, 128, fl(0), 1, one, one, 1 << 30, null) == -1   # slot too small
+    assert lib.slim_decode_attn(one, one, 262144, 0, one, 128, 64, 32768, null, null, 0, 32, 8, 128, fl(0), 1, one, one, 16, null) == -3
     pair = lambda m, b1, b2: lib.slim_linear_pair(one, 4096, one, b1, 4096, 4096, one, one, b2, 1024, 1024, one, null, m,
                                                   4096, 1, null)
     assert pair(512, one, null) == -1 and pair(64, null, null) == -2                               # one bias only; m <= 128
