@@ -50,8 +50,6 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     n = slim.kept_tokens(N, wl.block, n_keep)
     bf = torch.bfloat16
     es = 2
-    h_all = torch.randn(N, Hd, device=dev).to(bf)
-    h = h_all[:n].contiguous()
     k_all = torch.randn(N, Hkv, d, device=dev).to(bf)
     q_win = torch.randn(wl.window, Hq, d, device=dev).to(bf)
     q = torch.randn(n, Hq, d, device=dev).to(bf)
@@ -59,11 +57,8 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     o = torch.empty_like(q)
     act = torch.empty(n, F, device=dev, dtype=bf)
     y = torch.randn(n, Hd, device=dev).to(bf)
-    out_kv = torch.empty(N, Hkv * d, device=dev, dtype=bf)
-    out_q = torch.empty(n, Hq * d, device=dev, dtype=bf)
     out_h = torch.empty(n, Hd, device=dev, dtype=bf)
     scores = torch.empty(slim.n_blocks(N, wl.block), device=dev, dtype=torch.float32)
-    sws = torch.empty(4096, device=dev, dtype=torch.uint8)
     kept = slim.slim_select_topk_blocks(torch.randn_like(scores), n_keep)
     lib = slim.load_library()
     st = torch.cuda.current_stream().cuda_stream
