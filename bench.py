@@ -230,7 +230,7 @@ def bench_model(args, slim, inputs, wl, dev):
              for _, w in inputs.model_weights(wl, workers=16)]
     shape = slim.make_shape(wl.hidden, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.ffn, wl.block, wl.unit,
                             wl.window, x.dtype, wl.rope_theta, wl.rms_eps)
-    keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, wl.schedule)
+    keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, {} if args.no_prune else wl.schedule)
     out = slim.slim_prefill_model(shape, w_gpu, x, pos, keeps)           # allocates outputs once
     lib = slim.load_library()
     import ctypes as C
@@ -269,7 +269,7 @@ def bench_model(args, slim, inputs, wl, dev):
                                f"blocks (block {wl.block}, window {wl.window})",
                    "n_tokens": wl.seq, "n_keep_blocks": [k for k in keeps if k],
                    "tokens_after_pruning_layers": [wl.seq] + [per_layer[l] for l in sorted(wl.schedule)],
-                   "seed": wl.seed},
+                   "seed": wl.seed, **({"variant": "no pruning (dense prefill)"} if args.no_prune else {})},
         "prefill_ms": round(ms, 3), "model_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
         "model_mfma_frac": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "unpruned_flops_ratio": None,
@@ -460,6 +460,8 @@ def main():
                     help="variant: pooled scoring baselines of the ablation instead of TokenUnits")
     ap.add_argument("--placement", choices=["before", "after"], default="before",
                     help="variant: drop the blocks after the pruning layer's attention instead of before it")
+    ap.add_argument("--no-prune", action="store_true",
+                    help="variant (model workloads): every layer a Preserve layer, the dense prefill the pruned one is compared with")
     ap.add_argument("--block", type=int, default=0, help="variant: block size override (the paper's block-size sweep)")
     ap.add_argument("--unit", type=int, default=0, help="variant: TokenUnit size override")
     ap.add_argument("--window", type=int, default=0, help="variant: local query window override")

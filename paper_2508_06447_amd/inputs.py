@@ -89,6 +89,10 @@ WORKLOADS = {
     # card's (28 layers, hidden 3584, 28 query / 4 kv heads of 128, FFN 18944, Q/K/V bias, theta 1e6).
     "cfg6": Workload("cfg6", "bf16", 32768, block=64, window=64, keep_ratio=0.375, seed=5,
                      x_kind="zipf", **_QWEN),
+    # The schedule the paper uses for LLaMA-3.1-8B (Section 5.1: pruning at layers 10/20/30 down to 8k/4k/2k of a 32k
+    # prompt, i.e. 0.25/0.5/0.5 of the incoming blocks), on the same random-init layer shapes as cfg5.
+    "cfg8": Workload("cfg8", "bf16", 32768, block=64, window=64, keep_ratio=1.0, seed=7,
+                     x_kind="normal", n_layers=32, schedule={10: 0.25, 20: 0.5, 30: 0.5}, **_LLAMA),
     "cfg7": Workload("cfg7", "bf16", 32768, block=64, window=64, keep_ratio=1.0, seed=6,
                      x_kind="normal", n_layers=28, schedule={9: 0.375, 18: 0.5, 26: 0.66666}, **_QWEN),
 }
