@@ -114,10 +114,9 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     rows = [
         ("row_rstd_all", "hbm", N * Hd * es + N * 4, lambda: rstd(x, N, rstd_all)),   # in the layer it also writes the
         ("rope_table_all", "alu", N * d * 4, lambda: slim.slim_rope_table(pos, N, d, wl.rope_theta)),   # cos/sin table
-        ("window_q_proj", "mfma", 2 * wl.window * Hd * Hq * d,
-         lambda: lin_scaled(x[w0:], wd["wq"], bq, rstd_all[w0:], wl.window, Hq * d, q_win)),
-        ("rope_window_q", "latency", 2 * wl.window * Hq * d * es, lambda: slim.slim_rope(q_win, pos[w0:], wl.rope_theta)),
-        ("window_query", "latency", wl.window * Hq * d * es, lambda: slim.slim_window_query(q_win, Hkv)),
+        # window query straight from the window's rows: split skinny projection + (rotation, means); bytes = Wq once
+        ("window_query_from_rows", "hbm", Hq * d * Hd * es + wl.window * Hd * es,
+         lambda: slim.slim_window_query_from_rows(x[w0:], wd["wq"], bq, rope_all[w0:], Hq, Hkv, rstd=rstd_all[w0:])),
         ("k_proj_all_rope_score", "mfma", 2 * N * Hd * Hkv * d,
          lambda: lin_rope(x, wd["wk"], bk, rope_all, N, Hkv, rstd_all, k_all, qt, tsc)),
         ("score_blocks_from_token_scores", "latency", N * Hkv * 4 + scores.numel() * 4,

@@ -165,6 +165,16 @@ int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w
  *                      reduced to [-pi, pi] in double, evaluated in float (within 4e-7 of the double result).
  *   slim_window_query: qt[Hkv*d] float = (1/(window*Hq)) sum over the window rows and over the query heads of
  *                      each kv group of q_win[window, Hq, d]: Eq. (2)'s q_l with its head mean folded in.
+ *   slim_window_query_from_rows (+ _workspace_bytes): the same qt, straight from the hidden rows of the window:
+ *                      qt = (1/(window*Hq)) sum over rows t and heads of the group of RoPE_t(rows[t] . wq_h^T *
+ *                      rstd[t] + bq_h), with no Query states written in between (the projection is kept in float
+ *                      through the rotation and the means, so it differs from projecting to bf16 first by that
+ *                      rounding).  rows[window, k_in] bf16 with row stride lda; wq [Hq*128, k_in]; bias NULL = none;
+ *                      rstd[window] as for slim_linear_rope (NULL = rows are used as they are); table[window, 128] =
+ *                      slim_rope_table of the window rows' positions.  The projection is a skinny product whose
+ *                      reduction dimension is split over workgroups; the partial sums go through `workspace` and are
+ *                      added in a fixed order.  bf16, head_dim 128, k_in % 64 == 0, lda % 8 == 0, window <= 256,
+ *                      16-byte aligned pointers: UNSUPPORTED otherwise; WORKSPACE_TOO_SMALL.
  *   slim_linear_rope:  out[m, n_heads, 128] = RoPE(a[m, k_in] . w^T + bias) (bias NULL = none), rotation in float
  *                      on the unrounded projection, one rounding.  With qt != NULL (then n_heads = Hkv) also
  *                      token_scores[m, n_heads] float = the rounded key of (token, head) dotted with qt's slice.
@@ -180,6 +190,10 @@ int slim_swiglu_linear(const void* a, int lda, const void* w_gate, const void* w
 int slim_rope_table(const int* pos, int n, int head_dim, float theta, float* table, void* stream);
 int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_heads, int head_dim, int dtype,
                       float* qt, void* stream);
+size_t slim_window_query_from_rows_workspace_bytes(int window, int n_q_heads);
+int slim_window_query_from_rows(const void* rows, int lda, const void* wq, const void* bias, const float* rstd,
+                                const float* table, int window, int n_q_heads, int n_kv_heads, int k_in,
+                                float* qt, void* workspace, size_t workspace_bytes, void* stream);
 int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m,
                      int n_heads, int head_dim, int k_in, int ldo, int dtype, const float* rstd, void* out,
                      const float* qt, float* token_scores, void* stream);

@@ -25,7 +25,8 @@ EXPORTS = (
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
     "slim_kv_swap_workspace_bytes", "slim_kv_swap", "slim_decode_attn_workspace_bytes", "slim_decode_attn", "slim_gemv", "slim_decode_layer_workspace_bytes",
     "slim_decode_layer",
-    "slim_rope_table", "slim_window_query", "slim_linear_rope", "slim_score_blocks_from_token_scores",
+    "slim_rope_table", "slim_window_query", "slim_window_query_from_rows_workspace_bytes", "slim_window_query_from_rows",
+    "slim_linear_rope", "slim_score_blocks_from_token_scores",
     "slim_linear_pair", "slim_row_rstd", "slim_rmsnorm_linear", "slim_rmsnorm_swiglu_linear", "slim_fold_gain",
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
@@ -89,6 +90,9 @@ def load_library(path: str | None = None) -> C.CDLL:
                                       vp, sz, vp]
     lib.slim_rope_table.argtypes = [vp, i, i, f, vp, vp]
     lib.slim_window_query.argtypes = [vp, i, i, i, i, i, vp, vp]
+    lib.slim_window_query_from_rows_workspace_bytes.restype = sz
+    lib.slim_window_query_from_rows_workspace_bytes.argtypes = [i, i]
+    lib.slim_window_query_from_rows.argtypes = [vp, i, vp, vp, vp, vp, i, i, i, i, vp, vp, sz, vp]
     lib.slim_linear_rope.argtypes = [vp, i, vp, vp, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp]
     lib.slim_row_rstd.argtypes = [vp, i, i, f, i, vp, vp]
     lib.slim_linear_pair.argtypes = [vp, i, vp, vp, i, i, vp, vp, vp, i, i, vp, vp, i, i, i, vp]
@@ -304,6 +308,22 @@ def slim_window_query(q_win: torch.Tensor, n_kv_heads: int) -> torch.Tensor:
     qt = torch.empty(n_kv_heads * d, dtype=torch.float32, device=q_win.device)
     _check(lib.slim_window_query(_dev(q_win, "q_win"), w, Hq, n_kv_heads, d, _dtype_code(q_win), _dev(qt, "qt"), _stream()),
            "slim_window_query")
+    return qt
+
+
+def slim_window_query_from_rows(rows: torch.Tensor, wq: torch.Tensor, bias: torch.Tensor | None, table: torch.Tensor,
+                                n_q_heads: int, n_kv_heads: int, rstd: torch.Tensor | None = None) -> torch.Tensor:
+    """qt[Hkv*128] float32 of Eq. (2) from the window's hidden rows [w, k_in] (row stride = rows.stride(0)): projection,
+    rotation with table[w,128] and the window / head means without Query states in between."""
+    lib = load_library()
+    w, k_in = rows.shape
+    qt = torch.empty(n_kv_heads * 128, dtype=torch.float32, device=rows.device)
+    nbytes = lib.slim_window_query_from_rows_workspace_bytes(w, n_q_heads)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=rows.device)
+    _check(lib.slim_window_query_from_rows(_dev(rows, "rows"), rows.stride(0), _dev(wq, "wq"), _dev(bias, "bias"),
+                                           _dev(rstd, "rstd"), _dev(table, "table"), w, n_q_heads, n_kv_heads, k_in,
+                                           _dev(qt, "qt"), _dev(ws, "workspace"), ws.numel(), _stream()),
+           "slim_window_query_from_rows")
     return qt
 
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslim.so")
-SOURCES = ("api.hip", "prune.hip", "norm_rope.hip", "gemm.hip", "attn.hip", "kvswap.hip", "decode.hip", "gemv.hip", "probe.hip")
+SOURCES = ("api.hip", "prune.hip", "norm_rope.hip", "gemm.hip", "attn.hip", "kvswap.hip", "decode.hip", "gemv.hip", "window.hip", "probe.hip")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 

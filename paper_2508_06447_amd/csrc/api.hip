@@ -2,6 +2,7 @@
 // the pruned prefill layer.  No kernel lives here.
 #include "slim_common.h"
 #include <math.h>
+#include <algorithm>
 #include <string.h>
 
 namespace slim {
@@ -39,7 +40,9 @@ static LayerPlan plan_layer(const slim_layer_shape* s, int N, int n_keep) {
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
     p.h = take((size_t)N * s->hidden * es);              // RMSNorm output: all N rows, later n' rows
     p.k_all = take((size_t)N * kv * es);                 // Key states of all tokens
-    p.q_win = take((size_t)s->window * qd * es);
+    // Query states of the window, or (window query taken straight from the hidden rows) its float partial sums
+    p.q_win = take(std::max((size_t)s->window * qd * es,
+                            slim_window_query_from_rows_workspace_bytes(std::min(s->window, kWindowRowsMax), s->n_q_heads)));
     p.qt = take(slim_score_blocks_workspace_bytes(s->n_kv_heads, s->head_dim));
     p.scores = take((size_t)p.nb * sizeof(float));
     p.table = take((size_t)N * s->head_dim * sizeof(float));            // cos | sin of every token's rotation angles
@@ -266,6 +269,25 @@ int slim_window_query(const void* q_win, int window, int n_q_heads, int n_kv_hea
         return SLIM_INVALID_ARG;
     if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
     return launch_window_query(q_win, window, n_q_heads, n_kv_heads, head_dim, dtype, qt, (hipStream_t)stream);
+}
+
+size_t slim_window_query_from_rows_workspace_bytes(int window, int n_q_heads) {
+    if (window < 1 || n_q_heads < 1) return 0;
+    return align_up((size_t)kWindowSplitsMax * window * n_q_heads * 128 * sizeof(float), 256);
+}
+
+int slim_window_query_from_rows(const void* rows, int lda, const void* wq, const void* bias, const float* rstd,
+                                const float* table, int window, int n_q_heads, int n_kv_heads, int k_in, float* qt,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (!rows || !wq || !table || !qt || !workspace || window < 1 || n_q_heads < 1 || n_kv_heads < 1 || k_in < 1 ||
+        lda < k_in || n_q_heads % n_kv_heads != 0)
+        return SLIM_INVALID_ARG;
+    if (window > kWindowRowsMax || k_in % 64 != 0 || lda % 8 != 0 || !aligned16(rows) || !aligned16(wq) ||
+        !aligned16(workspace))
+        return SLIM_UNSUPPORTED;
+    if (workspace_bytes < slim_window_query_from_rows_workspace_bytes(window, n_q_heads)) return SLIM_WORKSPACE_TOO_SMALL;
+    return launch_window_query_rows(rows, lda, wq, bias, rstd, table, window, n_q_heads, n_kv_heads, k_in,
+                                    (float*)workspace, qt, (hipStream_t)stream);
 }
 
 int slim_linear_rope(const void* a, int lda, const void* w, const void* bias, const float* table, int m, int n_heads,
@@ -532,12 +554,22 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     const int n = p.n_out;
     const int w_eff = s->window < N ? s->window : N;
     const bool after = p.prune && s->placement == SLIM_PRUNE_AFTER_ATTENTION;
+    // The window query: with the scores riding on the Key projection it is all that is needed of the window's Query
+    // states, and it is taken straight from the window's hidden rows (skinny split projection, rotation and means in
+    // float); both placements use the same kernels, so they select from identical scores.
+    const bool win_direct = fused_score && w_eff <= kWindowRowsMax;
+    auto window_query_direct = [&]() -> int {
+        const unsigned char* r_win = (const unsigned char*)rows_in + (size_t)(N - w_eff) * Hd * es;
+        return launch_window_query_rows(r_win, Hd, w->wq, w->bq, sc_in ? sc_in + (N - w_eff) : nullptr,
+                                        table + (size_t)(N - w_eff) * d, w_eff, Hq, Hkv, Hd, (float*)q_win, qt, st);
+    };
     if (after) {
         // Attention first, over all N tokens; its last w_eff Query rows are the local window.
         void* o_all = ws + p.o_all;
         SLIM_TRY(project_qv(rows_in, sc_in, pos_in, N, qc, vc));
         const unsigned char* q_last = (const unsigned char*)qc + (size_t)(N - w_eff) * qd * es;
-        if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
+        if (win_direct) SLIM_TRY(window_query_direct());
+        else if (fused_score) SLIM_TRY(launch_window_query(q_last, w_eff, Hq, Hkv, d, dt, qt, st));
         SLIM_TRY(project_rope(rows_in, sc_in, w->wk, w->bk, pos_in, 0, N, Hkv, k_all, ktab, fused_score ? qt : nullptr, tscore));
         SLIM_TRY(launch_attn(qc, k_all, vc, N, Hq, Hkv, d, 0.f, dt, o_all, st));
         float* scores = scores_out ? scores_out : (float*)(ws + p.scores);
@@ -548,7 +580,9 @@ int slim_pruned_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
         SLIM_TRY(launch_compact(o_all, nullptr, kept_blocks_out, n_keep, s->block, N, qd, dt, o, nullptr, st));
         resid = x_out;
     } else {
-    if (p.prune) {
+    if (p.prune && win_direct) {
+        SLIM_TRY(window_query_direct());
+    } else if (p.prune) {
         // Query states of the local window (last w_eff rows) and their head-group-summed mean.
         const unsigned char* r_win = (const unsigned char*)rows_in + (size_t)(N - w_eff) * Hd * es;
         SLIM_TRY(project_rope(r_win, sc_in ? sc_in + (N - w_eff) : nullptr, w->wq, w->bq,

@@ -117,6 +117,13 @@ int launch_row_rstd(const void* x, int n, int hidden, float eps, int dtype, floa
                     const int* pos = nullptr, int d = 0, float theta = 0.f, float* table = nullptr);
 int launch_fold_gain(const void* w, const void* gain, int n_out, int k_in, int dtype, void* out, hipStream_t st);
 int launch_window_query(const void* q_win, int w, int Hq, int Hkv, int d, int dtype, float* qtilde, hipStream_t st);
+// Window query from the hidden rows of the window (skinny split projection + rotation + means); `partial` holds
+// kWindowSplitsMax * w * Hq * 128 floats.
+constexpr int kWindowSplitsMax = 4;
+constexpr int kWindowRowsMax = 256;
+int launch_window_query_rows(const void* x, int lda, const void* wq, const void* bias, const float* rstd,
+                             const float* table, int w, int Hq, int Hkv, int k_in, float* partial, float* qt,
+                             hipStream_t st);
 int launch_token_score_blocks(const float* token_scores, int N, int H, int block, int unit, float* scores, hipStream_t st);
 int launch_unit_keys(const void* k, int N, int E, int block, int unit, int dtype, float* k_rep, hipStream_t st);
 int launch_score_from_unit_keys(const void* q_win, const float* k_rep, int N, int w, int Hq, int Hkv, int d,

@@ -255,6 +255,46 @@ def test_linear_rope_epilogue_and_token_scores(slim, m, heads, k, with_bias):
     np.testing.assert_allclose(f64(ts), want_ts, rtol=0, atol=2e-5 * max(1.0, np.abs(want_ts).max()))
 
 
+@pytest.mark.parametrize("w,Hq,Hkv,hidden,with_bias,scaled", [
+    (64, 32, 8, 4096, False, True),     # the LLaMA-shaped window: 4 splits of the reduction dimension
+    (64, 28, 4, 3584, True, True),      # Qwen-shaped: bias, 56 chunks dealt unevenly to the waves
+    (7, 4, 4, 128, True, False),        # fewer rows than one MFMA tile, 2 chunks for 4 waves
+    (100, 8, 2, 256, False, True),      # two row tiles, the second ragged
+    (256, 4, 1, 64, True, False),       # the largest window, a single chunk
+    (1, 2, 2, 512, False, True),
+])
+def test_window_query_from_rows(slim, w, Hq, Hkv, hidden, with_bias, scaled):
+    """qt from the window's hidden rows (split projection, rotation and means in float) against the oracle's
+    projection + RoPE + window / head means in float64."""
+    print(f"window query from rows w={w} Hq={Hq} Hkv={Hkv} hidden={hidden} bias={with_bias} scaled={scaled}", flush=True)
+    bf, d, theta = torch.bfloat16, 128, 500000.0
+    g = np.random.default_rng(w + Hq)
+    big = rand((w + 3, hidden), bf, 11, 2.0)
+    rows = big[3:]                                                            # a view into a larger buffer
+    wq = rand((Hq * d, hidden), bf, 12, 0.05)
+    b = rand((Hq * d,), bf, 13, 1.0) if with_bias else None
+    pos = np.sort(g.choice(100000, w, replace=False)).astype(np.int32)
+    table = slim.slim_rope_table(dev(torch.from_numpy(pos)), w, d, theta)
+    x = f64(rows)
+    rstd = 1.0 / np.sqrt((x * x).mean(axis=1) + 1e-5) if scaled else None
+    xn = x * rstd[:, None] if scaled else x
+    q = so.project_heads(xn, f64(wq), Hq, d, pos, theta, True, None, None if b is None else f64(b))
+    want = so.window_query(q).reshape(Hkv, Hq // Hkv, d).sum(axis=1).reshape(-1) / Hq
+    rows_gpu = dev(big)[3:]
+    got = slim.slim_window_query_from_rows(rows_gpu, dev(wq), None if b is None else dev(b), table, Hq, Hkv,
+                                           rstd=None if rstd is None else dev(torch.from_numpy(rstd.astype(np.float32))))
+    # float accumulation over hidden * w * G products and the 4e-7 table: far inside a bf16 rounding of the states
+    np.testing.assert_allclose(f64(got), want, rtol=0, atol=2e-5 * max(1.0, np.abs(q).max()))
+    # the route through stored bf16 Query states agrees to the rounding of those states
+    if not scaled:
+        q_win = slim.slim_linear_rope(rows_gpu.contiguous(), dev(wq), None if b is None else dev(b), table, d)
+        via = slim.slim_window_query(q_win, Hkv)
+        assert (via - got).abs().max().item() < 2.0 ** -8 * max(1.0, np.abs(q).max())
+    again = slim.slim_window_query_from_rows(rows_gpu, dev(wq), None if b is None else dev(b), table, Hq, Hkv,
+                                             rstd=None if rstd is None else dev(torch.from_numpy(rstd.astype(np.float32))))
+    assert torch.equal(got, again)
+
+
 @pytest.mark.parametrize("N,block,unit,w,Hq,Hkv,hidden", [
     (1024, 64, 8, 64, 32, 8, 512), (1000, 64, 8, 4, 8, 2, 256), (1003, 64, 8, 16, 28, 4, 256), (333, 32, 5, 7, 4, 4, 128),
 ])

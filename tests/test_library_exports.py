@@ -74,6 +74,12 @@ def test_argument_errors_are_reported_before_anything_is_enqueued(lib):
     assert lib.slim_rope_table(null, 8, 128, fl(5e5), null, null) == -1                            # no output
     assert lib.slim_rope_table(null, 8, 127, fl(5e5), one, null) == -1                             # odd head_dim
     assert lib.slim_window_query(one, 4, 6, 4, 128, 1, one, null) == -1                            # Hq % Hkv
+    assert lib.slim_window_query_from_rows_workspace_bytes(64, 32) == 4 * 64 * 32 * 128 * 4
+    assert lib.slim_window_query_from_rows_workspace_bytes(0, 32) == 0
+    wqr = lambda window, k_in, Hq, ws: lib.slim_window_query_from_rows(one, k_in, one, null, null, one, window, Hq, 4, k_in,
+                                                                       one, one, ws, null)
+    assert wqr(64, 4096, 6, 1 << 30) == -1 and wqr(257, 4096, 8, 1 << 30) == -2 and wqr(64, 4000, 8, 1 << 30) == -2
+    assert wqr(64, 4096, 8, 4096) == -3
     rope = lambda head_dim, k_in, dtype: lib.slim_linear_rope(one, k_in, one, null, one, 64, 8, head_dim, k_in, 8 * head_dim,
                                                               dtype, null, one, null, null, null)
     assert rope(64, 4096, 1) == -2 and rope(128, 4000, 1) == -2 and rope(128, 4096, 0) == -2       # head_dim, k % 64, fp32
