@@ -65,9 +65,22 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     xc = torch.empty(n, Hd, device=dev, dtype=bf)
     pc = torch.empty(n, dtype=torch.int32, device=dev)
 
-    def compact():
-        lib.slim_compact_tokens(x.data_ptr(), pos.data_ptr(), kept.data_ptr(), n_keep, wl.block, N, Hd, 1,
-                                xc.data_ptr(), pc.data_ptr(), st)
+    # HBM-bound kernels run on rotating buffer sets whose total exceeds the 256 MB memory-side cache several times,
+    # so that no call finds its operands cached from the previous one.
+    def rotating(make_call, bytes_per_call, *tensors):
+        n_sets = max(3, min(16, -(-(3 * 256 << 20) // max(bytes_per_call, 1))))
+        calls = [make_call(*tensors)] + [make_call(*[t.clone() for t in tensors]) for _ in range(n_sets - 1)]
+        state = [0]
+
+        def step():
+            calls[state[0] % n_sets]()
+            state[0] += 1
+        return step
+
+    def compact_call(xs, xd):
+        return lambda: lib.slim_compact_tokens(xs.data_ptr(), pos.data_ptr(), kept.data_ptr(), n_keep, wl.block, N, Hd, 1,
+                                               xd.data_ptr(), pc.data_ptr(), st)
+    compact = rotating(compact_call, 2 * n * Hd * es, x, xc)
 
     # The launches of one pruning layer with folded gains, in order (the layer runs exactly these kernels).
     rstd_all = torch.empty(N, dtype=torch.float32, device=dev)
@@ -107,8 +120,12 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     def compact_rstd():
         lib.slim_compact_tokens(rstd_all.data_ptr(), nul, kept.data_ptr(), n_keep, wl.block, N, 1, 0, rstd_kept.data_ptr(), nul, st)
 
-    def compact_k():
-        lib.slim_compact_tokens(k_all.data_ptr(), nul, kept.data_ptr(), n_keep, wl.block, N, Hkv * d, 1, k.data_ptr(), nul, st)
+    def compact_k_call(ks, kd):
+        return lambda: lib.slim_compact_tokens(ks.data_ptr(), nul, kept.data_ptr(), n_keep, wl.block, N, Hkv * d, 1,
+                                               kd.data_ptr(), nul, st)
+    compact_k = rotating(compact_k_call, 2 * n * Hkv * d * es, k_all, k)
+    rope_q = rotating(lambda qq: (lambda: slim.slim_rope(qq, pc, wl.rope_theta)), 2 * n * Hq * d * es, q)
+    rstd_y = rotating(lambda yy: (lambda: rstd(yy, n, rstd_kept)), n * Hd * es, y)
 
     bq, bk, bv = wd.get("bq"), wd.get("bk"), wd.get("bv")
     rows = [
@@ -127,11 +144,11 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
         ("compact_k", "hbm", 2 * n * Hkv * d * es, compact_k),
         ("compact_rstd", "latency", 2 * n * 4, compact_rstd),
         ("qv_proj", "mfma", 2 * n * Hd * (Hq + Hkv) * d, qv_pair),
-        ("rope_q", "hbm", 2 * n * Hq * d * es, lambda: slim.slim_rope(q, pc, wl.rope_theta)),
+        ("rope_q", "hbm", 2 * n * Hq * d * es, rope_q),
         ("prefill_attn", "mfma", 2 * n * n * d * Hq, lambda: slim.slim_prefill_attn(q, k, v, out=o)),
         ("o_proj_residual", "mfma", 2 * n * Hd * Hq * d,
          lambda: slim.slim_linear(o.view(n, Hq * d), wd["wo"], residual=y, out=out_h)),
-        ("row_rstd_kept", "hbm", n * Hd * es + n * 4, lambda: rstd(y, n, rstd_kept)),
+        ("row_rstd_kept", "hbm", n * Hd * es + n * 4, rstd_y),
         ("ffn_gate_up_swiglu", "mfma", 4 * n * Hd * F, swiglu_scaled),
         ("ffn_down_residual", "mfma", 2 * n * Hd * F, lambda: slim.slim_linear(act, wd["w_down"], residual=y, out=out_h)),
     ]
