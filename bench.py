@@ -152,6 +152,22 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
         ("ffn_gate_up_swiglu", "mfma", 4 * n * Hd * F, swiglu_scaled),
         ("ffn_down_residual", "mfma", 2 * n * Hd * F, lambda: slim.slim_linear(act, wd["w_down"], residual=y, out=out_h)),
     ]
+    # The stand-alone scoring and selection entry points on direct Query/Key tensors whose blocks carry a Zipf(1.1)
+    # scale (the layer's RMSNorm would cancel such a scale, so the layer-level scores are not skewed): Eq. 1-2 from
+    # stored keys, one pass over K, then top-k on those skewed scores.
+    from paper_2508_06447_amd import inputs as _inputs
+    qs, ks = _inputs.stage_qk(wl, skew=True)
+    qs, ks = qs.to(dev), ks.to(dev)
+    sc_skew = torch.empty_like(scores)
+    ws_sc = torch.empty(max(lib.slim_score_blocks_workspace_bytes(Hkv, d), 256), dtype=torch.uint8, device=dev)
+    score_alone = rotating(lambda kk: (lambda: slim.slim_score_blocks(qs, kk, wl.block, wl.unit, sc_skew, ws_sc)),
+                           N * Hkv * d * es, ks)
+    kept_skew = torch.empty_like(kept)
+    rows += [
+        ("score_blocks_from_keys_skewed", "hbm", N * Hkv * d * es + wl.window * Hq * d * es + scores.numel() * 4, score_alone),
+        ("select_topk_skewed", "latency", scores.numel() * 4 + n_keep * 4,
+         lambda: slim.slim_select_topk_blocks(sc_skew, n_keep, kept=kept_skew)),
+    ]
     table = {}
     for name, bound, work, fn in rows:
         med, mean = time_gpu(fn, reps)
