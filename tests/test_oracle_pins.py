@@ -234,6 +234,23 @@ def test_scores_closed_form_cases():
     assert (r8 >= np.array(want) - 1e-12).all() and (r8 <= tok.reshape(nb, B).max(1) + 1e-12).all()
 
 
+def test_short_trailing_unit_is_averaged_over_its_own_tokens():
+    # block 7, unit 3: units of 3, 3 and 1 tokens.  Only the lone token of the short unit carries a key, aligned
+    # with the group-summed window query, so that unit wins and its mean is that token's key itself.
+    w, Hq, Hkv, d, B, u = 2, 4, 2, 4, 7, 3
+    q = rng.standard_normal((w, Hq, d))
+    qt = q.mean(0).reshape(Hkv, Hq // Hkv, d).sum(1)
+    k = np.zeros((2 * B, Hkv, d))
+    k[2 * B - 1] = 3.0 * qt
+    np.testing.assert_array_equal(so.unit_keys(k[B:], u)[2], k[2 * B - 1])
+    r = so.block_scores(q, k, B, u)
+    np.testing.assert_allclose(r, [0.0, 3.0 * (qt * qt).sum() / Hq], rtol=1e-12)
+    # the same with a short last BLOCK: 9 tokens = a block of 7 and one of 2 (a single unit of 2 tokens)
+    k = np.zeros((9, Hkv, d))
+    k[7], k[8] = 1.0 * qt, 3.0 * qt
+    np.testing.assert_allclose(so.block_scores(q, k, B, u)[1], 2.0 * (qt * qt).sum() / Hq, rtol=1e-12)
+
+
 def test_scores_head_mapping_is_grouped_not_interleaved():
     # Hq=4, Hkv=2: heads 0,1 read kv head 0; heads 2,3 read kv head 1.
     d = 2
@@ -439,6 +456,12 @@ def test_kv_swap_hand_worked_and_invariants():
     r = so.kv_swap_step({0, 1, 2, 3}, {0, 1, 2, 7}, {4, 5, 6, 7}, 0.75)
     assert not r["swapped"] and r["active"] == {0, 1, 2, 3} and not r["offload"] and not r["load"]
     assert so.kv_swap_step({0, 1, 2, 3}, {0, 1, 2, 7}, {4, 5, 6, 7}, 0.76)["swapped"]
+    # the overlap is a fraction of the CANDIDATE set (Algorithm 1), not of the resident one: 3 of 4 candidates are
+    # among 8 resident blocks -> 0.75, no swap at gamma 0.5 (3/8 would swap); 1 of 2 -> 0.5, swap at gamma 0.6
+    r = so.kv_swap_step(set(range(8)), {0, 1, 2, 9}, {8, 9, 10}, 0.5)
+    assert r["overlap"] == 0.75 and not r["swapped"]
+    r = so.kv_swap_step(set(range(8)), {0, 9}, {8, 9, 10}, 0.6)
+    assert r["overlap"] == 0.5 and r["swapped"] and r["load"] == {9} and r["offload"] == set(range(1, 8))
     # gamma = 0 never swaps; gamma > 1 always takes the candidate set, with nothing to move when it is the old set
     assert not so.kv_swap_step({0, 1}, {2, 3}, {2, 3}, 0.0)["swapped"]
     r = so.kv_swap_step({0, 1}, {0, 1}, {5}, 1.5)
