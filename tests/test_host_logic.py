@@ -67,3 +67,47 @@ def test_generators_are_seeded_and_per_matrix():
     assert all(torch.equal(a[k], d[k]) for k in a)
     x1, x2 = inputs.hidden_states(wl), inputs.hidden_states(wl)
     assert torch.equal(x1, x2) and x1.dtype == torch.bfloat16 and float(a["g_attn"].float().min()) == 1.0
+
+
+def test_product_and_oracle_do_not_know_each_other():
+    """The package never imports the oracle (no CPU fallback can hide in it), the oracle never imports the package,
+    and outside tests/ the oracle is imported only inside bench.py's cpu_baseline and __graft_entry__.smoke()."""
+    import ast
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def imported(path):
+        tree = ast.parse(open(path).read())
+        mods = set()
+        for node in ast.walk(tree):
+            if isinstance(node, ast.Import):
+                mods |= {a.name.split(".")[0] for a in node.names}
+            elif isinstance(node, ast.ImportFrom) and node.level == 0 and node.module:
+                mods.add(node.module.split(".")[0])
+        return mods
+
+    pkg = os.path.join(root, "paper_2508_06447_amd")
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            assert "oracle" not in imported(os.path.join(pkg, f)), f
+    for f in os.listdir(os.path.join(root, "oracle")):
+        if f.endswith(".py"):
+            assert "paper_2508_06447_amd" not in imported(os.path.join(root, "oracle", f)), f
+    # top-level scripts: the oracle only inside the named functions
+    for script, allowed in (("bench.py", {"cpu_baseline"}), ("__graft_entry__.py", {"smoke"})):
+        tree = ast.parse(open(os.path.join(root, script)).read())
+        for fn in [n for n in ast.walk(tree) if isinstance(n, (ast.FunctionDef, ast.Module))]:
+            own = [n for n in (fn.body if isinstance(fn, ast.Module) else ast.walk(fn))
+                   if isinstance(n, (ast.Import, ast.ImportFrom))]
+            for n in own:
+                names = [a.name for a in n.names] if isinstance(n, ast.Import) else [n.module or ""]
+                if any(m.split(".")[0] == "oracle" for m in names):
+                    assert isinstance(fn, ast.FunctionDef) and fn.name in allowed, (script, getattr(fn, "name", "module"))
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    from paper_2508_06447_amd import binding
+    with pytest.raises(FileNotFoundError):
+        binding.load_library(str(tmp_path / "libslim.so"))
+    with pytest.raises(ValueError):
+        binding._dev(torch.zeros(4), "x")                 # a CPU tensor is refused, not silently computed on
