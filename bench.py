@@ -131,8 +131,9 @@ def stage_table(slim, wl, wd, x, pos, n_keep, reps):
     rows = [
         ("row_rstd_all", "hbm", N * Hd * es + N * 4, lambda: rstd(x, N, rstd_all)),   # in the layer it also writes the
         ("rope_table_all", "alu", N * d * 4, lambda: slim.slim_rope_table(pos, N, d, wl.rope_theta)),   # cos/sin table
-        # window query straight from the window's rows: split skinny projection + (rotation, means); bytes = Wq once
-        ("window_query_from_rows", "hbm", Hq * d * Hd * es + wl.window * Hd * es,
+        # window query straight from the window's rows: split skinny projection + (rotation, means); two launches that
+        # read Wq (32 MB) once: launch- and latency-bound, so no bandwidth figure
+        ("window_query_from_rows", "latency", Hq * d * Hd * es + wl.window * Hd * es,
          lambda: slim.slim_window_query_from_rows(x[w0:], wd["wq"], bq, rope_all[w0:], Hq, Hkv, rstd=rstd_all[w0:])),
         ("k_proj_all_rope_score", "mfma", 2 * N * Hd * Hkv * d,
          lambda: lin_rope(x, wd["wk"], bk, rope_all, N, Hkv, rstd_all, k_all, qt, tsc)),
