@@ -64,6 +64,22 @@ int slim_score_blocks(const void* q_win, const void* k, int n_tokens, int window
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
+ * slim_score_blocks for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and
+ * results (bit for bit) as slim_score_blocks, minus the workspace: the head-group-summed window query
+ * goes through a 32 KiB array that lives in the library's device image (one copy per GPU, held until the
+ * process ends).  The call allocates and frees nothing.  The first call on a device looks up that
+ * device's copy of the array (one runtime query, no allocation; make that first call outside a capture).
+ * Limit: Hkv * head_dim <= 8192 (UNSUPPORTED beyond, as for slim_score_blocks).  Every call on one GPU
+ * shares that GPU's array: calls that overlap on one GPU (different streams, or different threads)
+ * race on it, so serialise them; the array keeps the last call's window query and every call overwrites
+ * all of it that it reads.  Other errors as slim_score_blocks.
+ */
+int slim_score_blocks_static(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads,
+                             int n_kv_heads, int head_dim, int block, int unit, int dtype, float* scores,
+                             void* stream);
+
+/* ------------------------------------------------------------------------------------------------
  * Pooled block scores -- the two baselines of the scoring ablation (Table 3, "Block Importance
  * Scoring Algorithm"): one representative key per block, the average of its token Key states
  * (SLIM_POOL_AVG, which is Eq. 1-2 with a single TokenUnit per block) or their element-wise maximum

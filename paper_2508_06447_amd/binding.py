@@ -22,6 +22,7 @@ FORCE_FIRST, FORCE_LAST = 1, 2
 
 EXPORTS = (
     "slim_status_string", "slim_last_hip_error", "slim_score_blocks_workspace_bytes", "slim_score_blocks",
+    "slim_score_blocks_static",
     "slim_score_blocks_pooled", "slim_unit_keys", "slim_score_blocks_from_unit_keys",
     "slim_kv_swap_workspace_bytes", "slim_kv_swap", "slim_decode_attn_workspace_bytes", "slim_decode_attn", "slim_gemv", "slim_decode_layer_workspace_bytes",
     "slim_decode_layer",
@@ -74,6 +75,7 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_score_blocks_workspace_bytes.restype = sz
     lib.slim_score_blocks_workspace_bytes.argtypes = [i, i]
     lib.slim_score_blocks.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
+    lib.slim_score_blocks_static.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp]
     lib.slim_score_blocks_pooled.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
     lib.slim_unit_keys.argtypes = [vp, i, i, i, i, i, i, vp, vp]
     lib.slim_score_blocks_from_unit_keys.argtypes = [vp, vp, i, i, i, i, i, i, i, i, vp, vp, sz, vp]
@@ -183,6 +185,18 @@ def slim_score_blocks(q_win: torch.Tensor, k: torch.Tensor, block: int, unit: in
     _check(lib.slim_score_blocks(_dev(q_win, "q_win"), _dev(k, "k"), N, w, Hq, Hkv, d, block, unit, _dtype_code(k),
                                  _dev(scores, "scores"), _dev(workspace, "workspace"), workspace.numel(), _stream()),
            "slim_score_blocks")
+    return scores
+
+
+def slim_score_blocks_static(q_win: torch.Tensor, k: torch.Tensor, block: int, unit: int,
+                             scores: torch.Tensor) -> torch.Tensor:
+    """slim_score_blocks without a workspace: the library's own per-GPU scratch array carries the window query.
+    The caller passes every buffer, `scores` included, so the call allocates nothing."""
+    lib = load_library()
+    w, Hq, d = q_win.shape
+    N, Hkv, _ = k.shape
+    _check(lib.slim_score_blocks_static(_dev(q_win, "q_win"), _dev(k, "k"), N, w, Hq, Hkv, d, block, unit,
+                                        _dtype_code(k), _dev(scores, "scores"), _stream()), "slim_score_blocks_static")
     return scores
 
 

@@ -3,9 +3,37 @@
 #include "slim_common.h"
 #include <math.h>
 #include <algorithm>
+#include <mutex>
 #include <string.h>
 
 namespace slim {
+
+// Scratch of the entry point that allocates nothing (slim_score_blocks_static): the head-group-summed window
+// query that travels from the reduction kernel to the scoring kernel.  Each GPU holds its own copy of the array
+// at its own address; host code uses the address hipGetSymbolAddress reports for the current device, never the
+// array's name.
+constexpr int kScratchFloats = 8192;                 // the largest Hkv * head_dim the scoring kernels take
+constexpr int kScratchDevices = 64;
+static __device__ __align__(256) float scratch[kScratchFloats];
+static std::mutex g_scratch_mutex;
+static float* g_scratch_ptr[kScratchDevices];        // per device, filled on the first call there
+
+static int scratch_of_current_device(float** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return set_hip_error(e);
+    if (dev < 0 || dev >= kScratchDevices) return SLIM_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return set_hip_error(e);
+        if (!p) return SLIM_HIP_ERROR;
+        g_scratch_ptr[dev] = (float*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SLIM_OK;
+}
 
 static thread_local char g_hip_error[256] = "";
 
@@ -110,6 +138,22 @@ int slim_score_blocks(const void* q_win, const void* k, int n_tokens, int window
     if (workspace_bytes < slim_score_blocks_workspace_bytes(n_kv_heads, head_dim)) return SLIM_WORKSPACE_TOO_SMALL;
     return launch_score(q_win, k, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit, 0, dtype, scores,
                         (float*)workspace, (hipStream_t)stream);
+}
+
+int slim_score_blocks_static(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads, int n_kv_heads,
+                             int head_dim, int block, int unit, int dtype, float* scores, void* stream) {
+    if (!q_win || !k || !scores || n_tokens < 1 || window < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 ||
+        block < 1 || unit < 1 || unit > block || n_q_heads % n_kv_heads != 0)
+        return SLIM_INVALID_ARG;
+    if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
+    const long long E = (long long)n_kv_heads * head_dim;
+    if (E > kScratchFloats || E % (dtype == SLIM_BF16 ? 8 : 4) != 0 || !aligned16(k)) return SLIM_UNSUPPORTED;
+    float* qt = nullptr;
+    const int rc = scratch_of_current_device(&qt);
+    if (rc != SLIM_OK) return rc;
+    // Both kernels write every element of the scratch they read (qt[0 .. E)), so nothing needs clearing.
+    return launch_score(q_win, k, n_tokens, window, n_q_heads, n_kv_heads, head_dim, block, unit, 0, dtype, scores, qt,
+                        (hipStream_t)stream);
 }
 
 int slim_score_blocks_pooled(const void* q_win, const void* k, int n_tokens, int window, int n_q_heads,
