@@ -42,6 +42,10 @@ constexpr int STAGE_BYTES = 2 * TILE_BYTES;             // K tile, then V tile
 __device__ __forceinline__ int k_off(int r, int c) { return (r * 16 + (c ^ (r & 15))) * 16; }
 __device__ __forceinline__ int v_off(int r, int c) { return (r * 16 + (c ^ ((r & 3) << 2))) * 16; }
 
+// GROUPED (4 query heads per kv head): the four waves of a workgroup take the same 64 queries of the four heads
+// that share a kv head, so all of them stop at the same diagonal and no wave runs units that are masked for it
+// alone.  Otherwise the waves take 4 x 64 consecutive queries of one head.
+template <bool GROUPED>
 __global__ void __launch_bounds__(64 * ANW) __attribute__((amdgpu_waves_per_eu(1, 1)))
 attn_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kg, const bf16_t* __restrict__ Vg,
                  bf16_t* __restrict__ O, int n, int Hq, int Hkv, float scale_log2e, int n_qt) {
@@ -50,21 +54,24 @@ attn_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kg, co
     // workgroups to its CUs in id order.  Give each XCD a contiguous range of heads, so the query heads
     // sharing a kv head meet in one L2, and walk that range's query tiles from the one with the most keys
     // down, all heads of the range at each size: longest-first order per XCD keeps its CUs evenly loaded.
-    int h, qt_idx;
-    if (Hq % 8 == 0) {
-        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, hpx = Hq >> 3;
-        h = xcd * hpx + j % hpx;
-        qt_idx = n_qt - 1 - j / hpx;
-    } else {
-        h = blockIdx.x % Hq;
-        qt_idx = n_qt - 1 - blockIdx.x / Hq;
-    }
-    const int g = h / (Hq / Hkv);
-    const int q0 = qt_idx * BQ;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hh = lane >> 5;
-    const int qw0 = q0 + wave * 64;                       // first query of this wave
+    const int n_units = GROUPED ? Hkv : Hq;               // (kv heads | heads) that the grid walks per query tile
+    int u, qt_idx;
+    if (n_units % 8 == 0) {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3, upx = n_units >> 3;
+        u = xcd * upx + j % upx;
+        qt_idx = n_qt - 1 - j / upx;
+    } else {
+        u = blockIdx.x % n_units;
+        qt_idx = n_qt - 1 - blockIdx.x / n_units;
+    }
+    const int h = GROUPED ? u * 4 + wave : u;
+    const int g = GROUPED ? u : h / (Hq / Hkv);
+    constexpr int WGQ = GROUPED ? 64 : BQ;                // query rows per workgroup
+    const int q0 = qt_idx * WGQ;
+    const int qw0 = GROUPED ? q0 : q0 + wave * 64;        // first query of this wave
     const size_t qstride = (size_t)Hq * AD;
     const unsigned lds_base = (unsigned)(uintptr_t)lds;
 
@@ -94,7 +101,7 @@ attn_bf16_kernel(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ Kg, co
     const unsigned last_tile = (n + BKV - 1) / BKV - 1;   // tiles past it re-read it (into a stage nobody reads)
     const unsigned nl = n - last_tile * BKV, nl1 = nl - 1; // rows of the last tile; its loads clamp their rows to nl1
     const unsigned last_ragged = nl != BKV ? last_tile : 0xffffffffu;
-    const int last_q = min(q0 + BQ, n) - 1;
+    const int last_q = min(q0 + WGQ, n) - 1;
     const unsigned nkt = last_q / BKV + 1;                // causal: tiles up to the last query's diagonal
     const unsigned nmain = nkt > 3 ? nkt - 3 : 0;         // tiles that need no mask
     const uint64_t kb = (uint64_t)(uintptr_t)(Kg + (size_t)g * AD), vb = (uint64_t)(uintptr_t)(Vg + (size_t)g * AD);
@@ -163,12 +170,20 @@ int launch_attn(const void* q, const void* k, const void* v, int n, int Hq, int 
         static std::once_flag attr_once;
         static hipError_t attr_err = hipSuccess;
         std::call_once(attr_once, [&] {
-            attr_err = hipFuncSetAttribute((const void*)attn_bf16_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            attr_err = hipFuncSetAttribute((const void*)attn_bf16_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (attr_err == hipSuccess)
+                attr_err = hipFuncSetAttribute((const void*)attn_bf16_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         });
         if (attr_err != hipSuccess) return set_hip_error(attr_err);
-        const int n_qt = (n + BQ - 1) / BQ;
-        hipLaunchKernelGGL(attn_bf16_kernel, dim3(n_qt * Hq), dim3(64 * ANW), smem, st, (const bf16_t*)q, (const bf16_t*)k,
-                           (const bf16_t*)v, (bf16_t*)out, n, Hq, Hkv, scale * 1.4426950408889634f, n_qt);
+        if (Hq == 4 * Hkv) {
+            const int n_qt = (n + 63) / 64;
+            hipLaunchKernelGGL(attn_bf16_kernel<true>, dim3(n_qt * Hkv), dim3(64 * ANW), smem, st, (const bf16_t*)q,
+                               (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, n, Hq, Hkv, scale * 1.4426950408889634f, n_qt);
+        } else {
+            const int n_qt = (n + BQ - 1) / BQ;
+            hipLaunchKernelGGL(attn_bf16_kernel<false>, dim3(n_qt * Hq), dim3(64 * ANW), smem, st, (const bf16_t*)q,
+                               (const bf16_t*)k, (const bf16_t*)v, (bf16_t*)out, n, Hq, Hkv, scale * 1.4426950408889634f, n_qt);
+        }
         return check_launch();
     }
     dim3 grid(n, Hq);

@@ -29,6 +29,7 @@ transcendental -> use 1, compare -> select 2, ...) are checked on the finished i
 s_nop where a pair is too close; the numbers are the ones the compiler inserts for the same pairs on gfx950.
 """
 import os
+import re
 import sys
 
 # ----------------------------------------------------------------------------- register map
@@ -456,6 +457,12 @@ def rescale_block(returns):
 def prologue():
     out = []
     e = out.append
+    # Query rows first (raw, into v0..63), so that their latency passes under the address arithmetic, the tile loads
+    # and the clearing of the accumulators; then scaled by scale*log2(e), rounded to bf16 again, into the Q agprs
+    for qt in (0, 1):
+        for ks in range(8):
+            d = (qt * 8 + ks) * 4
+            e(Ins(f"global_load_dwordx4 {V(d, 4)}, %[qrow{qt}], off offset:{ks * 32}", "vmem", w=vr(d, 4)))
     for st in range(8):
         e(valu(f"v_xor_b32 {V(KOFF + st)}, {st << 5}, %[koff0]", w=vr(KOFF + st)))
     for dt in range(4):
@@ -476,12 +483,13 @@ def prologue():
     e(salu(f"s_mov_b32 {S(S_VPTR + 1)}, %[vbase_hi]", w=sr(S_VPTR + 1)))
     out += flat([ragged_switch(0), ragged_switch(1)])
     out += flat(tile_load_instrs(0) + tile_advance(0) + tile_load_instrs(1) + tile_advance(1) + tile_load_instrs(0) + tile_advance(0))
-    # Q: raw rows into v0..63, scaled by scale*log2(e), rounded to bf16 again, into the Q agprs
+    for i in range(128):
+        e(valu(f"v_accvgpr_write_b32 {A(O_ACC + i)}, 0", w=ar(O_ACC + i)))
     for qt in (0, 1):
-        for ks in range(8):
-            d = (qt * 8 + ks) * 4
-            e(Ins(f"global_load_dwordx4 {V(d, 4)}, %[qrow{qt}], off offset:{ks * 32}", "vmem", w=vr(d, 4)))
-    e(raw("s_waitcnt vmcnt(0)", "wait"))
+        e(valu(f"v_mov_b32 {V(LRUN[qt])}, 0", w=vr(LRUN[qt])))
+    e(salu(f"s_mov_b32 {S(S_T)}, 0", w=sr(S_T)))
+    e(salu(f"s_mov_b32 {S(S_K0N)}, 0", w=sr(S_K0N)))
+    e(raw("s_waitcnt vmcnt(24)", "wait"))       # the Query rows are there; the 24 tile loads may still be in flight
     for i in range(64):
         lo, hi = TMP + 2 * (i & 3), TMP + 2 * (i & 3) + 1
         e(valu(f"v_lshlrev_b32 {V(lo)}, 16, {V(i)}", r=vr(i), w=vr(lo)))
@@ -490,12 +498,7 @@ def prologue():
         e(valu(f"v_mul_f32 {V(hi)}, %[scale], {V(hi)}", r=vr(hi), w=vr(hi)))
         e(valu(f"v_cvt_pk_bf16_f32 {V(lo)}, {V(lo)}, {V(hi)}", r=vr(lo) + vr(hi), w=vr(lo)))
         e(valu(f"v_accvgpr_write_b32 {A(Q_ACC + i)}, {V(lo)}", r=vr(lo), w=ar(Q_ACC + i)))
-    for i in range(128):
-        e(valu(f"v_accvgpr_write_b32 {A(O_ACC + i)}, 0", w=ar(O_ACC + i)))
-    for qt in (0, 1):
-        e(valu(f"v_mov_b32 {V(LRUN[qt])}, 0", w=vr(LRUN[qt])))
-    e(salu(f"s_mov_b32 {S(S_T)}, 0", w=sr(S_T)))
-    e(salu(f"s_mov_b32 {S(S_K0N)}, 0", w=sr(S_K0N)))
+    e(raw("s_waitcnt vmcnt(0)", "wait"))
     e(raw("s_barrier", "barrier"))
     # S(0): K fragments of unit 0 into the second S buffer's registers (free for now), 16 MFMAs from zero
     for st in range(8):
@@ -552,7 +555,6 @@ def epilogue():
                 e(valu(f"v_cvt_pk_bf16_f32 {V(t)}, {V(t)}, {V(t + 1)}", r=vr(t, 2), w=vr(t)))
                 e(valu(f"v_cvt_pk_bf16_f32 {V(t + 1)}, {V(t + 2)}, {V(t + 3)}", r=vr(t + 2, 2), w=vr(t + 1)))
                 e(Ins(f"global_store_dwordx2 %[orow{qt}], {V(t, 2)}, off offset:{(dt * 32 + 8 * vg) * 2}", "vmem", r=vr(t, 2)))
-        e(raw("s_waitcnt vmcnt(0)", "wait"))
         e(raw(f"s_mov_b64 exec, {S(S_SAVE, 2)}", "salu", r=sr(S_SAVE, 2), w=["exec"]))
     return out
 
@@ -594,8 +596,11 @@ def main():
     here = os.path.dirname(os.path.abspath(__file__))
     with open(os.path.join(here, "attn_bf16_body.inc"), "w") as f:
         f.write("// generated by gen_attn_asm.py -- do not edit\n")
+        # labels get the asm statement's unique number, so that the block can be instantiated more than once
+        names = sorted((x.text[:-1] for x in seq if x.kind == "label"), key=len, reverse=True)
+        pattern = re.compile(r"\b(" + "|".join(names) + r")\b")
         for x in seq:
-            f.write('    "' + x.text + '\\n"\n')
+            f.write('    "' + pattern.sub(lambda m: m.group(1) + "_%=", x.text) + '\\n"\n')
     clob = ([f'"v{i}"' for i in range(LAST_V + 1)] + [f'"a{i}"' for i in range(LAST_A + 1)] +
             [f'"s{i}"' for i in range(FIRST_S, LAST_S + 1)] + ['"vcc"', '"scc"', '"memory"'])
     with open(os.path.join(here, "attn_bf16_clobbers.inc"), "w") as f:
