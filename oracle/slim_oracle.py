@@ -363,13 +363,21 @@ def layer_scores(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
     return block_scores(q_win, k, s.block, s.unit), k
 
 
+def ffn_residual(s: LayerShape, w: LayerWeights, y: np.ndarray, rounding=None) -> np.ndarray:
+    """The "FFN" stage of Fig. 2 with its residual: z = y + Wd (silu(Wg r) * (Wu r)), r = RMSNorm(y)."""
+    r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
+    act = _rnd(silu(linear(r, w.w_gate)) * linear(r, w.w_up), rounding)
+    return _rnd(y + linear(act, w.w_down), rounding)
+
+
 def layer_after_selection(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
-                          kept_blocks: np.ndarray, rows: np.ndarray | None = None, rounding=None):
+                          kept_blocks: np.ndarray, rows: np.ndarray | None = None, rounding=None, want_y: bool = False):
     """Everything after the block set is known: compact, QKV for the kept tokens (RoPE with the
     original positions), causal GQA attention over the compacted sequence, output projection
     + residual, SwiGLU FFN + residual.  `rows` (indices into the compacted sequence) limits the
     output to a sample of rows; attention for a sampled row still sees every kept key before it.
-    Returns (z[rows or n', hidden], pos'[n'])."""
+    Returns (z[rows or n', hidden], pos'[n']), and with want_y also y, the residual stream between the
+    attention branch and the FFN (an intermediate of the same computation, handed out unchanged)."""
     xk, posk = compact_tokens(x, pos, kept_blocks, s.block)
     n = xk.shape[0]
     h = _rnd(rmsnorm(xk, w.g_attn, s.rms_eps), rounding)
@@ -380,14 +388,13 @@ def layer_after_selection(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np
     q = project_heads(h[rows], w.wq, s.n_q_heads, s.head_dim, posk[rows], s.rope_theta, True, rounding, w.bq)
     o = _rnd(causal_gqa_attention(q, k, v, rows=rows, rounding=rounding), rounding)
     y = _rnd(xk[rows] + linear(o.reshape(len(rows), -1), w.wo), rounding)
-    r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
-    act = _rnd(silu(linear(r, w.w_gate)) * linear(r, w.w_up), rounding)
-    z = _rnd(y + linear(act, w.w_down), rounding)
-    return z, posk
+    z = ffn_residual(s, w, y, rounding)
+    return (z, posk, y) if want_y else (z, posk)
 
 
 def layer_after_selection_literal(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray,
-                                  kept_blocks: np.ndarray, rows: np.ndarray | None = None, rounding=None):
+                                  kept_blocks: np.ndarray, rows: np.ndarray | None = None, rounding=None,
+                                  want_y: bool = False):
     """The placement Section 4.1 describes: the block decision is taken right after Attention, so the
     pruning layer's own attention still sees every incoming token, and the hidden states of the pruned
     blocks are dropped for everything that follows (this layer's output projection and FFN included).
@@ -402,10 +409,8 @@ def layer_after_selection_literal(s: LayerShape, w: LayerWeights, x: np.ndarray,
     q = project_heads(h[Tr], w.wq, s.n_q_heads, s.head_dim, pos[Tr], s.rope_theta, True, rounding, w.bq)
     o = _rnd(causal_gqa_attention(q, k, v, rows=Tr, rounding=rounding), rounding)
     y = _rnd(x[Tr] + linear(o.reshape(len(Tr), -1), w.wo), rounding)
-    r = _rnd(rmsnorm(y, w.g_ffn, s.rms_eps), rounding)
-    act = _rnd(silu(linear(r, w.w_gate)) * linear(r, w.w_up), rounding)
-    z = _rnd(y + linear(act, w.w_down), rounding)
-    return z, pos[T]
+    z = ffn_residual(s, w, y, rounding)
+    return (z, pos[T], y) if want_y else (z, pos[T])
 
 
 def pruned_layer(s: LayerShape, w: LayerWeights, x: np.ndarray, pos: np.ndarray, n_keep: int,

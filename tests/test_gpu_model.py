@@ -11,7 +11,8 @@ import torch
 
 from oracle import slim_oracle as so
 from paper_2508_06447_amd import inputs
-from tests.helpers import MAX_ABS, MEAN_ABS, assert_selection_matches, bf16_floor, errs, f64, oracle_shape, oracle_weights
+from tests.helpers import (assert_residual_close, assert_selection_matches, f64, ffn_response_sigma, oracle_shape,
+                           oracle_weights, score_tolerance)
 from tests.test_gpu_layer import sample_rows
 
 pytestmark = pytest.mark.gpu
@@ -44,7 +45,10 @@ def run_loop(slim, shape, weights_gpu, x, pos, keeps, capture):
     return x, pos, saved
 
 
-def check_layer_local(label, wl, w_cpu, x_in, pos_in, keep, res, np_dtype, rows_count):
+def check_layer_local(slim, shape, label, wl, w_cpu, w_gpu, x_in, pos_in, keep, res, np_dtype, rows_count):
+    """One layer of the schedule against the oracle's layer on the GPU's own input (teacher-forced): scores at the
+    stated 2e-3, or, where a block's products are large, at the tolerance that follows their size; kept set outside
+    the 1e-3 band; positions; y (the layer rerun with a zero down projection) and z element by element."""
     s, ow = oracle_shape(wl), oracle_weights(w_cpu, np_dtype)
     xs = x_in.cpu().to(torch.float32).numpy().astype(np_dtype)
     ps = pos_in.cpu().numpy()
@@ -52,22 +56,32 @@ def check_layer_local(label, wl, w_cpu, x_in, pos_in, keep, res, np_dtype, rows_
     nb = so.n_blocks(N, wl.block)
     if keep < nb:
         sc_ref, _ = so.layer_scores(s, ow, xs, ps)
-        sc_err = float(np.abs(f64(res["scores"]) - sc_ref).max())
+        sc_d = np.abs(f64(res["scores"]) - sc_ref)
+        sc_err = float(sc_d.max())
         kept = res["kept"].cpu().numpy()
         _, band, ndiff = assert_selection_matches(kept, sc_ref.astype(np.float64), keep)
-        assert sc_err < 5e-3
+        if sc_err >= 2e-3:                                   # deep layers: larger hidden states, larger products
+            assert (sc_d <= score_tolerance(s, ow, xs, ps)).all(), f"{label}: scores off by {sc_err:.2e}"
     else:
         kept, sc_err, band, ndiff = np.arange(nb, dtype=np.int32), 0.0, 0, 0
     T = so.kept_token_index(kept, wl.block, N)
     np.testing.assert_array_equal(res["pos"].cpu().numpy(), ps[T])
     rows = None if rows_count is None else sample_rows(len(T), wl.block, rows_count)
-    z_ref, fl_max, fl_mean = bf16_floor(s, ow, xs, ps, kept, rows=rows)
-    got = res["x"] if rows is None else res["x"][torch.from_numpy(rows).cuda()]
-    mx, mean = errs(got, z_ref.astype(np.float64))
-    print(f"{label}: N={N} keep {keep}/{nb}; scores max-abs {sc_err:.2e}, {band} in band, {ndiff} differ; "
-          f"z max-abs {mx:.3e} mean-abs {mean:.3e} (bf16-rounding oracle {fl_max:.3e}/{fl_mean:.3e}); "
-          f"|z| max {np.abs(z_ref).max():.1f}", flush=True)
-    assert mx <= max(MAX_ABS, 1.5 * fl_max) and mean <= max(MEAN_ABS, 1.5 * fl_mean)
+    z_ref, _, y_ref = so.layer_after_selection(s, ow, xs, ps, kept, rows=rows, want_y=True)
+    z_ref, y_ref = z_ref.astype(np.float64), y_ref.astype(np.float64)
+    pick = (lambda t: t) if rows is None else (lambda t: t[torch.from_numpy(rows).cuda()])
+    w0 = dict(w_gpu, w_down=torch.zeros_like(w_gpu["w_down"]))
+    y_gpu = pick(slim.slim_pruned_layer(shape, w0, x_in, pos_in, keep)["x"])
+    ymx, ymean = assert_residual_close(y_gpu, y_ref, [y_ref], f"{label} y")
+    stored_r = 1 if "g_ffn" in w_gpu else 0              # with gain vectors the normalised row is stored as well
+    z_tf = so.ffn_residual(s, ow, f64(y_gpu).astype(np_dtype)).astype(np.float64)
+    assert_residual_close(pick(res["x"]), z_tf, [z_tf], f"{label} z from the GPU's y",
+                          ffn_sigma=ffn_response_sigma(f64(y_gpu), z_tf, None, stored_r) if stored_r else None)
+    sig = ffn_response_sigma(y_ref, z_ref, f64(y_gpu) - y_ref, stored_r)
+    mx, mean = assert_residual_close(pick(res["x"]), z_ref, [z_ref, y_ref], f"{label} z", ffn_sigma=sig)
+    print(f"{label}: N={N} keep {keep}/{nb}, {z_ref.shape[0]} rows; scores max-abs {sc_err:.2e}, {band} in band, {ndiff} differ; "
+          f"y max-abs {ymx:.3e} mean-abs {ymean:.3e}; z max-abs {mx:.3e} mean-abs {mean:.3e}; |z| max {np.abs(z_ref).max():.1f}",
+          flush=True)
 
 
 def to_gpu(w, fold):
@@ -94,15 +108,17 @@ def test_small_schedule_every_layer(slim, fold):
     assert out["x"].shape[0] == 4 * 64 + 37 and int(out["pos"][-1]) == wl.seq - 1 and int(out["pos"][0]) == 0
     for l in range(5):
         xi, pi, keep, res = saved[l]
-        check_layer_local(f"small model layer {l}", wl, w_cpu[l], xi, pi, keep, res, np.float64, None)
+        check_layer_local(slim, shape, f"small model layer {l}", wl, w_cpu[l], w_gpu[l], xi, pi, keep, res, np.float64, None)
     # NULL positions on entry mean 0..N-1
     out2 = slim.slim_prefill_model(shape, w_gpu, x, None, keeps)
     assert torch.equal(out2["x"], out["x"]) and torch.equal(out2["pos"], out["pos"])
 
 
 def test_cfg5_full_schedule_layer_local(slim):
+    """The 32-layer schedule at full size: the three pruning layers on ALL of their output rows, eleven more layers
+    spread over the depth on sampled rows; every one teacher-forced on the GPU's own input to that layer."""
     wl = inputs.WORKLOADS["cfg5"]
-    check = {0: 24, 8: 32, 16: 32, 24: None, 31: None}      # layer -> sampled rows (None = all rows)
+    check = {0: 32, 3: 32, 6: 32, 8: None, 9: 32, 12: 32, 15: 32, 16: None, 17: 32, 20: 32, 23: 32, 24: None, 27: 32, 31: None}
     x, pos = inputs.hidden_states(wl).cuda(), inputs.positions(wl).cuda()
     w_gpu, w_cpu = [], {}
     for l, w in inputs.model_weights(wl, workers=16):
@@ -120,7 +136,40 @@ def test_cfg5_full_schedule_layer_local(slim):
     assert torch.equal(out["x"], xl) and torch.equal(out["pos"], pl)
     p = out["pos"].cpu().numpy()
     assert p[0] == 0 and p[-1] == wl.seq - 1 and (np.diff(p) > 0).all() and (p.reshape(8, 64)[:, 0] % 64 == 0).all()
-    del w_gpu
     for l, rows in check.items():
         xi, pi, keep, res = saved[l]
-        check_layer_local(f"cfg5 layer {l}", wl, w_cpu[l], xi, pi, keep, res, np.float32, rows)
+        check_layer_local(slim, shape, f"cfg5 layer {l}", wl, w_cpu[l], w_gpu[l], xi, pi, keep, res, np.float32, rows)
+
+
+def test_free_running_schedule_report(slim):
+    """Information, plus loose sanity gates: a 16-layer LLaMA-shaped prefill of 4096 tokens that prunes at layers
+    4, 8 and 12, against the oracle running freely from the same input (its own hidden states, its own kept sets).
+    After several bf16 layers the two residual streams differ by about a percent, so kept sets may part inside the
+    score band and the outputs are compared where both kept the token."""
+    wl = inputs.scaled(inputs.WORKLOADS["cfg5"], seq=4096, n_layers=16, schedule={4: 0.5, 8: 0.5, 12: 0.5})
+    x, pos = inputs.hidden_states(wl), inputs.positions(wl)
+    w_cpu = [w for _, w in inputs.model_weights(wl, workers=16)]
+    shape = make_shape(slim, wl, x.dtype)
+    keeps = slim.schedule_keep_counts(wl.seq, wl.block, wl.n_layers, wl.schedule)
+    out = slim.slim_prefill_model(shape, [to_gpu(w, True) for w in w_cpu], x.cuda(), pos.cuda(), keeps)
+    torch.cuda.synchronize()
+    print("GPU done; oracle running freely", flush=True)
+    s = oracle_shape(wl)
+    xo, po, kept_log = so.prefill_model(s, lambda l: oracle_weights(w_cpu[l], np.float32), wl.n_layers,
+                                        x.to(torch.float32).numpy(), pos.numpy(), wl.schedule)
+    kept_gpu = out["kept"].cpu().numpy()
+    ofs = 0
+    for l in sorted(wl.schedule):
+        kept_ref = kept_log[l]
+        mine = set(kept_gpu[ofs:ofs + len(kept_ref)].tolist())
+        ofs += len(kept_ref)
+        jac = len(mine & set(kept_ref.tolist())) / len(mine | set(kept_ref.tolist()))
+        print(f"free-running: layer {l} keeps {len(kept_ref)} blocks, Jaccard of the kept sets {jac:.3f}", flush=True)
+        assert jac >= 0.5
+    pg = out["pos"].cpu().numpy()
+    both, ig, io = np.intersect1d(pg, po, return_indices=True)
+    zg, zo = f64(out["x"])[ig], xo[io].astype(np.float64)
+    rel = float(np.sqrt(np.mean((zg - zo) ** 2)) / np.sqrt(np.mean(zo ** 2)))
+    print(f"free-running: {len(both)} of {len(pg)} final tokens kept by both; final residual stream differs by {rel:.3e} of "
+          f"its rms (max-abs {np.abs(zg - zo).max():.3e}, |z| max {np.abs(zo).max():.1f})", flush=True)
+    assert len(both) >= len(pg) // 2 and rel < 0.1

@@ -422,6 +422,30 @@ def test_attention_matches_oracle(slim, n, Hq, Hkv, d, dtype):
     assert mx2 <= (MAX_ABS if dtype == torch.bfloat16 else 2e-5)
 
 
+@pytest.mark.parametrize("n,q_scale", [(9856, 1.0), (26240, 1.0), (16384, 1.0), (9856, 2.5)])
+def test_attention_full_size_sampled_rows(slim, n, q_scale):
+    """slim_prefill_attn alone at the kept-token counts of the 32K, 131K and 32-layer workloads (32 query / 8 kv heads
+    of 128), in the launch configuration the layer uses, on sampled rows that the oracle evaluates one by one: the
+    first and last rows, rows on both sides of every boundary the kernel has (32-key unit, 64-query wave, 128-key
+    tile, 256), rows of the last, short tile, and random ones.  q_scale 2.5: logits of +-15 and more, so that the
+    softmax is carried by a few keys and the reference of the online softmax moves."""
+    Hq, Hkv, d = 32, 8, 128
+    print(f"attn full size n={n} H={Hq}/{Hkv} d={d} q x {q_scale}", flush=True)
+    q, k, v = inputs.stage_qkv(n, Hq, Hkv, d, "bf16", seed=n % 1000 + int(10 * q_scale))
+    if q_scale != 1.0:
+        q = (q.float() * q_scale).to(torch.bfloat16)
+    g = np.random.default_rng(n)
+    edges = [0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, n // 2 - 1, n // 2, (n // 128) * 128 - 1,
+             (n // 128) * 128, (n // 256) * 256 - 1, (n // 256) * 256, n - 65, n - 64, n - 33, n - 32, n - 2, n - 1]
+    rows = np.array(sorted(set(r for r in edges if 0 <= r < n) | set(g.integers(0, n, 44).tolist())))
+    assert len(rows) >= 64
+    got = slim.slim_prefill_attn(dev(q), dev(k), dev(v))[torch.from_numpy(rows).cuda()]
+    want = so.causal_gqa_attention(f64(q)[rows], f64(k), f64(v), rows=rows)
+    mx, mean = errs(got, want)
+    print(f"   {len(rows)} rows: max-abs {mx:.3e} mean-abs {mean:.3e}", flush=True)
+    assert np.isfinite(f64(got)).all() and mx <= MAX_ABS and mean <= MEAN_ABS
+
+
 def test_attention_peaked_logits_and_first_row(slim):
     n, Hq, Hkv, d = 300, 4, 2, 128
     q, k, v = inputs.stage_qkv(n, Hq, Hkv, d, "bf16", seed=9)

@@ -499,6 +499,30 @@ def test_keep_ratio_one_is_exactly_the_unpruned_layer():
     np.testing.assert_allclose(a["z"], torch_layer_unpruned(s, w, x, pos), rtol=1e-9, atol=1e-11)
 
 
+def test_the_intermediate_y_is_the_layer_with_a_zero_down_projection():
+    """want_y hands out the residual stream between the two branches: it is what the layer returns when the FFN
+    branch contributes nothing, in both placements and on sampled rows, and z is untouched by the request."""
+    import dataclasses
+    s, w, x, pos = small_layer(seed=21, n=45)
+    kept = np.array([0, 2, 5], dtype=np.int32)
+    w0 = dataclasses.replace(w, w_down=np.zeros_like(w.w_down))
+    for fn in (so.layer_after_selection, so.layer_after_selection_literal):
+        for rows in (None, np.array([0, 3, 9, 12])):
+            z, p, y = fn(s, w, x, pos, kept, rows=rows, want_y=True)
+            np.testing.assert_array_equal(z, fn(s, w, x, pos, kept, rows=rows)[0])
+            np.testing.assert_array_equal(y, fn(s, w0, x, pos, kept, rows=rows)[0])
+            assert np.abs(z - y).max() > 1e-3
+
+
+def test_bf16_spacing_used_by_the_gpu_tolerances():
+    from tests.helpers import ulp_bf16
+    a = np.concatenate([rng.standard_normal(2000) * 10.0 ** rng.integers(-4, 4, 2000), [1.0, 2.0, 0.5, 7.999, 8.0, 15.99]])
+    t = torch.from_numpy(np.abs(a)).to(torch.float32).to(torch.bfloat16)          # a bf16 value in the same binade or the next
+    up = torch.nextafter(t, torch.tensor(float("inf"), dtype=torch.bfloat16))
+    np.testing.assert_array_equal(ulp_bf16(t.double().numpy()), (up.double() - t.double()).numpy())
+    assert ulp_bf16(np.array([8.0]))[0] == 0.0625 and ulp_bf16(np.array([-7.99]))[0] == 0.03125
+
+
 def test_pruned_layer_uses_original_positions_and_kept_tokens_only():
     s, w, x, pos = small_layer(seed=5, n=64)
     res = so.pruned_layer(s, w, x, pos, n_keep=4)
