@@ -3,13 +3,20 @@
  *
  * C ABI.  Conventions shared by every entry point:
  *   - Every data pointer is a DEVICE pointer owned by the caller, unless marked "host".
- *     The library never allocates, frees or keeps a pointer after the call returns.
+ *     The library never allocates, frees or keeps a pointer after the call returns.  What it keeps between
+ *     calls is derived, immutable once computed and guarded for concurrent callers: device properties, the
+ *     one-time raising of kernels' LDS limits, a memo of tile-schedule choices per problem shape, and the
+ *     per-device address of the scratch array of slim_score_blocks_static.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only enqueues
  *     kernels on that stream; it never synchronises with the host.
  *   - `dtype`: SLIM_F32 (0) = IEEE binary32, SLIM_BF16 (1) = bfloat16.  It is the type of every
  *     activation and weight tensor of the call.  Block scores are always float; indices are int32.
  *   - Tensors are dense row-major; "x[n, H, d]" means d is contiguous.
- *   - Return value: SLIM_OK (0) or a negative error code.  On error nothing has been enqueued.
+ *   - Return value: SLIM_OK (0) or a negative error code.  Argument errors (INVALID_ARG, UNSUPPORTED,
+ *     WORKSPACE_TOO_SMALL) are found before the first launch: nothing has been enqueued.  SLIM_HIP_ERROR means
+ *     the runtime refused a launch; a call that enqueues several kernels (the layer, the model, the decode
+ *     layer, the two-kernel stage calls) may then already have enqueued the earlier ones, and its outputs
+ *     and workspace are undefined.
  *   - Calls on different streams may overlap as long as their buffers (workspace included) are
  *     distinct.
  *
@@ -385,7 +392,8 @@ int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, siz
  *   slim_gemv: the single-token projection, out[n] = s * (w[n, :] . x) + bias[n] + residual[n] (NULL = absent), or
  *              with w_up: silu(s * w . x) * (s * w_up . x);  s = *scale (device float, e.g. the token's 1/rms from
  *              slim_row_rstd for a folded gain) or 1 when scale is NULL.  Every weight is read once.  out may alias
- *              residual.  k_in % 8 == 0 (bf16) / % 4 (fp32), k_in <= 16384, 16-byte aligned w, w_up, x.
+ *              residual.  k_in % 8 == 0 (bf16) / % 4 (fp32), k_in <= 16376 (the token is staged in 64 KiB of LDS as floats,
+ *              beside 16 bytes of partial sums; UNSUPPORTED beyond), 16-byte aligned w, w_up, x.
  *   slim_decode_layer:
  *     x_new [hidden], position = the token's position (for RoPE), x_out [hidden] (may not alias x_new)
  *     gpu_pool / slot_bytes / layer_offset / block_of_slot / n_slots / n_prompt_tokens: as slim_decode_attn
@@ -394,7 +402,7 @@ int slim_decode_attn(const void* q, const void* gpu_pool, size_t slot_bytes, siz
  *     q_out [Hq, 128] or NULL: the token's Query states (post-RoPE), e.g. for the scoring window of the next steps
  *     workspace >= slim_decode_layer_workspace_bytes(...), 256-byte aligned
  *   Weights as slim_pruned_layer (NULL gains = folded).  head_dim 128, at most 8 query heads per kv head, hidden,
- *   ffn, Hq*128 <= 16384.  6 launches with folded gains (8 otherwise), no host synchronisation.  Errors as the stage
+ *   ffn, Hq*128 <= 16376.  6 launches with folded gains (8 otherwise), no host synchronisation.  Errors as the stage
  *   calls.
  */
 int slim_gemv(const void* w, const void* w_up, const void* x, const float* scale, const void* bias,
@@ -404,20 +412,6 @@ int slim_decode_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
                       const void* gpu_pool, size_t slot_bytes, size_t layer_offset, const int* block_of_slot,
                       int n_slots, int n_prompt_tokens, void* k_response, void* v_response, int n_response,
                       void* x_out, void* q_out, void* workspace, size_t workspace_bytes, void* stream);
-
-/* ------------------------------------------------------------------------------------------------
- * Measurement probes (no counterpart in the paper): measured ceilings to set beside the nameplate
- * rooflines.  slim_probe_mfma runs a register-only loop of v_mfma_f32_32x32x16_bf16 (n_workgroups
- * workgroups of 8 waves, `iters` rounds of 8 independent MFMAs per wave) and slim_probe_mfma_flops
- * returns the flop count of such a launch; `sink` is a device float that is never written.
- * random_operands = 0: constant small-integer operands; != 0: pseudo-random operands in [-1, 1) that
- * change from one MFMA to the next, as real activations and weights do (the chip clocks lower then).
- * slim_probe_copy copies `bytes` (multiple of 16, 16-byte aligned pointers) device to device with
- * 16-byte accesses.  Both only enqueue work.  Errors: INVALID_ARG, UNSUPPORTED (alignment).
- */
-double slim_probe_mfma_flops(int n_workgroups, int iters);
-int slim_probe_mfma(int n_workgroups, int iters, int random_operands, float* sink, void* stream);
-int slim_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -2,7 +2,7 @@
 thin ctypes binding with the same entry-point names."""
 from .binding import (  # noqa: F401
     BF16, F32, FORCE_FIRST, FORCE_LAST, POOL_AVG, POOL_MAX, PRUNE_BEFORE_ATTENTION,
-    PRUNE_AFTER_ATTENTION, LIB_PATH, EXPORTS, LayerShape, LayerWeights, SlimError, kept_tokens,
+    PRUNE_AFTER_ATTENTION, LIB_PATH, PROBE_LIB_PATH, EXPORTS, PROBE_EXPORTS, load_probe_library, LayerShape, LayerWeights, SlimError, kept_tokens,
     load_library, make_shape, make_weights, n_blocks, pruned_layer_workspace_bytes, slim_compact_tokens,
     slim_linear, slim_linear_bias, slim_prefill_attn, slim_pruned_layer, slim_rmsnorm, slim_rope, slim_score_blocks,
     slim_score_blocks_static,

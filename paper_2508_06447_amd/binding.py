@@ -14,6 +14,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libslim.so")
+PROBE_LIB_PATH = os.path.join(_HERE, "libslim_probe.so")
 
 F32, BF16 = 0, 1
 POOL_AVG, POOL_MAX = 1, 2
@@ -32,8 +33,8 @@ EXPORTS = (
     "slim_select_topk_blocks", "slim_compact_tokens", "slim_prefill_attn", "slim_rmsnorm", "slim_rope",
     "slim_linear", "slim_linear_bias", "slim_swiglu_linear", "slim_kept_tokens", "slim_pruned_layer_workspace_bytes",
     "slim_pruned_layer", "slim_prefill_model_tokens", "slim_prefill_model_workspace_bytes", "slim_prefill_model",
-    "slim_probe_mfma_flops", "slim_probe_mfma", "slim_probe_copy",
 )
+PROBE_EXPORTS = ("slim_probe_mfma_flops", "slim_probe_mfma", "slim_probe_copy")   # libslim_probe.so, include/slim_probe.h
 
 
 class SlimError(RuntimeError):
@@ -121,10 +122,6 @@ def load_library(path: str | None = None) -> C.CDLL:
     lib.slim_prefill_model_workspace_bytes.argtypes = [C.POINTER(LayerShape), i, ip, i]
     lib.slim_prefill_model.argtypes = [C.POINTER(LayerShape), C.POINTER(LayerWeights), i, ip, vp, vp, i, vp, vp, vp,
                                        vp, sz, vp]
-    lib.slim_probe_mfma_flops.restype = C.c_double
-    lib.slim_probe_mfma_flops.argtypes = [i, i]
-    lib.slim_probe_mfma.argtypes = [i, i, i, vp, vp]
-    lib.slim_probe_copy.argtypes = [vp, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name)                      # every declared symbol must resolve
     if path is None:
@@ -654,9 +651,27 @@ def slim_prefill_model(shape: LayerShape, layer_weights: list, x: torch.Tensor, 
     return out
 
 
+_probe_lib = None
+
+
+def load_probe_library() -> C.CDLL:
+    """Load libslim_probe.so: the measurement probes of bench.py, kept out of the method's library."""
+    global _probe_lib
+    if _probe_lib is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            raise FileNotFoundError(f"{PROBE_LIB_PATH} not found: build it with __graft_entry__.build()")
+        lib = C.CDLL(PROBE_LIB_PATH)
+        lib.slim_probe_mfma_flops.restype = C.c_double
+        lib.slim_probe_mfma_flops.argtypes = [C.c_int, C.c_int]
+        lib.slim_probe_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        lib.slim_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        _probe_lib = lib
+    return _probe_lib
+
+
 def probe_mfma(n_workgroups: int, iters: int, sink: torch.Tensor, random_operands: bool = False) -> float:
     """Enqueue the register-only MFMA loop; returns its flop count."""
-    lib = load_library()
+    lib = load_probe_library()
     _check(lib.slim_probe_mfma(n_workgroups, iters, int(random_operands), _dev(sink, "sink"), _stream()),
            "slim_probe_mfma")
     return lib.slim_probe_mfma_flops(n_workgroups, iters)
@@ -665,5 +680,5 @@ def probe_mfma(n_workgroups: int, iters: int, sink: torch.Tensor, random_operand
 def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> int:
     """Enqueue a plain device copy of src into dst; returns the bytes copied."""
     nbytes = src.numel() * src.element_size()
-    _check(load_library().slim_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "slim_probe_copy")
+    _check(load_probe_library().slim_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "slim_probe_copy")
     return nbytes

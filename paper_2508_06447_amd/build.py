@@ -1,4 +1,5 @@
-"""Builds libslim.so in-tree with hipcc for gfx950 (cross-compiles without a GPU)."""
+"""Builds libslim.so (the method) and libslim_probe.so (bench.py's measurement probes) in-tree with hipcc for
+gfx950 (cross-compiles without a GPU)."""
 from __future__ import annotations
 
 import os
@@ -9,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslim.so")
+PROBE_LIB = os.path.join(HERE, "libslim_probe.so")
 SOURCES = ("api.hip", "prune.hip", "norm_rope.hip", "gemm.hip", "attn.hip", "kvswap.hip", "decode.hip", "gemv.hip", "window.hip", "probe.hip")
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
@@ -32,10 +34,12 @@ def build_lib(verbose: bool = True, extra_flags=()) -> str:
             print(out)
         if p.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+    probe = [o for o in objs if os.path.basename(o) == "probe.o"]
+    for lib, members in ((LIB, [o for o in objs if o not in probe]), (PROBE_LIB, probe)):
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *members]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return LIB
 
 

@@ -225,7 +225,7 @@ int slim_gemv(const void* w, const void* w_up, const void* x, const float* scale
               int n_out, int k_in, int dtype, void* out, void* stream) {
     if (!w || !x || !out || n_out < 1 || k_in < 1) return SLIM_INVALID_ARG;
     if (!dtype_ok(dtype)) return SLIM_UNSUPPORTED;
-    if (k_in % (dtype == SLIM_BF16 ? 8 : 4) != 0 || k_in > 16384 || !aligned16(w) || !aligned16(x) || (w_up && !aligned16(w_up)))
+    if (k_in % (dtype == SLIM_BF16 ? 8 : 4) != 0 || k_in > 16376 || !aligned16(w) || !aligned16(x) || (w_up && !aligned16(w_up)))
         return SLIM_UNSUPPORTED;
     return launch_gemv(w, w_up, x, scale, -1.f, bias, residual, n_out, k_in, dtype, out, (hipStream_t)stream);
 }
@@ -265,7 +265,7 @@ int slim_decode_layer(const slim_layer_shape* s, const slim_layer_weights* w, co
     const int dt = s->dtype, Hd = s->hidden, Hq = s->n_q_heads, Hkv = s->n_kv_heads, d = s->head_dim;
     const int qd = Hq * d, kvd = Hkv * d, vec = dt == SLIM_BF16 ? 8 : 4;
     const size_t es = elem_size(dt);
-    if (d != 128 || Hq / Hkv > 8 || Hd % vec != 0 || s->ffn % vec != 0 || Hd > 16384 || s->ffn > 16384 || qd > 16384 ||
+    if (d != 128 || Hq / Hkv > 8 || Hd % vec != 0 || s->ffn % vec != 0 || Hd > 16376 || s->ffn > 16376 || qd > 16376 ||
         !aligned16(x_new) || !aligned16(x_out) || !aligned16(k_response) || !aligned16(v_response) ||
         ((uintptr_t)workspace & 255u) || slot_bytes % 16 != 0 || layer_offset % 16 != 0 || (n_slots > 0 && !aligned16(gpu_pool)) ||
         (q_out && !aligned16(q_out)))

@@ -580,12 +580,10 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
     const void* kern;
     if constexpr (GENERIC) kern = (const void*)gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>;
     else kern = (const void*)gemm_bf16_kernel<TW, TA, WGN, WGM, EPI>;
-    static bool attr_done = false;                       // raising the LDS limit is per function, once
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return set_hip_error(e);
-        attr_done = true;
-    }
+    static std::once_flag attr_once;                     // raising the LDS limit is per function, once
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&] { attr_err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); });
+    if (attr_err != hipSuccess) return set_hip_error(attr_err);
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     if constexpr (GENERIC)
         hipLaunchKernelGGL((gemm_bf16_generic_kernel<TW, TA, WGN, WGM, EPI>), dim3(tiles_m * tiles_n), dim3(64 * WGN * WGM),
@@ -606,6 +604,7 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
 //   straddles columns of the band walk and shares fewer operand panels in that XCD's L2);
 //   +5 % for fewer than 4 token-tiles of small tiles (too few rows to share a weight panel between the
 //   workgroups that run together).
+// The result is a pure function of its arguments; the cache only remembers it (guarded, never invalidated).
 static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
     static std::mutex mu;
     static std::map<std::tuple<int, int, int>, int> cache;
@@ -652,12 +651,12 @@ static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf1
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
     auto kern = gemm_bf16_two_size_kernel<EPI>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return set_hip_error(e);
-        attr_done = true;
-    }
+    static std::once_flag attr_once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(attr_once, [&] {
+        attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    });
+    if (attr_err != hipSuccess) return set_hip_error(attr_err);
     const int tiles_n = (N + S::BN - 1) / S::BN + (re.w_2 ? (re.n_2 + S::BN - 1) / S::BN : 0);
     const int small_tiles_m = (M - big_tiles_m * S::BM_BIG + S::BM_SMALL - 1) / S::BM_SMALL;
     hipLaunchKernelGGL(kern, dim3((big_tiles_m + small_tiles_m) * tiles_n), dim3(512), smem, st, A, lda, W0, W1, R, C,
@@ -666,14 +665,14 @@ static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf1
 }
 
 static int cu_count() {
-    static int n = 0;
-    if (n == 0) {
+    static std::once_flag once;                          // immutable once read: a property of the device
+    static int n = 256;
+    std::call_once(once, [] {
         int dev = 0;
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0)
             n = prop.multiProcessorCount;
-        if (n <= 0) n = 256;
-    }
+    });
     return n;
 }
 

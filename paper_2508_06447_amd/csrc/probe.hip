@@ -2,6 +2,7 @@
 // the same run: a register-only MFMA loop (what the matrix pipes sustain at the clocks the chip holds
 // under that load, with constant or with changing operand bits) and a plain 16-byte-per-lane copy (what HBM sustains for a read+write stream).
 #include "slim_common.h"
+#include "slim_probe.h"
 
 namespace slim {
 
@@ -72,7 +73,7 @@ int slim_probe_mfma(int n_workgroups, int iters, int random_operands, float* sin
         hipLaunchKernelGGL(mfma_loop_kernel<true>, dim3(n_workgroups), dim3(64 * kProbeWaves), 0, (hipStream_t)stream, iters, sink);
     else
         hipLaunchKernelGGL(mfma_loop_kernel<false>, dim3(n_workgroups), dim3(64 * kProbeWaves), 0, (hipStream_t)stream, iters, sink);
-    return check_launch();
+    return hipGetLastError() == hipSuccess ? SLIM_OK : SLIM_HIP_ERROR;
 }
 
 int slim_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
@@ -81,7 +82,7 @@ int slim_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
     const size_t n_vec = bytes / 16;
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n_vec + 1023) / 1024)), dim3(256), 0, (hipStream_t)stream,
                        (const u32x4*)src, (u32x4*)dst, n_vec);
-    return check_launch();
+    return hipGetLastError() == hipSuccess ? SLIM_OK : SLIM_HIP_ERROR;
 }
 
 }  // extern "C"

@@ -52,7 +52,6 @@ def test_layer_workspace_grows_with_tokens_and_is_aligned(lib):
     a = slim.pruned_layer_workspace_bytes(shape, 8192, 64)
     b = slim.pruned_layer_workspace_bytes(shape, 32768, 154)
     assert 0 < a < b and a % 256 == 0 and b % 256 == 0
-    assert lib.slim_probe_mfma_flops(2, 3) == 2 * 8 * 3 * 8 * 2.0 * 32 * 32 * 16
 
 
 def test_generators_are_seeded_and_per_matrix():

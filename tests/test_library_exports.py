@@ -17,8 +17,8 @@ def lib():
     return slim.load_library()
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "slim.h")).read()
+def declared_symbols(header="slim.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(slim_[a-z_0-9]+)\s*\(", text)))
 
@@ -29,6 +29,21 @@ def test_every_declared_symbol_is_exported(lib):
     assert len(names) >= 14 and set(names) == set(slim.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
+
+
+def test_the_probes_live_in_a_library_and_header_of_their_own(lib):
+    """The method's ABI (slim.h, libslim.so) holds no measurement helper; bench.py's probes are declared in
+    slim_probe.h and exported by libslim_probe.so only."""
+    import paper_2508_06447_amd as slim
+    assert not [n for n in declared_symbols() if "probe" in n]
+    names = declared_symbols("slim_probe.h")
+    assert set(names) == set(slim.PROBE_EXPORTS) and len(names) == 3
+    plib = slim.load_probe_library()
+    for n in names:
+        assert getattr(plib, n) is not None
+        assert not hasattr(lib, n)
+    assert plib.slim_probe_mfma_flops(2, 3) == 2 * 8 * 3 * 8 * 2.0 * 32 * 32 * 16
+    assert plib.slim_probe_copy(None, None, 16, None) == -1
 
 
 def test_status_strings_and_host_only_helpers(lib):
