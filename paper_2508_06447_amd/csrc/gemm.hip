@@ -8,11 +8,14 @@
 // and the activation tile the "B" operand, so a lane ends up with 4 consecutive output features of
 // one token and stores them as one 8-byte vector.
 //
-// Main kernel (k_in a multiple of 64): 8 waves per workgroup, two waves per SIMD, 256x256 output tile
-// (128 features x 2 matrices x 256 tokens for SwiGLU).  Operand tiles go from global memory straight
-// into LDS (global_load_lds_dwordx4, no VGPR staging), double-buffered; MFMA fragments are read one
-// k-step ahead of their use, across k-tiles too.  A register-staged kernel with k predicates covers
-// ragged k_in.
+// Main path (k_in a multiple of 64, more than 128 rows): 4 waves per workgroup, one per SIMD, 256x256 output tile
+// (128 features x 2 matrices x 256 tokens for SwiGLU), each wave 128 x 128 of it, so that every MFMA fragment read
+// from LDS feeds four MFMAs.  Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
+// VGPR staging), double-buffered; MFMA fragments are read one k-step ahead of their use, across k-tiles too.  The
+// k-loop is generated assembly (gen_gemm_asm.py -> gemm_bf16_mainloops.inc): with a lone wave per SIMD the order of
+// MFMA, LDS and tile-load instructions inside the wave is the schedule.  The residual epilogue (output and down
+// projection) and few rows (<= 128, narrow tiles) use an 8-wave C++ tile with the same LDS layout and pipeline; a
+// register-staged kernel with k predicates covers ragged k_in.
 #include "slim_common.h"
 
 #include <map>
@@ -47,6 +50,11 @@ constexpr int BK = 64;                                   // k-depth of an LDS ti
 // so that the 16 lanes served together by a 128-bit LDS read hit distinct banks.
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 __device__ __forceinline__ int lds_off(int r, int c) { return (r * 8 + (c ^ swz(r))) * 16; }   // bytes
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+#include "gemm_bf16_mainloops.inc"
+#pragma clang diagnostic pop
 
 // Epilogue shared by both bf16 kernels.  acc[w][i][j][v] is out[token m][feature n] with
 //   m = mw + j*32 + l32,   n = nw + i*32 + 8*(v/4) + 4*hh + (v%4)      (mw, nw: the wave's origin)
@@ -257,7 +265,7 @@ __device__ __forceinline__ void tile_of_workgroup(int L, bool xcd_runs, int tile
     tn = rem / gm;
 }
 
-// One output tile of the main path.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned
+// One output tile of the few-row kernel.  8 waves arranged WGN x WGM; requires K % 64 == 0 and 16-byte aligned
 // rows.  The tile starts at token m0, feature n0; M and N bound the loads (clamped) and the stores.
 // With re.row_scale the accumulators of token row m are multiplied by row_scale[m] before the epilogue: with
 // row_scale = 1/sqrt(mean(a[m,:]^2) + eps) and a = the raw residual stream this is the projection of RMSNorm(a)
@@ -417,7 +425,73 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
     }
 }
 
-// Main kernel: every workgroup computes one tile of the same shape.
+// One output tile of the main path: 4 waves arranged 2 (features) x 2 (tokens), each with TW x TA MFMA tiles (of
+// each weight matrix); requires K % 64 == 0, 16-byte aligned rows and row strides below 2^23 elements.  The k-loop
+// is gemm_mainloop_<TW>_<TA>_<NW>; its operands:
+//   wfrag0 / afrag0   LDS byte address of the lane's weight / activation fragment of k-step 0 in stage 0;
+//   r0, chunk         the lane's row inside a group of 32 tile rows and its (swizzled) 16-byte chunk of a 128-byte
+//                     row: wave-load i of a k-tile covers tile rows 32 i + r0 and lands at ldsw + i * 4096;
+//   wlim / alim       last valid row of the tile (loads of rows beyond it are clamped to it; never stored);
+//   strides in bytes, kt = K / 64, and the three tile origins.
+// The tile starts at token m0, feature n0; M and N bound the loads and the stores.  row_scale as in gemm_tile.
+template <int TW, int TA, int EPI>
+__device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
+                                           const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
+                                           int N, int K, int m0, int n0, unsigned char* lds, const EpiExtra& re) {
+    static_assert(EPI != EPI_ROPE || TW == 4, "the RoPE epilogue needs one 128-wide head per wave");
+    static_assert(EPI != EPI_RESIDUAL, "the residual epilogue runs in the 8-wave tile");
+    constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr int BN = 64 * TW, WROWS = BN * NW;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1, wm = wave >> 1;
+    const int l32 = lane & 31, hh = lane >> 5;
+    const unsigned lds_base = (unsigned)(uintptr_t)lds;
+    const unsigned wfrag0 = lds_base + lds_off(wn * TW * 32 + l32, hh);
+    const unsigned afrag0 = lds_base + WROWS * BK * 2 + lds_off(wm * TA * 32 + l32, hh);
+    const unsigned r0 = wave * 8 + (lane >> 3), chunk = ((lane & 7) ^ swz(r0)) * 16;
+    const uint64_t w0base = (uint64_t)(uintptr_t)(W0 + (size_t)n0 * K);
+    const uint64_t w1base = NW == 2 ? (uint64_t)(uintptr_t)(W1 + (size_t)n0 * K) : w0base;
+    const uint64_t abase = (uint64_t)(uintptr_t)(A + (size_t)m0 * lda);
+    f32x16 acc[NW][TW][TA];
+#define SLIM_LOOP_ARGS wfrag0, afrag0, r0, chunk, N - 1 - n0, M - 1 - m0, (unsigned)K * 2, (unsigned)lda * 2,          \
+                       (unsigned)(K / BK), lds_base + wave * 1024, w0base, w1base, abase, acc
+    if constexpr (TW == 4 && TA == 4) gemm_mainloop_4_4_1(SLIM_LOOP_ARGS);
+    else if constexpr (TW == 4 && TA == 2) gemm_mainloop_4_2_1(SLIM_LOOP_ARGS);
+    else if constexpr (TW == 2 && TA == 4) gemm_mainloop_2_4_2(SLIM_LOOP_ARGS);
+    else gemm_mainloop_2_2_2(SLIM_LOOP_ARGS);
+#undef SLIM_LOOP_ARGS
+    static_assert((TW == 4 && NW == 1 && (TA == 4 || TA == 2)) || (TW == 2 && NW == 2 && (TA == 4 || TA == 2)),
+                  "no generated k-loop for this wave tile");
+    if (re.row_scale) {
+#pragma unroll
+        for (int j = 0; j < TA; ++j) {
+            const float inv = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
+#pragma unroll
+            for (int w = 0; w < NW; ++w)
+#pragma unroll
+                for (int i = 0; i < TW; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[w][i][j][v] *= inv;
+        }
+    }
+    // The epilogue reuses the stage buffers: every wave must be past its last fragment reads and tile loads.
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    workgroup_barrier();
+    const bool wide = (N % 8 == 0) && (ldo % 8 == 0) && (((uintptr_t)C & 15) == 0) &&
+                      (EPI != EPI_BIAS || ((uintptr_t)R & 7) == 0);
+    if constexpr (EPI == EPI_ROPE) {                     // the launcher has checked what `wide` checks
+        store_tile_rope<TA>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+                            lds + wave * (TA * 32 * TW * 64), re);
+    } else {
+        if (wide)
+            store_tile_via_lds<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+                                            lds + wave * (TA * 32 * TW * 64));
+        else
+            store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+    }
+}
+
+// Few-row kernel: every workgroup computes one tile of the same shape.
 template <int TW, int TA, int WGN, int WGM, int EPI>
 __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict__ A, int lda,
                                                         const bf16_t* __restrict__ W0,
@@ -431,28 +505,23 @@ __global__ void __launch_bounds__(512) gemm_bf16_kernel(const bf16_t* __restrict
 }
 
 // Shapes of the two-size launch: 256-token tiles for the first big_tiles_m token-tiles, 128-token tiles
-// (same feature width) for the rest.  Wave tiles: plain 64 tokens x 128 features (big), 64 x 64 (small);
-// SwiGLU 64 tokens x 64 gate + 64 up features (big), 64 x 32 + 32 (small); RoPE keeps 128 features (one head)
-// per wave in the small tiles too: 32 tokens x 128 features.
+// (same feature width) for the rest.  Wave tiles: 128 features x 128 tokens (large), 128 x 64 (small); for SwiGLU
+// the 128 features are 64 gate + 64 up.  Either way a wave of the plain shapes holds one 128-wide head (RoPE).
 template <int EPI> struct TileShapes {
-    static constexpr int TW_BIG = EPI == EPI_SWIGLU ? 2 : 4;
-    static constexpr int TW_SMALL = EPI == EPI_SWIGLU ? 1 : (EPI == EPI_ROPE ? 4 : 2);
-    static constexpr int TA_SMALL = EPI == EPI_ROPE ? 1 : 2, WGN_SMALL = EPI == EPI_ROPE ? 2 : 4, WGM_SMALL = 8 / WGN_SMALL;
-    static constexpr int BN = 32 * TW_BIG * 2;           // = 32 * TW_SMALL * WGN_SMALL
-    static constexpr int BM_BIG = 256, BM_SMALL = 32 * TA_SMALL * WGM_SMALL;
-    static_assert(BN == 32 * TW_SMALL * WGN_SMALL && BM_SMALL == 128, "both tile sizes share the feature width");
+    static constexpr int TW = EPI == EPI_SWIGLU ? 2 : 4;
+    static constexpr int TA_BIG = 4, TA_SMALL = 2;
+    static constexpr int BN = 64 * TW;
+    static constexpr int BM_BIG = 64 * TA_BIG, BM_SMALL = 64 * TA_SMALL;
 };
 
 // Two tile sizes in one launch.  Workgroups are started in id order, so the 256-token tiles run first
 // and the 128-token tiles fill the last, partly empty round of workgroups: the tail of the launch costs
 // about half a tile time instead of a whole one, and a ragged last token-tile wastes no MFMA work.
 template <int EPI>
-__global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* __restrict__ A, int lda,
-                                                                 const bf16_t* __restrict__ W0,
-                                                                 const bf16_t* __restrict__ W1, const bf16_t* R,
-                                                                 bf16_t* C, int ldo, int M, int N, int K,
-                                                                 int big_tiles_m, int small_tiles_m, int tiles_n,
-                                                                 EpiExtra re) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+gemm_bf16_two_size_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0,
+                          const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M, int N, int K,
+                          int big_tiles_m, int small_tiles_m, int tiles_n, EpiExtra re) {
     using S = TileShapes<EPI>;
     extern __shared__ __align__(16) unsigned char lds[];
     const int n_big = big_tiles_m * tiles_n;
@@ -465,10 +534,33 @@ __global__ void __launch_bounds__(512) gemm_bf16_two_size_kernel(const bf16_t* _
         tn -= re.tiles_n1;
     }
     if (big)
-        gemm_tile<S::TW_BIG, 2, 2, 4, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
+        gemm_tile4<S::TW, S::TA_BIG, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, re);
     else
-        gemm_tile<S::TW_SMALL, S::TA_SMALL, S::WGN_SMALL, S::WGM_SMALL, EPI>(
-            A, lda, W0, W1, R, C, ldo, M, N, K, big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, re);
+        gemm_tile4<S::TW, S::TA_SMALL, EPI>(A, lda, W0, W1, R, C, ldo, M, N, K,
+                                            big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, re);
+}
+
+// The residual epilogue reads a second tile through LDS; with a lone wave per SIMD nothing hides that pass, and the
+// launch measured slower than with the 8-wave tile (two waves per SIMD: one wave's epilogue steps overlap the
+// other's).  So output and down projection keep 8 waves: wave tiles of 64 tokens x 128 features (large) and
+// 64 x 64 (small), the same workgroup tiles as above.
+__global__ void __launch_bounds__(512)
+gemm_bf16_two_size_residual_kernel(const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W0, const bf16_t* R,
+                                   bf16_t* C, int ldo, int M, int N, int K, int big_tiles_m, int small_tiles_m,
+                                   int tiles_n) {
+    using S = TileShapes<EPI_RESIDUAL>;
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int n_big = big_tiles_m * tiles_n;
+    const bool big = (int)blockIdx.x < n_big;
+    int tm, tn;
+    if (big) tile_of_workgroup(blockIdx.x, true, big_tiles_m, tiles_n, tm, tn);
+    else tile_of_workgroup(blockIdx.x - n_big, n_big % 8 == 0, small_tiles_m, tiles_n, tm, tn);
+    const EpiExtra none;
+    if (big)
+        gemm_tile<4, 2, 2, 4, EPI_RESIDUAL>(A, lda, W0, nullptr, R, C, ldo, M, N, K, tm * S::BM_BIG, tn * S::BN, lds, none);
+    else
+        gemm_tile<2, 2, 4, 2, EPI_RESIDUAL>(A, lda, W0, nullptr, R, C, ldo, M, N, K,
+                                            big_tiles_m * S::BM_BIG + tm * S::BM_SMALL, tn * S::BN, lds, none);
 }
 
 // Generic kernel (any k_in that is a multiple of 8): register-staged loads with k predicates.
@@ -650,17 +742,28 @@ static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf1
     using S = TileShapes<EPI>;
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
-    auto kern = gemm_bf16_two_size_kernel<EPI>;
     static std::once_flag attr_once;
     static hipError_t attr_err = hipSuccess;
-    std::call_once(attr_once, [&] {
-        attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    });
-    if (attr_err != hipSuccess) return set_hip_error(attr_err);
+    if ((size_t)K >= (1u << 23) || (size_t)lda >= (1u << 23)) return SLIM_UNSUPPORTED;   // 32-bit offsets inside a tile
     const int tiles_n = (N + S::BN - 1) / S::BN + (re.w_2 ? (re.n_2 + S::BN - 1) / S::BN : 0);
     const int small_tiles_m = (M - big_tiles_m * S::BM_BIG + S::BM_SMALL - 1) / S::BM_SMALL;
-    hipLaunchKernelGGL(kern, dim3((big_tiles_m + small_tiles_m) * tiles_n), dim3(512), smem, st, A, lda, W0, W1, R, C,
-                       ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n, re);
+    const dim3 grid((big_tiles_m + small_tiles_m) * tiles_n);
+    if constexpr (EPI == EPI_RESIDUAL) {
+        auto kern = gemm_bf16_two_size_residual_kernel;
+        std::call_once(attr_once, [&] {
+            attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        });
+        if (attr_err != hipSuccess) return set_hip_error(attr_err);
+        hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, A, lda, W0, R, C, ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n);
+    } else {
+        auto kern = gemm_bf16_two_size_kernel<EPI>;
+        std::call_once(attr_once, [&] {
+            attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        });
+        if (attr_err != hipSuccess) return set_hip_error(attr_err);
+        hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, A, lda, W0, W1, R, C, ldo, M, N, K, big_tiles_m, small_tiles_m,
+                           tiles_n, re);
+    }
     return check_launch();
 }
 
@@ -681,6 +784,11 @@ static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_
                          int ldo, int M, int N, int K, hipStream_t st, const EpiExtra& re = EpiExtra()) {
     if constexpr (EPI != EPI_ROPE) {                     // (row_scale and RoPE callers have checked K % 64 == 0)
         if (K % BK != 0) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+    }
+    if ((size_t)K >= (1u << 23) || (size_t)lda >= (1u << 23)) {   // 32-bit byte offsets inside a tile of 256 rows
+        if constexpr (EPI == EPI_ROPE) return SLIM_UNSUPPORTED;
+        else if (!re.row_scale && !re.w_2) return launch_bf16<2, 2, 2, 2, EPI, true>(A, lda, W0, W1, R, C, ldo, M, N, K, st);
+        else return SLIM_UNSUPPORTED;
     }
     if (M <= 128) {
         // Few rows: the launch streams the weights once and is bound by how many workgroups pull on memory at the same

@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Writes gemm_bf16_mainloops.inc: the k-loops of the bf16 projection kernels ("QKV Generation", output projection
+and "FFN" of Fig. 2) as gfx950 assembly inside C++ device functions, one per wave-tile shape.  csrc/gemm.hip
+includes the file; its C++ part computes the operands and runs the epilogues on the accumulators the functions
+return.  Run `python gen_gemm_asm.py` after changing this file; the .inc is committed.
+
+Shape of a workgroup: 4 waves, one per SIMD, arranged 2 (features) x 2 (tokens); a wave owns TW x TA MFMA tiles of
+32 x 32 (for SwiGLU: of each of the NW = 2 weight matrices), 128 x 128 outputs in the large tiles, so that each
+fragment read from LDS feeds four MFMAs.  The 16 accumulators fill the accumulation registers (they are the asm
+statement's outputs); fragments are double-buffered in v0..; a lone wave per SIMD means the order of matrix, LDS and
+tile-load instructions in the wave is the schedule, so it is written out here.
+
+k-loop: k-tiles of 64, two LDS stages (tile rows of 128 bytes, 16-byte chunks XOR-swizzled as in gemm.hip), operand
+tiles global -> LDS directly.  Per k-tile: four k-steps of TW*TA*NW MFMAs; the fragments of step s+1 are read beside
+the MFMAs of step s, also across k-tiles.  The one barrier of a k-tile sits before its last k-step, when every wave
+holds that step's fragments and its own part of the next tile has landed; from there on the stage is refilled with
+the tile two ahead.  Those tile loads are issued over three k-steps (a third beside the last k-step, the rest beside
+the first two k-steps of the next tile): issued in one burst right after the barrier they back the wave's
+instruction issue up behind the memory pipeline and cost a quarter of the MFMA rate.
+"""
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from gen_attn_asm import Ins, vr, sr, V, S, valu, salu, nop, label, branch, raw, fix_hazards, weight   # noqa: E402
+
+SPREAD = 3
+S_KPW, S_KPW2, S_KPA, S_CNT, S_LST, S_TMP = 40, 42, 44, 46, 47, 48
+FIRST_S, LAST_S = 40, 48
+
+
+class Shape:
+    def __init__(self, TW, TA, NW):
+        self.TW, self.TA, self.NW = TW, TA, NW
+        self.NWF, self.NAF = NW * TW, TA                       # fragments per k-step
+        n = 4 * (self.NWF + self.NAF)
+        self.FRAG = [0, n]                                     # two fragment buffers: W frags then A frags
+        self.WADR = 2 * n                                      # [stage][ks] LDS addresses of the W fragments
+        self.AADR = self.WADR + 8
+        self.WOFS = self.AADR + 8                              # lane offsets of the tile loads: <= 8 W, <= 8 A
+        self.AOFS = self.WOFS + 8
+        self.TMPV = self.AOFS + 8
+        self.BN = 32 * TW * 2                                  # features per matrix in a workgroup tile
+        self.WROWS = self.BN * NW
+        self.AROWS = 32 * TA * 2
+        self.STAGE = (self.WROWS + self.AROWS) * 128
+        self.NLW = self.WROWS // 32                            # wave-loads per wave and k-tile: weights, then activations
+        self.NLD = (self.WROWS + self.AROWS) // 32
+        assert self.STAGE <= 65536 and self.NLW <= 8 and self.NLD - self.NLW <= 8
+        self.LAST_V = self.TMPV
+        self.name = f"{TW}_{TA}_{NW}"
+
+    def acc(self, w, i, j):
+        return f"%[c{(w * self.TW + i) * self.TA + j}]"
+
+    def mfma(self, buf, w, i, j, zero):
+        wf = self.FRAG[buf] + 4 * (w * self.TW + i)
+        af = self.FRAG[buf] + 4 * (self.NWF + j)
+        c = self.acc(w, i, j)
+        return Ins(f"v_mfma_f32_32x32x16_bf16 {c}, {V(wf, 4)}, {V(af, 4)}, {'0' if zero else c}", "mfma",
+                   r=vr(wf, 4) + vr(af, 4) + ([] if zero else [c]), w=[c])
+
+    def frag_reads(self, buf, stage, ks):
+        out = []
+        for w in range(self.NW):
+            for i in range(self.TW):
+                d = self.FRAG[buf] + 4 * (w * self.TW + i)
+                off = (w * self.BN + i * 32) * 128
+                out.append(Ins(f"ds_read_b128 {V(d, 4)}, {V(self.WADR + stage * 4 + ks)} offset:{off}", "lds",
+                               r=vr(self.WADR + stage * 4 + ks), w=vr(d, 4)))
+        for j in range(self.TA):
+            d = self.FRAG[buf] + 4 * (self.NWF + j)
+            out.append(Ins(f"ds_read_b128 {V(d, 4)}, {V(self.AADR + stage * 4 + ks)} offset:{j * 32 * 128}", "lds",
+                           r=vr(self.AADR + stage * 4 + ks), w=vr(d, 4)))
+        return out
+
+    def tile_loads(self, stage):
+        """The wave's wave-loads of the k-tile at the pending pointers into `stage`; then the pointers move on
+        (they stay on the last k-tile once it is reached: later loads re-read it into a stage nobody reads)."""
+        out = []
+        for i in range(self.NLD):
+            if i < self.NLW:
+                ofs, ptr = self.WOFS + i, (S_KPW2 if (self.NW == 2 and i * 32 >= self.BN) else S_KPW)
+            else:
+                ofs, ptr = self.AOFS + i - self.NLW, S_KPA
+            out.append(salu(f"s_add_u32 m0, %[ldsw], {stage * self.STAGE + i * 4096}", w=["m0", "scc"]))
+            out.append(Ins(f"global_load_lds_dwordx4 {V(ofs)}, {S(ptr, 2)}", "vmem", r=vr(ofs) + ["m0"] + sr(ptr, 2)))
+        out += [salu(f"s_sub_u32 {S(S_LST)}, {S(S_LST)}, 1", r=sr(S_LST), w=sr(S_LST) + ["scc"]),
+                salu(f"s_cmp_gt_i32 {S(S_LST)}, 0", r=sr(S_LST), w=["scc"]),
+                salu(f"s_cselect_b32 {S(S_TMP)}, 128, 0", r=["scc"], w=sr(S_TMP))]
+        for p in (S_KPW, S_KPW2, S_KPA) if self.NW == 2 else (S_KPW, S_KPA):
+            out += [salu(f"s_add_u32 {S(p)}, {S(p)}, {S(S_TMP)}", r=sr(p) + sr(S_TMP), w=sr(p) + ["scc"]),
+                    salu(f"s_addc_u32 {S(p + 1)}, {S(p + 1)}, 0", r=sr(p + 1) + ["scc"], w=sr(p + 1) + ["scc"])]
+        return out
+
+    @staticmethod
+    def deal(mf, fills):
+        out, k = [], 0
+        for i, m in enumerate(mf):
+            out.append(m)
+            want = (i + 1) * len(fills) // len(mf)
+            out += fills[k:want]
+            k = want
+        return out
+
+    def k_tile(self, stage, first):
+        """One k-tile from `stage`; the fragments of its k-step 0 are in buffer 0 (already requested)."""
+        seq = []
+        order = [(w, i, j) for w in range(self.NW) for i in range(self.TW) for j in range(self.TA)]
+        share = lambda loads, k: loads[k * len(loads) // SPREAD:(k + 1) * len(loads) // SPREAD]
+        for ks in range(4):
+            buf = ks & 1
+            seq.append(raw("s_waitcnt lgkmcnt(0)", "wait"))
+            mf = [self.mfma(buf, w, i, j, first and ks == 0) for (w, i, j) in order]
+            if ks < 3:
+                carry = share(self.tile_loads(stage ^ 1), ks + 1) if (not first and ks + 1 < SPREAD) else []
+                seq += self.deal(mf, self.frag_reads(buf ^ 1, stage, ks + 1) + carry)
+            else:
+                seq += [raw("s_waitcnt vmcnt(0)", "wait"), raw("s_barrier", "barrier")]
+                seq += self.deal(mf, self.frag_reads(buf ^ 1, stage ^ 1, 0) + share(self.tile_loads(stage), 0))
+        return seq
+
+    def body(self):
+        pro = []
+        e = pro.append
+        for st in range(2):
+            for ks in range(4):
+                for adr, src in ((self.WADR, "wfrag0"), (self.AADR, "afrag0")):
+                    r = adr + st * 4 + ks
+                    e(valu(f"v_xor_b32 {V(r)}, {ks << 5}, %[{src}]", w=vr(r)))
+                    if st:
+                        e(valu(f"v_add_u32 {V(r)}, {self.STAGE}, {V(r)}", r=vr(r), w=vr(r)))
+        # tile-load lane offsets: row 32 i + r0 of its matrix, clamped to the last valid row
+        for i in range(self.NLD):
+            is_w = i < self.NLW
+            ofs = (self.WOFS + i) if is_w else (self.AOFS + i - self.NLW)
+            row = (32 * i) % self.BN if is_w else 32 * (i - self.NLW)
+            lim, stride = ("%[wlim]", "%[wstride]") if is_w else ("%[alim]", "%[astride]")
+            e(valu(f"v_add_u32 {V(self.TMPV)}, {row}, %[r0]", w=vr(self.TMPV)))
+            e(valu(f"v_min_i32 {V(self.TMPV)}, {lim}, {V(self.TMPV)}", r=vr(self.TMPV), w=vr(self.TMPV)))
+            e(valu(f"v_mad_u32_u24 {V(ofs)}, {V(self.TMPV)}, {stride}, %[chunk]", r=vr(self.TMPV), w=vr(ofs)))
+        ptrs = [(S_KPW, "w0base"), (S_KPA, "abase")] + ([(S_KPW2, "w1base")] if self.NW == 2 else [])
+        for p, name in ptrs:
+            e(salu(f"s_mov_b32 {S(p)}, %[{name}_lo]", w=sr(p)))
+            e(salu(f"s_mov_b32 {S(p + 1)}, %[{name}_hi]", w=sr(p + 1)))
+        e(salu(f"s_mov_b32 {S(S_CNT)}, %[kt]", w=sr(S_CNT)))
+        e(salu(f"s_mov_b32 {S(S_LST)}, %[kt]", w=sr(S_LST)))
+        pro += self.tile_loads(0) + self.tile_loads(1)
+        e(raw("s_waitcnt vmcnt(0)", "wait"))
+        e(raw("s_barrier", "barrier"))
+        pro += self.frag_reads(0, 0, 0)
+        body0f, body0, body1 = self.k_tile(0, True), self.k_tile(0, False), self.k_tile(1, False)
+        dec = lambda: [salu(f"s_sub_u32 {S(S_CNT)}, {S(S_CNT)}, 1", r=sr(S_CNT), w=sr(S_CNT) + ["scc"]),
+                       salu(f"s_cmp_eq_u32 {S(S_CNT)}, 0", r=sr(S_CNT), w=["scc"]), branch("s_cbranch_scc1 GDONE_%=")]
+        seq = fix_hazards(pro + body0f) + dec() + [label("GLOOP_%=")]
+        loop = body1 + dec() + body0 + dec() + [branch("s_branch GLOOP_%=")]
+        seq += fix_hazards(loop, history=body0 + body1)
+        # drain the trailing loads; the accumulators are read by the compiler's code next: pad past the MFMA latency
+        seq += [label("GDONE_%="), raw("s_waitcnt vmcnt(0) lgkmcnt(0)", "wait"), nop(8), nop(8)]
+        n_mfma = sum(1 for x in body0 if x.kind == "mfma")
+        n_oth = sum(weight(x) for x in body0 if x.kind not in ("mfma", "label"))
+        print(f"wave tile {self.name}: k-tile of {n_mfma} MFMAs and {n_oth} other instructions, vgprs to v{self.LAST_V}", file=sys.stderr)
+        return seq
+
+    def function(self):
+        n = self.NW * self.TW * self.TA
+        seq = self.body()
+        out = [f"// wave tile of {self.TW} x {self.TA} MFMA tiles, {self.NW} weight matri{'x' if self.NW == 1 else 'ces'}",
+               f"__device__ __forceinline__ void gemm_mainloop_{self.name}(unsigned wfrag0, unsigned afrag0, unsigned r0, unsigned chunk,",
+               "        int wlim, int alim, unsigned wstride, unsigned astride, unsigned kt, unsigned ldsw, uint64_t w0base,",
+               f"        uint64_t w1base, uint64_t abase, f32x16 (&acc)[{self.NW}][{self.TW}][{self.TA}]) {{",
+               "    f32x16 " + ", ".join(f"c{k}" for k in range(n)) + ";",
+               "    const unsigned w0base_lo = (unsigned)w0base, w0base_hi = (unsigned)(w0base >> 32);",
+               "    const unsigned w1base_lo = (unsigned)w1base, w1base_hi = (unsigned)(w1base >> 32);",
+               "    const unsigned abase_lo = (unsigned)abase, abase_hi = (unsigned)(abase >> 32);",
+               "    asm volatile("]
+        out += ['        "' + x.text + '\\n"' for x in seq]
+        out.append("        : " + ", ".join(f'[c{k}] "=&a"(c{k})' for k in range(n)))
+        ins = ['[wfrag0] "v"(wfrag0)', '[afrag0] "v"(afrag0)', '[r0] "v"(r0)', '[chunk] "v"(chunk)', '[wlim] "s"(wlim)',
+               '[alim] "s"(alim)', '[wstride] "s"(wstride)', '[astride] "s"(astride)', '[kt] "s"(kt)', '[ldsw] "s"(ldsw)',
+               '[w0base_lo] "s"(w0base_lo)', '[w0base_hi] "s"(w0base_hi)', '[abase_lo] "s"(abase_lo)', '[abase_hi] "s"(abase_hi)']
+        if self.NW == 2:
+            ins += ['[w1base_lo] "s"(w1base_lo)', '[w1base_hi] "s"(w1base_hi)']
+        out.append("        : " + ", ".join(ins))
+        clob = [f'"v{i}"' for i in range(self.LAST_V + 1)] + [f'"s{i}"' for i in range(FIRST_S, LAST_S + 1)] + ['"vcc"', '"scc"', '"memory"']
+        out.append("        : " + ", ".join(clob) + ");")
+        if self.NW == 1:
+            out.append("    (void)w1base_lo; (void)w1base_hi;")
+        k = 0
+        for w in range(self.NW):
+            for i in range(self.TW):
+                for j in range(self.TA):
+                    out.append(f"    acc[{w}][{i}][{j}] = c{k};")
+                    k += 1
+        out.append("}")
+        return "\n".join(out) + "\n"
+
+
+def main():
+    here = os.path.dirname(os.path.abspath(__file__))
+    with open(os.path.join(here, "gemm_bf16_mainloops.inc"), "w") as f:
+        f.write("// generated by gen_gemm_asm.py -- do not edit\n")
+        for cfg in ((4, 4, 1), (2, 4, 2), (4, 2, 1), (2, 2, 2)):
+            f.write("\n" + Shape(*cfg).function())
+
+
+if __name__ == "__main__":
+    main()
