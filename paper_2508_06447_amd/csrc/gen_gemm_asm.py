@@ -25,6 +25,7 @@ sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from gen_attn_asm import Ins, vr, sr, V, S, valu, salu, nop, label, branch, raw, fix_hazards, weight   # noqa: E402
 
 SPREAD = 3
+N_ACC_IN_VGPRS = 4
 S_KPW, S_KPW2, S_KPA, S_CNT, S_LST, S_TMP = 40, 42, 44, 46, 47, 48
 FIRST_S, LAST_S = 40, 48
 
@@ -175,7 +176,9 @@ class Shape:
                "    const unsigned abase_lo = (unsigned)abase, abase_hi = (unsigned)(abase >> 32);",
                "    asm volatile("]
         out += ['        "' + x.text + '\\n"' for x in seq]
-        out.append("        : " + ", ".join(f'[c{k}] "=&a"(c{k})' for k in range(n)))
+        # the last accumulators live in VGPRs: with all 256 accumulation registers taken by the outputs the compiler
+        # spills some of them to scratch memory behind the loop
+        out.append("        : " + ", ".join(f'[c{k}] "=&{"a" if k < n - N_ACC_IN_VGPRS else "v"}"(c{k})' for k in range(n)))
         ins = ['[wfrag0] "v"(wfrag0)', '[afrag0] "v"(afrag0)', '[r0] "v"(r0)', '[chunk] "v"(chunk)', '[wlim] "s"(wlim)',
                '[alim] "s"(alim)', '[wstride] "s"(wstride)', '[astride] "s"(astride)', '[kt] "s"(kt)', '[ldsw] "s"(ldsw)',
                '[w0base_lo] "s"(w0base_lo)', '[w0base_hi] "s"(w0base_hi)', '[abase_lo] "s"(abase_lo)', '[abase_hi] "s"(abase_hi)']
