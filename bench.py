@@ -200,6 +200,48 @@ def profiled_traffic(kernel_prefix):
     return None
 
 
+def profiled_in_layer(table):
+    """Kernel durations inside slim_pruned_layer as last measured with a rocprofv3 kernel trace (see profiles/), joined
+    with the work figures of the stage table: the stage table times each kernel alone, back to back with itself; inside
+    the layer a kernel starts with the caches, clocks and memory state that its predecessor left.  Returns None if no
+    measurement is on file.  bench.py itself runs no profiler."""
+    path = os.path.join(ROOT, "profiles", "pruned_layer_cfg3_in_layer_times.txt")
+    by_stage, order = {}, []
+    try:
+        for line in open(path):
+            if line.startswith("#") or not line.strip():
+                continue
+            _, kernel, stages, mean, lo, hi = line.rstrip("\n").split("\t")
+            if stages not in by_stage:
+                by_stage[stages] = {"kernels": [], "us": 0.0}
+                order.append(stages)
+            by_stage[stages]["kernels"].append(kernel)
+            by_stage[stages]["us"] += float(mean)
+    except (OSError, ValueError):
+        return None
+    out = []
+    for stages in order:
+        e = {"stages": stages, "kernels": by_stage[stages]["kernels"], "ms": round(by_stage[stages]["us"] / 1e3, 4)}
+        parts = [table.get(name) for name in stages.split("+")]
+        if all(parts):
+            work, bound = sum(t["work"] for t in parts), parts[0]["bound"]
+            e["bound"] = bound
+            if bound == "mfma":
+                e["tflops"] = round(work / (e["ms"] * 1e-3) / 1e12, 1)
+                e["frac"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+            elif bound == "hbm":
+                e["gbs"] = round(work / (e["ms"] * 1e-3) / 1e9, 1)
+                e["frac"] = round(e["gbs"] / PEAK_HBM_GBS, 4)
+            if len(parts) == 1:
+                parts[0]["in_layer_ms"] = e["ms"]
+                if "frac" in e:
+                    parts[0]["in_layer_frac"] = e["frac"]
+        out.append(e)
+    return {"source": "profiles/pruned_layer_cfg3_in_layer_times.txt (rocprofv3 kernel trace of this command, means over "
+                      "the timed layer calls; not re-measured by this run)",
+            "sum_ms": round(sum(e["ms"] for e in out), 4), "kernels": out}
+
+
 def measured_ceilings(slim, dev):
     """What this chip sustains in this run: a register-only MFMA loop and a plain 1 GiB copy."""
     import torch
@@ -587,6 +629,12 @@ def main():
                            "frac": dom["frac"], "traffic": profiled_traffic("gemm_bf16_two_size_kernel<2>"),
                            "traffic_unit": "bytes per launch, rocprofv3 FETCH_SIZE x2 + WRITE_SIZE (profiles/)",
                            "algorithmic_bytes": 2 * (n * Hd + 2 * F * Hd + n * F), "avg_ms": dom["ms"]}
+        in_layer = profiled_in_layer(table)
+        if in_layer:
+            rec["in_layer"] = in_layer
+            if "in_layer_ms" in dom:
+                rec["roofline"]["in_layer_avg_ms"] = dom["in_layer_ms"]
+                rec["roofline"]["in_layer_frac"] = dom["in_layer_frac"]
     if not args.no_stages:
         rec["measured_ceilings"] = measured_ceilings(slim, dev)
     if not args.no_cpu:
