@@ -78,7 +78,7 @@ __device__ __forceinline__ void store_tile(f32x16 (&acc)[EPI == EPI_SWIGLU ? 2 :
                 for (int e = 0; e < 4; ++e) {
                     if (EPI == EPI_SWIGLU) {
                         const float g = acc[0][i][j][vg * 4 + e], u = acc[NW - 1][i][j][vg * 4 + e];
-                        o[e] = g / (1.0f + __expf(-g)) * u;
+                        o[e] = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;   // v_rcp_f32: 1 ulp, the result is rounded to bf16
                     } else {
                         o[e] = acc[0][i][j][vg * 4 + e];
                     }
@@ -147,7 +147,7 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
                 for (int e = 0; e < 4; ++e) {
                     if (EPI == EPI_SWIGLU) {
                         const float g = acc[0][i][j][vg * 4 + e], u = acc[NW - 1][i][j][vg * 4 + e];
-                        o[e] = g / (1.0f + __expf(-g)) * u;
+                        o[e] = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;   // v_rcp_f32: 1 ulp, the result is rounded to bf16
                     } else {
                         o[e] = acc[0][i][j][vg * 4 + e];
                     }
