@@ -689,19 +689,20 @@ static int launch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t*
 // How many 256-token tiles to run before the 128-token tiles.  Workgroups are handed to free CUs in id
 // order, which is list scheduling; it is simulated for each candidate and the shortest makespan wins.
 // The model, fitted to sweeps of the split on the layer's shapes:
-//   a 128-token tile costs small_cost of a 256-token one (0.5 plain, 0.55 SwiGLU);
+//   a 128-token tile costs small_cost of a 256-token one (small_tile_cost);
 //   CU speeds are spread over +-8 % (tiles do not run equally fast on all CUs, which is what makes a
 //   fine-grained tail pay even when the large tiles fill whole rounds);
-//   +1 % / +3 % when the per-XCD run of large tiles is not a multiple of 8 / of 4 tiles (the run then
-//   straddles columns of the band walk and shares fewer operand panels in that XCD's L2);
-//   +5 % for fewer than 4 token-tiles of small tiles (too few rows to share a weight panel between the
-//   workgroups that run together).
+//   for the 8-wave tiles only (the sweeps of the 4-wave tiles show neither effect):
+//     +1 % / +3 % when the per-XCD run of large tiles is not a multiple of 8 / of 4 tiles (the run then
+//     straddles columns of the band walk and shares fewer operand panels in that XCD's L2);
+//     +5 % for fewer than 4 token-tiles of small tiles (too few rows to share a weight panel between the
+//     workgroups that run together).
 // The result is a pure function of its arguments; the cache only remembers it (guarded, never invalidated).
-static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
+static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost, bool eight_waves) {
     static std::mutex mu;
-    static std::map<std::tuple<int, int, int>, int> cache;
+    static std::map<std::tuple<int, int, int, bool>, int> cache;
     std::lock_guard<std::mutex> lock(mu);
-    const auto key = std::make_tuple(M, tiles_n, (int)(small_cost * 1000));
+    const auto key = std::make_tuple(M, tiles_n, (int)(small_cost * 1000), eight_waves);
     const auto hit = cache.find(key);
     if (hit != cache.end()) return hit->second;
     std::vector<double> speed(n_cu);
@@ -723,16 +724,23 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost) {
             if (s.first > makespan) makespan = s.first;
             free_at.push(s);
         }
-        if (nb > 0 && nb % 8 == 0) {
+        if (eight_waves && nb > 0 && nb % 8 == 0) {
             const long run = nb / 8;
             if (run % 8 != 0) makespan *= 1.01;
             if (run % 4 != 0) makespan *= 1.03;
         }
-        if (small_tiles_m > 0 && small_tiles_m < 4 && mb > 0) makespan *= 1.05;
+        if (eight_waves && small_tiles_m > 0 && small_tiles_m < 4 && mb > 0) makespan *= 1.05;
         if (makespan < best) { best = makespan; best_mb = mb; }
     }
     cache[key] = best_mb;
     return best_mb;
+}
+
+// What a 128-token tile costs next to a 256-token one of the same launch (measured k-loop + epilogue times): the
+// 4-wave small tiles run 8 MFMAs per k-step against 6 fragment reads and 3 tile loads (SwiGLU: 8 against 6 and 3,
+// with the longer epilogue per output), the 8-wave ones keep the ratio of the large tile.
+template <int EPI> constexpr double small_tile_cost() {
+    return EPI == EPI_RESIDUAL ? 0.5 : (EPI == EPI_SWIGLU ? 0.7 : 0.6);
 }
 
 template <int EPI>
@@ -800,7 +808,7 @@ static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_
     }
     const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;
     return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K,
-                                      plan_big_tiles(M, tiles_n, cu_count(), EPI == EPI_SWIGLU ? 0.55 : 0.5), st, re);
+                                      plan_big_tiles(M, tiles_n, cu_count(), small_tile_cost<EPI>(), EPI == EPI_RESIDUAL), st, re);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
@@ -904,13 +912,13 @@ int launch_linear_pair(const void* a, int lda, const void* w_1, const void* bias
         re.tiles_n1 = (n_1 + S::BN - 1) / S::BN;
         const int tiles_n = re.tiles_n1 + (n_2 + S::BN - 1) / S::BN;
         return launch_two_size<EPI_BIAS>(A, lda, W, nullptr, B, (bf16_t*)out_1, ldo_1, m, n_1, k_in,
-                                         plan_big_tiles(m, tiles_n, cu_count(), 0.5), st, re);
+                                         plan_big_tiles(m, tiles_n, cu_count(), small_tile_cost<EPI_BIAS>(), false), st, re);
     }
     using S = TileShapes<EPI_PLAIN>;
     re.tiles_n1 = (n_1 + S::BN - 1) / S::BN;
     const int tiles_n = re.tiles_n1 + (n_2 + S::BN - 1) / S::BN;
     return launch_two_size<EPI_PLAIN>(A, lda, W, nullptr, nullptr, (bf16_t*)out_1, ldo_1, m, n_1, k_in,
-                                      plan_big_tiles(m, tiles_n, cu_count(), 0.5), st, re);
+                                      plan_big_tiles(m, tiles_n, cu_count(), small_tile_cost<EPI_PLAIN>(), false), st, re);
 }
 
 // At most one of w1 (SwiGLU), residual and bias is set.
