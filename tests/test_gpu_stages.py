@@ -173,6 +173,9 @@ def test_rope_with_large_positions(slim, n, H, d, dtype):
     (256, 256, 64, torch.bfloat16), (512, 1024, 4096, torch.bfloat16), (300, 520, 192, torch.bfloat16),
     (64, 4096, 4096, torch.bfloat16), (1, 8, 8, torch.bfloat16), (700, 260, 200, torch.bfloat16),
     (1300, 776, 128, torch.bfloat16), (3000, 512, 64, torch.bfloat16),   # several 256- and 128-token tiles
+    (129, 264, 320, torch.bfloat16),     # one row past a 128-token tile, an odd number of k-tiles
+    (257, 64, 448, torch.bfloat16),      # one row past a 256-token tile, a quarter of a feature tile
+    (1000, 8, 128, torch.bfloat16),      # eight features: every weight row of the tile but eight is a clamped copy
     (130, 70, 50, torch.float32), (512, 688, 256, torch.float32),
 ])
 def test_linear_all_epilogues(slim, m, n, k, dtype):
