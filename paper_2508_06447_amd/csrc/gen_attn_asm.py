@@ -593,7 +593,7 @@ def main():
     used_v = max(int(r[1:]) for x in seq for r in (x.r | x.w) if r[0] == "v" and r[1:].isdigit())
     used_a = max(int(r[1:]) for x in seq for r in (x.r | x.w) if r[0] == "a" and r[1:].isdigit())
     assert used_v <= LAST_V and used_a <= LAST_A, (used_v, used_a)
-    here = os.path.dirname(os.path.abspath(__file__))
+    here = sys.argv[1] if len(sys.argv) > 1 else os.path.dirname(os.path.abspath(__file__))   # output directory
     with open(os.path.join(here, "attn_bf16_body.inc"), "w") as f:
         f.write("// generated by gen_attn_asm.py -- do not edit\n")
         # labels get the asm statement's unique number, so that the block can be instantiated more than once

@@ -2,7 +2,8 @@
 """Writes gemm_bf16_mainloops.inc: the k-loops of the bf16 projection kernels ("QKV Generation", output projection
 and "FFN" of Fig. 2) as gfx950 assembly inside C++ device functions, one per wave-tile shape.  csrc/gemm.hip
 includes the file; its C++ part computes the operands and runs the epilogues on the accumulators the functions
-return.  Run `python gen_gemm_asm.py` after changing this file; the .inc is committed.
+return.  Run `python gen_gemm_asm.py` after changing this file (an argument names another output directory); the .inc is
+committed and tests/test_generated_sources.py checks that it is current.
 
 Shape of a workgroup: 4 waves, one per SIMD, arranged 2 (features) x 2 (tokens); a wave owns TW x TA MFMA tiles of
 32 x 32 (for SwiGLU: of each of the NW = 2 weight matrices), 128 x 128 outputs in the large tiles, so that each
@@ -200,7 +201,7 @@ class Shape:
 
 
 def main():
-    here = os.path.dirname(os.path.abspath(__file__))
+    here = sys.argv[1] if len(sys.argv) > 1 else os.path.dirname(os.path.abspath(__file__))   # output directory
     with open(os.path.join(here, "gemm_bf16_mainloops.inc"), "w") as f:
         f.write("// generated by gen_gemm_asm.py -- do not edit\n")
         for cfg in ((4, 4, 1), (2, 4, 2), (4, 2, 1), (2, 2, 2)):
