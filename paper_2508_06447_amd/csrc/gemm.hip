@@ -134,6 +134,16 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
             *reinterpret_cast<uint4*>(region + slot(row, rchunk)) = v;
         }
     }
+    uint2 bias4[EPI == EPI_BIAS ? TW * 4 : 1];            // the lane's bias values, requested together
+    if (EPI == EPI_BIAS) {
+#pragma unroll
+        for (int i = 0; i < TW; ++i)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                const int n = nw + i * 32 + 8 * vg + 4 * hh;
+                bias4[i * 4 + vg] = n < N ? *reinterpret_cast<const uint2*>(R + n) : make_uint2(0, 0);
+            }
+    }
 #pragma unroll
     for (int j = 0; j < TA; ++j)
 #pragma unroll
@@ -157,11 +167,8 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[EPI == EPI_SWIG
                     o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
                 }
                 if (EPI == EPI_BIAS) {                    // 4 consecutive features of the bias vector (N % 8 == 0 here)
-                    const int n = nw + i * 32 + 8 * vg + 4 * hh;
-                    if (n < N) {
-                        const uint2 r = *reinterpret_cast<const uint2*>(R + n);
-                        o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
-                    }
+                    const uint2 r = bias4[EPI == EPI_BIAS ? i * 4 + vg : 0];
+                    o[0] += lo_bf16(r.x); o[1] += hi_bf16(r.x); o[2] += lo_bf16(r.y); o[3] += hi_bf16(r.y);
                 }
                 *cell = make_uint2(pack_bf16x2(o[0], o[1]), pack_bf16x2(o[2], o[3]));
             }
@@ -192,30 +199,44 @@ __device__ __forceinline__ void store_tile_rope(f32x16 (&acc)[1][4][TA], const b
     float dot[TA];
 #pragma unroll
     for (int j = 0; j < TA; ++j) dot[j] = 0.f;
+    // Per half of the head's rotation indices (i), every table, bias and window-query value the lane needs is requested
+    // first and used afterwards: 8 * TA + 16 loads in flight, one wait.  (Left to the compiler, the loads went out two
+    // at a time, each pair waited for: forty memory round trips per tile.)
+    const float* trow0[TA];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < TA; ++j) trow0[j] = re.table + (size_t)min(mw + j * 32 + l32, M - 1) * 128 + 4 * hh;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        float4 c4[4][TA], s4[4][TA], q1[4], q2[4];
+        uint2 r1[4], r2[4];
 #pragma unroll
         for (int vg = 0; vg < 4; ++vg) {
             const int f = i * 32 + 8 * vg + 4 * hh;      // rotation index of element e = 0
-            float b1[4] = {0.f, 0.f, 0.f, 0.f}, b2[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < TA; ++j) {
+                c4[vg][j] = *reinterpret_cast<const float4*>(trow0[j] + i * 32 + 8 * vg);
+                s4[vg][j] = *reinterpret_cast<const float4*>(trow0[j] + i * 32 + 8 * vg + 64);
+            }
+            r1[vg] = r2[vg] = make_uint2(0, 0);
             if (bias) {
-                const uint2 r1 = *reinterpret_cast<const uint2*>(bias + nw + f);
-                const uint2 r2 = *reinterpret_cast<const uint2*>(bias + nw + 64 + f);
-                b1[0] = lo_bf16(r1.x); b1[1] = hi_bf16(r1.x); b1[2] = lo_bf16(r1.y); b1[3] = hi_bf16(r1.y);
-                b2[0] = lo_bf16(r2.x); b2[1] = hi_bf16(r2.x); b2[2] = lo_bf16(r2.y); b2[3] = hi_bf16(r2.y);
+                r1[vg] = *reinterpret_cast<const uint2*>(bias + nw + f);
+                r2[vg] = *reinterpret_cast<const uint2*>(bias + nw + 64 + f);
             }
-            float4 q1 = make_float4(0.f, 0.f, 0.f, 0.f), q2 = q1;
+            q1[vg] = q2[vg] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (score) {
-                q1 = *reinterpret_cast<const float4*>(re.qt + nw + f);
-                q2 = *reinterpret_cast<const float4*>(re.qt + nw + 64 + f);
+                q1[vg] = *reinterpret_cast<const float4*>(re.qt + nw + f);
+                q2[vg] = *reinterpret_cast<const float4*>(re.qt + nw + 64 + f);
             }
+        }
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+            const float b1[4] = {lo_bf16(r1[vg].x), hi_bf16(r1[vg].x), lo_bf16(r1[vg].y), hi_bf16(r1[vg].y)};
+            const float b2[4] = {lo_bf16(r2[vg].x), hi_bf16(r2[vg].x), lo_bf16(r2[vg].y), hi_bf16(r2[vg].y)};
 #pragma unroll
             for (int j = 0; j < TA; ++j) {
                 const int row = j * 32 + l32;
-                const float* trow = re.table + (size_t)min(mw + row, M - 1) * 128 + f;
-                const float4 c4 = *reinterpret_cast<const float4*>(trow);
-                const float4 s4 = *reinterpret_cast<const float4*>(trow + 64);
-                const float c[4] = {c4.x, c4.y, c4.z, c4.w}, sn[4] = {s4.x, s4.y, s4.z, s4.w};
+                const float c[4] = {c4[vg][j].x, c4[vg][j].y, c4[vg][j].z, c4[vg][j].w};
+                const float sn[4] = {s4[vg][j].x, s4[vg][j].y, s4[vg][j].z, s4[vg][j].w};
                 float o1[4], o2[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -228,10 +249,11 @@ __device__ __forceinline__ void store_tile_rope(f32x16 (&acc)[1][4][TA], const b
                 *reinterpret_cast<uint2*>(region + slot(row, i * 4 + vg) + hh * 8) = p1;
                 *reinterpret_cast<uint2*>(region + slot(row, (i + 2) * 4 + vg) + hh * 8) = p2;
                 if (score)
-                    dot[j] += lo_bf16(p1.x) * q1.x + hi_bf16(p1.x) * q1.y + lo_bf16(p1.y) * q1.z + hi_bf16(p1.y) * q1.w +
-                              lo_bf16(p2.x) * q2.x + hi_bf16(p2.x) * q2.y + lo_bf16(p2.y) * q2.z + hi_bf16(p2.y) * q2.w;
+                    dot[j] += lo_bf16(p1.x) * q1[vg].x + hi_bf16(p1.x) * q1[vg].y + lo_bf16(p1.y) * q1[vg].z + hi_bf16(p1.y) * q1[vg].w +
+                              lo_bf16(p2.x) * q2[vg].x + hi_bf16(p2.x) * q2[vg].y + lo_bf16(p2.y) * q2[vg].z + hi_bf16(p2.y) * q2[vg].w;
             }
         }
+    }
     if (score) {
 #pragma unroll
         for (int j = 0; j < TA; ++j) {
@@ -397,16 +419,17 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
         if (kt + 1 < KT) k_tile(kt + 1, Stage1{}, Stage0{});
     }
     if (re.row_scale) {
+        float inv[TA];                                   // all requested before the first is used: one wait, not TA
 #pragma unroll
-        for (int j = 0; j < TA; ++j) {
-            const float inv = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
+        for (int j = 0; j < TA; ++j) inv[j] = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
+#pragma unroll
+        for (int j = 0; j < TA; ++j)
 #pragma unroll
             for (int w = 0; w < NW; ++w)
 #pragma unroll
                 for (int i = 0; i < TW; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[w][i][j][v] *= inv;
-        }
+                    for (int v = 0; v < 16; ++v) acc[w][i][j][v] *= inv[j];
     }
     // The epilogue reuses the stage buffers: every wave must be past its last fragment reads.
     __builtin_amdgcn_s_waitcnt(0x0070);
@@ -463,16 +486,17 @@ __device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda
     static_assert((TW == 4 && NW == 1 && (TA == 4 || TA == 2)) || (TW == 2 && NW == 2 && (TA == 4 || TA == 2)),
                   "no generated k-loop for this wave tile");
     if (re.row_scale) {
+        float inv[TA];                                   // all requested before the first is used: one wait, not TA
 #pragma unroll
-        for (int j = 0; j < TA; ++j) {
-            const float inv = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
+        for (int j = 0; j < TA; ++j) inv[j] = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
+#pragma unroll
+        for (int j = 0; j < TA; ++j)
 #pragma unroll
             for (int w = 0; w < NW; ++w)
 #pragma unroll
                 for (int i = 0; i < TW; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[w][i][j][v] *= inv;
-        }
+                    for (int v = 0; v < 16; ++v) acc[w][i][j][v] *= inv[j];
     }
     // The epilogue reuses the stage buffers: every wave must be past its last fragment reads and tile loads.
     __builtin_amdgcn_s_waitcnt(0x0070);
