@@ -198,6 +198,32 @@ def test_linear_all_epilogues(slim, m, n, k, dtype):
                                atol=rel * np.abs(sw).max())
 
 
+@pytest.mark.parametrize("m,n,k,lda,ldo", [(300, 520, 192, 256, 640), (1000, 264, 128, 136, 272), (64, 512, 256, 320, 520)])
+def test_linear_with_row_strides(slim, m, n, k, lda, ldo):
+    """Rows of a and of out / residual that are longer than what the call uses (lda > k_in, ldo > n_out), through the
+    C ABI directly: the padding columns of out must stay untouched."""
+    import ctypes
+    print(f"linear strided m={m} n={n} k={k} lda={lda} ldo={ldo}", flush=True)
+    lib = slim.load_library()
+    bf = torch.bfloat16
+    a_wide, w, w2 = dev(rand((m, lda), bf, 1)), dev(rand((n, k), bf, 2, 0.05)), dev(rand((n, k), bf, 3, 0.05))
+    r_wide = dev(rand((m, ldo), bf, 4))
+    A, W, W2, R = f64(a_wide)[:, :k], f64(w), f64(w2), f64(r_wide)[:, :n]
+    P = lambda t: ctypes.c_void_p(t.data_ptr() if t is not None else 0)
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    rel = 2.0 ** -8
+    for name, call, want in (
+            ("plain", lambda o: lib.slim_linear(P(a_wide), lda, P(w), P(None), m, n, k, ldo, 1, P(o), st), A @ W.T),
+            ("residual", lambda o: lib.slim_linear(P(a_wide), lda, P(w), P(r_wide), m, n, k, ldo, 1, P(o), st), A @ W.T + R),
+            ("swiglu", lambda o: lib.slim_swiglu_linear(P(a_wide), lda, P(w), P(w2), m, n, k, ldo, 1, P(o), st),
+             so.silu(A @ W.T) * (A @ W2.T))):
+        out = torch.full((m, ldo), 7.0, dtype=bf, device="cuda")
+        assert call(out) == 0, name
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(f64(out)[:, :n], want, rtol=rel, atol=rel * np.abs(want).max(), err_msg=name)
+        assert (f64(out)[:, n:] == 7.0).all(), f"{name}: wrote past n_out"
+
+
 @pytest.mark.parametrize("m,n,k,dtype", [
     (1300, 3584, 256, torch.bfloat16), (64, 512, 3584, torch.bfloat16), (300, 520, 192, torch.bfloat16),
     (700, 260, 200, torch.bfloat16), (130, 70, 50, torch.float32),
