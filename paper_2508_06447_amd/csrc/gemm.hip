@@ -462,7 +462,6 @@ __device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda
                                            const bf16_t* __restrict__ W1, const bf16_t* R, bf16_t* C, int ldo, int M,
                                            int N, int K, int m0, int n0, unsigned char* lds, const EpiExtra& re) {
     static_assert(EPI != EPI_ROPE || TW == 4, "the RoPE epilogue needs one 128-wide head per wave");
-    static_assert(EPI != EPI_RESIDUAL, "the residual epilogue runs in the 8-wave tile");
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr int BN = 64 * TW, WROWS = BN * NW;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -478,7 +477,17 @@ __device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda
     f32x16 acc[NW][TW][TA];
 #define SLIM_LOOP_ARGS wfrag0, afrag0, r0, chunk, N - 1 - n0, M - 1 - m0, (unsigned)K * 2, (unsigned)lda * 2,          \
                        (unsigned)(K / BK), lds_base + wave * 1024, w0base, w1base, abase, acc
-    if constexpr (TW == 4 && TA == 4) gemm_mainloop_4_4_1(SLIM_LOOP_ARGS);
+    // With a residual the k-loop itself adds the tile of R to the accumulators (it fetches the tile as MFMA fragments
+    // and multiplies it by identity slices), and the tile is then stored as a plain one.  The launcher has checked that
+    // the tile has all its features and that the rows of R are 16-byte aligned.
+    constexpr int EPI_OUT = EPI == EPI_RESIDUAL ? (int)EPI_PLAIN : EPI;
+    if constexpr (EPI == EPI_RESIDUAL) {
+        const unsigned rrow0 = wm * TA * 32 + l32;                              // the lane's token row of the tile (j = 0)
+        const unsigned rcol0 = (unsigned)(n0 + wn * TW * 32 + 8 * hh) * 2;      // byte column of its 8 features
+        const bf16_t* rbase = R + (size_t)m0 * ldo;
+        if constexpr (TA == 4) gemm_mainloop_4_4_1_resid(SLIM_LOOP_ARGS, rrow0, rcol0, (unsigned)ldo * 2, rbase);
+        else gemm_mainloop_4_2_1_resid(SLIM_LOOP_ARGS, rrow0, rcol0, (unsigned)ldo * 2, rbase);
+    } else if constexpr (TW == 4 && TA == 4) gemm_mainloop_4_4_1(SLIM_LOOP_ARGS);
     else if constexpr (TW == 4 && TA == 2) gemm_mainloop_4_2_1(SLIM_LOOP_ARGS);
     else if constexpr (TW == 2 && TA == 4) gemm_mainloop_2_4_2(SLIM_LOOP_ARGS);
     else gemm_mainloop_2_2_2(SLIM_LOOP_ARGS);
@@ -508,10 +517,10 @@ __device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda
                             lds + wave * (TA * 32 * TW * 64), re);
     } else {
         if (wide)
-            store_tile_via_lds<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+            store_tile_via_lds<TW, TA, EPI_OUT>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
                                             lds + wave * (TA * 32 * TW * 64));
         else
-            store_tile<TW, TA, EPI>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+            store_tile<TW, TA, EPI_OUT>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
     }
 }
 
@@ -760,32 +769,44 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost, bool 
     return best_mb;
 }
 
+// Which tile the residual epilogue runs in.  The 4-wave tile takes the residual tile in as MFMA fragments (16-byte loads
+// at the lane's own rows and features), which needs every tile to have all of its features and 16-byte aligned rows of
+// R.  It is the faster one (output projection of 9856 tokens: -4 % inside the layer) as long as the activation matrix
+// sits in the 256 MB memory-side cache; when it streams from HBM (down projection: 282 MB) the 8-wave tile, which
+// issues a k-tile's loads at once and so leaves them longest to arrive, measured 2.4 % faster.  The 8-wave tile's
+// epilogue parks a coalesced copy of the tile of R in LDS and takes any shape.
+static bool residual_in_four_waves(const bf16_t* R, int M, int N, int K, int ldo) {
+    const size_t activation_bytes = (size_t)M * K * sizeof(bf16_t);
+    return N % 256 == 0 && ldo % 8 == 0 && ((uintptr_t)R & 15) == 0 && activation_bytes <= ((size_t)160 << 20);
+}
+
 // What a 128-token tile costs next to a 256-token one of the same launch (measured k-loop + epilogue times): the
 // 4-wave small tiles run 8 MFMAs per k-step against 6 fragment reads and 3 tile loads (SwiGLU: 8 against 6 and 3,
 // with the longer epilogue per output), the 8-wave ones keep the ratio of the large tile.
-template <int EPI> constexpr double small_tile_cost() {
-    return EPI == EPI_RESIDUAL ? 0.5 : (EPI == EPI_SWIGLU ? 0.7 : 0.6);
+template <int EPI> constexpr double small_tile_cost(bool eight_waves) {
+    return eight_waves ? 0.5 : (EPI == EPI_SWIGLU ? 0.7 : 0.6);
 }
 
 template <int EPI>
 static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf16_t* W1, const bf16_t* R, bf16_t* C,
-                           int ldo, int M, int N, int K, int big_tiles_m, hipStream_t st,
+                           int ldo, int M, int N, int K, int big_tiles_m, bool eight_waves, hipStream_t st,
                            const EpiExtra& re = EpiExtra()) {
     using S = TileShapes<EPI>;
     constexpr int NW = EPI == EPI_SWIGLU ? 2 : 1;
     constexpr size_t smem = 2 * (size_t)(S::BN * NW + S::BM_BIG) * BK * 2;
-    static std::once_flag attr_once;
-    static hipError_t attr_err = hipSuccess;
-    if ((size_t)K >= (1u << 23) || (size_t)lda >= (1u << 23)) return SLIM_UNSUPPORTED;   // 32-bit offsets inside a tile
+    static std::once_flag attr_once, attr8_once;
+    static hipError_t attr_err = hipSuccess, attr8_err = hipSuccess;
+    if ((size_t)K >= (1u << 23) || (size_t)lda >= (1u << 23) || (size_t)ldo >= (1u << 23))
+        return SLIM_UNSUPPORTED;                         // 32-bit byte offsets inside a tile
     const int tiles_n = (N + S::BN - 1) / S::BN + (re.w_2 ? (re.n_2 + S::BN - 1) / S::BN : 0);
     const int small_tiles_m = (M - big_tiles_m * S::BM_BIG + S::BM_SMALL - 1) / S::BM_SMALL;
     const dim3 grid((big_tiles_m + small_tiles_m) * tiles_n);
-    if constexpr (EPI == EPI_RESIDUAL) {
+    if (EPI == EPI_RESIDUAL && eight_waves) {
         auto kern = gemm_bf16_two_size_residual_kernel;
-        std::call_once(attr_once, [&] {
-            attr_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        std::call_once(attr8_once, [&] {
+            attr8_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         });
-        if (attr_err != hipSuccess) return set_hip_error(attr_err);
+        if (attr8_err != hipSuccess) return set_hip_error(attr8_err);
         hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, A, lda, W0, R, C, ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n);
     } else {
         auto kern = gemm_bf16_two_size_kernel<EPI>;
@@ -831,8 +852,9 @@ static int dispatch_bf16(const bf16_t* A, int lda, const bf16_t* W0, const bf16_
         else return launch_bf16<2, 1, 2, 4, EPI, false>(A, lda, W0, W1, R, C, ldo, M, N, K, st, re);
     }
     const int tiles_n = (N + TileShapes<EPI>::BN - 1) / TileShapes<EPI>::BN;
+    const bool eight = EPI == EPI_RESIDUAL && !residual_in_four_waves(R, M, N, K, ldo);
     return launch_two_size<EPI>(A, lda, W0, W1, R, C, ldo, M, N, K,
-                                      plan_big_tiles(M, tiles_n, cu_count(), small_tile_cost<EPI>(), EPI == EPI_RESIDUAL), st, re);
+                                plan_big_tiles(M, tiles_n, cu_count(), small_tile_cost<EPI>(eight), eight), eight, st, re);
 }
 
 // fp32 path (small fp32 workloads only): 64x64 output tile, 16-deep k-tiles in LDS, 4x4 per thread.
@@ -936,13 +958,15 @@ int launch_linear_pair(const void* a, int lda, const void* w_1, const void* bias
         re.tiles_n1 = (n_1 + S::BN - 1) / S::BN;
         const int tiles_n = re.tiles_n1 + (n_2 + S::BN - 1) / S::BN;
         return launch_two_size<EPI_BIAS>(A, lda, W, nullptr, B, (bf16_t*)out_1, ldo_1, m, n_1, k_in,
-                                         plan_big_tiles(m, tiles_n, cu_count(), small_tile_cost<EPI_BIAS>(), false), st, re);
+                                         plan_big_tiles(m, tiles_n, cu_count(), small_tile_cost<EPI_BIAS>(false), false),
+                                         false, st, re);
     }
     using S = TileShapes<EPI_PLAIN>;
     re.tiles_n1 = (n_1 + S::BN - 1) / S::BN;
     const int tiles_n = re.tiles_n1 + (n_2 + S::BN - 1) / S::BN;
     return launch_two_size<EPI_PLAIN>(A, lda, W, nullptr, nullptr, (bf16_t*)out_1, ldo_1, m, n_1, k_in,
-                                      plan_big_tiles(m, tiles_n, cu_count(), small_tile_cost<EPI_PLAIN>(), false), st, re);
+                                      plan_big_tiles(m, tiles_n, cu_count(), small_tile_cost<EPI_PLAIN>(false), false),
+                                      false, st, re);
 }
 
 // At most one of w1 (SwiGLU), residual and bias is set.

@@ -32,8 +32,14 @@ FIRST_S, LAST_S = 40, 48
 
 
 class Shape:
-    def __init__(self, TW, TA, NW):
+    def __init__(self, TW, TA, NW, resid=False):
         self.TW, self.TA, self.NW = TW, TA, NW
+        # resid: out = a . w^T + R.  The loop's prologue requests the wave's part of the residual tile as MFMA B
+        # fragments (lane (token, half) takes features 8*half .. 8*half+7 of each group of 16 output features: 16-byte
+        # loads), and behind the first k-tile, when they have arrived, adds them to the accumulators with two MFMAs per
+        # accumulator whose A operand is a slice of the identity (row f of the 32-row tile has its one at k = f - 16p
+        # for the group p): acc += I . R, exact, no vector ALU work, and the epilogue is the plain one.
+        self.resid = resid
         self.NWF, self.NAF = NW * TW, TA                       # fragments per k-step
         n = 4 * (self.NWF + self.NAF)
         self.FRAG = [0, n]                                     # two fragment buffers: W frags then A frags
@@ -49,8 +55,12 @@ class Shape:
         self.NLW = self.WROWS // 32                            # wave-loads per wave and k-tile: weights, then activations
         self.NLD = (self.WROWS + self.AROWS) // 32
         assert self.STAGE <= 65536 and self.NLW <= 8 and self.NLD - self.NLW <= 8
-        self.LAST_V = self.TMPV
-        self.name = f"{TW}_{TA}_{NW}"
+        self.ROFS = self.TMPV + 1                              # byte offsets of the lane's TA residual rows
+        self.IDENT = (self.ROFS + TA + 1) & ~1                 # two identity slices, 4 registers each
+        self.RES = self.IDENT + 8                              # residual fragments, 4 registers per (j, i, p)
+        self.LAST_V = self.RES + 4 * TA * TW * 2 - 1 if resid else self.TMPV
+        assert self.LAST_V < 256
+        self.name = f"{TW}_{TA}_{NW}" + ("_resid" if resid else "")
 
     def acc(self, w, i, j):
         return f"%[c{(w * self.TW + i) * self.TA + j}]"
@@ -61,6 +71,19 @@ class Shape:
         c = self.acc(w, i, j)
         return Ins(f"v_mfma_f32_32x32x16_bf16 {c}, {V(wf, 4)}, {V(af, 4)}, {'0' if zero else c}", "mfma",
                    r=vr(wf, 4) + vr(af, 4) + ([] if zero else [c]), w=[c])
+
+    def res_frag(self, j, i, p):
+        return self.RES + 4 * ((j * self.TW + i) * 2 + p)
+
+    def residual_mfmas(self):
+        out = []
+        for p in range(2):                                     # the two MFMAs of an accumulator 16 apart
+            for j in range(self.TA):
+                for i in range(self.TW):
+                    c, a, b = self.acc(0, i, j), self.IDENT + 4 * p, self.res_frag(j, i, p)
+                    out.append(Ins(f"v_mfma_f32_32x32x16_bf16 {c}, {V(a, 4)}, {V(b, 4)}, {c}", "mfma",
+                                   r=vr(a, 4) + vr(b, 4) + [c], w=[c]))
+        return out
 
     def frag_reads(self, buf, stage, ks):
         out = []
@@ -148,10 +171,43 @@ class Shape:
         e(salu(f"s_mov_b32 {S(S_CNT)}, %[kt]", w=sr(S_CNT)))
         e(salu(f"s_mov_b32 {S(S_LST)}, %[kt]", w=sr(S_LST)))
         pro += self.tile_loads(0) + self.tile_loads(1)
-        e(raw("s_waitcnt vmcnt(0)", "wait"))
+        n_res = 0
+        if self.resid:
+            for j in range(self.TA):                           # row = min(rrow0 + 32 j, alim) of the workgroup tile
+                e(valu(f"v_add_u32 {V(self.TMPV)}, {32 * j}, %[rrow0]", w=vr(self.TMPV)))
+                e(valu(f"v_min_i32 {V(self.TMPV)}, %[alim], {V(self.TMPV)}", r=vr(self.TMPV), w=vr(self.TMPV)))
+                e(valu(f"v_mad_u32_u24 {V(self.ROFS + j)}, {V(self.TMPV)}, %[rstride], %[rcol0]", r=vr(self.TMPV), w=vr(self.ROFS + j)))
+            for j in range(self.TA):
+                for i in range(self.TW):
+                    for p in range(2):
+                        d = self.res_frag(j, i, p)
+                        e(Ins(f"global_load_dwordx4 {V(d, 4)}, {V(self.ROFS + j)}, %[rbase] offset:{i * 64 + p * 32}", "vmem",
+                              r=vr(self.ROFS + j), w=vr(d, 4)))
+                        n_res += 1
+            # identity slices: t = f - 8*half - 16p with f = rrow0 & 31 and half = bit 4 of rcol0; the lane's one is
+            # bf16 element t of its 8 (if 0 <= t < 8): dword t >> 1, upper half if t is odd
+            t, val, idx = self.TMPV, self.ROFS + self.TA, self.TMPV      # ROFS + TA is a spare register below IDENT
+            for p in range(2):
+                e(valu(f"v_and_b32 {V(t)}, 31, %[rrow0]", w=vr(t)))
+                e(valu(f"v_bfe_u32 {V(val)}, %[rcol0], 4, 1", w=vr(val)))
+                e(valu(f"v_lshlrev_b32 {V(val)}, 3, {V(val)}", r=vr(val), w=vr(val)))
+                e(valu(f"v_sub_u32 {V(t)}, {V(t)}, {V(val)}", r=vr(t) + vr(val), w=vr(t)))
+                e(valu(f"v_subrev_u32 {V(t)}, {16 * p}, {V(t)}", r=vr(t), w=vr(t)))
+                sh = self.IDENT + 7                            # free until the last select of p = 1 writes it
+                e(valu(f"v_and_b32 {V(sh)}, 1, {V(t)}", r=vr(t), w=vr(sh)))
+                e(valu(f"v_lshlrev_b32 {V(sh)}, 4, {V(sh)}", r=vr(sh), w=vr(sh)))
+                e(valu(f"v_mov_b32 {V(val)}, 0x3f80", w=vr(val)))                  # bf16 1.0
+                e(valu(f"v_lshlrev_b32 {V(val)}, {V(sh)}, {V(val)}", r=vr(sh) + vr(val), w=vr(val)))
+                e(valu(f"v_ashrrev_i32 {V(idx)}, 1, {V(t)}", r=vr(t), w=vr(idx)))
+                for dw in range(4):
+                    e(valu(f"v_cmp_eq_u32 vcc, {dw}, {V(idx)}", r=vr(idx), w=["vcc"], kind="vcmp"))
+                    e(valu(f"v_cndmask_b32 {V(self.IDENT + 4 * p + dw)}, 0, {V(val)}, vcc", r=vr(val) + ["vcc"], w=vr(self.IDENT + 4 * p + dw)))
+        e(raw(f"s_waitcnt vmcnt({n_res})", "wait"))
         e(raw("s_barrier", "barrier"))
         pro += self.frag_reads(0, 0, 0)
         body0f, body0, body1 = self.k_tile(0, True), self.k_tile(0, False), self.k_tile(1, False)
+        if self.resid:
+            body0f = body0f + self.residual_mfmas()            # behind the first k-tile's wait for every load
         dec = lambda: [salu(f"s_sub_u32 {S(S_CNT)}, {S(S_CNT)}, 1", r=sr(S_CNT), w=sr(S_CNT) + ["scc"]),
                        salu(f"s_cmp_eq_u32 {S(S_CNT)}, 0", r=sr(S_CNT), w=["scc"]), branch("s_cbranch_scc1 GDONE_%=")]
         seq = fix_hazards(pro + body0f) + dec() + [label("GLOOP_%=")]
@@ -167,10 +223,12 @@ class Shape:
     def function(self):
         n = self.NW * self.TW * self.TA
         seq = self.body()
-        out = [f"// wave tile of {self.TW} x {self.TA} MFMA tiles, {self.NW} weight matri{'x' if self.NW == 1 else 'ces'}",
+        out = [f"// wave tile of {self.TW} x {self.TA} MFMA tiles, {self.NW} weight matri{'x' if self.NW == 1 else 'ces'}"
+               + ("; adds the residual tile to the accumulators" if self.resid else ""),
                f"__device__ __forceinline__ void gemm_mainloop_{self.name}(unsigned wfrag0, unsigned afrag0, unsigned r0, unsigned chunk,",
                "        int wlim, int alim, unsigned wstride, unsigned astride, unsigned kt, unsigned ldsw, uint64_t w0base,",
-               f"        uint64_t w1base, uint64_t abase, f32x16 (&acc)[{self.NW}][{self.TW}][{self.TA}]) {{",
+               f"        uint64_t w1base, uint64_t abase, f32x16 (&acc)[{self.NW}][{self.TW}][{self.TA}]"
+               + (", unsigned rrow0, unsigned rcol0, unsigned rstride, const void* rbase" if self.resid else "") + ") {",
                "    f32x16 " + ", ".join(f"c{k}" for k in range(n)) + ";",
                "    const unsigned w0base_lo = (unsigned)w0base, w0base_hi = (unsigned)(w0base >> 32);",
                "    const unsigned w1base_lo = (unsigned)w1base, w1base_hi = (unsigned)(w1base >> 32);",
@@ -178,13 +236,16 @@ class Shape:
                "    asm volatile("]
         out += ['        "' + x.text + '\\n"' for x in seq]
         # the last accumulators live in VGPRs: with all 256 accumulation registers taken by the outputs the compiler
-        # spills some of them to scratch memory behind the loop
-        out.append("        : " + ", ".join(f'[c{k}] "=&{"a" if k < n - N_ACC_IN_VGPRS else "v"}"(c{k})' for k in range(n)))
+        # spills some of them to scratch memory behind the loop (the residual form has no VGPRs to spare for that)
+        in_vgprs = 0 if self.resid else N_ACC_IN_VGPRS
+        out.append("        : " + ", ".join(f'[c{k}] "=&{"a" if k < n - in_vgprs else "v"}"(c{k})' for k in range(n)))
         ins = ['[wfrag0] "v"(wfrag0)', '[afrag0] "v"(afrag0)', '[r0] "v"(r0)', '[chunk] "v"(chunk)', '[wlim] "s"(wlim)',
                '[alim] "s"(alim)', '[wstride] "s"(wstride)', '[astride] "s"(astride)', '[kt] "s"(kt)', '[ldsw] "s"(ldsw)',
                '[w0base_lo] "s"(w0base_lo)', '[w0base_hi] "s"(w0base_hi)', '[abase_lo] "s"(abase_lo)', '[abase_hi] "s"(abase_hi)']
         if self.NW == 2:
             ins += ['[w1base_lo] "s"(w1base_lo)', '[w1base_hi] "s"(w1base_hi)']
+        if self.resid:
+            ins += ['[rrow0] "v"(rrow0)', '[rcol0] "v"(rcol0)', '[rstride] "s"(rstride)', '[rbase] "s"(rbase)']
         out.append("        : " + ", ".join(ins))
         clob = [f'"v{i}"' for i in range(self.LAST_V + 1)] + [f'"s{i}"' for i in range(FIRST_S, LAST_S + 1)] + ['"vcc"', '"scc"', '"memory"']
         out.append("        : " + ", ".join(clob) + ");")
@@ -204,7 +265,7 @@ def main():
     here = sys.argv[1] if len(sys.argv) > 1 else os.path.dirname(os.path.abspath(__file__))   # output directory
     with open(os.path.join(here, "gemm_bf16_mainloops.inc"), "w") as f:
         f.write("// generated by gen_gemm_asm.py -- do not edit\n")
-        for cfg in ((4, 4, 1), (2, 4, 2), (4, 2, 1), (2, 2, 2)):
+        for cfg in ((4, 4, 1), (2, 4, 2), (4, 2, 1), (2, 2, 2), (4, 4, 1, True), (4, 2, 1, True)):
             f.write("\n" + Shape(*cfg).function())
 
 
