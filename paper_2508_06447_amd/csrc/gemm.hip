@@ -492,12 +492,18 @@ __device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda
     else if constexpr (TW == 2 && TA == 4) gemm_mainloop_2_4_2(SLIM_LOOP_ARGS);
     else gemm_mainloop_2_2_2(SLIM_LOOP_ARGS);
 #undef SLIM_LOOP_ARGS
+    // The epilogue's per-lane values are formed again behind the loop from a lane id that the compiler must take as
+    // new: anything it derived from the lane id earlier would otherwise be kept in VGPRs across the loop, which has
+    // few to spare, and be spilled to scratch memory.
+    int tid_e = tid;
+    asm volatile("" : "+v"(tid_e));
+    const int lane_e = tid_e & 63, l32_e = lane_e & 31, hh_e = lane_e >> 5;
     static_assert((TW == 4 && NW == 1 && (TA == 4 || TA == 2)) || (TW == 2 && NW == 2 && (TA == 4 || TA == 2)),
                   "no generated k-loop for this wave tile");
     if (re.row_scale) {
         float inv[TA];                                   // all requested before the first is used: one wait, not TA
 #pragma unroll
-        for (int j = 0; j < TA; ++j) inv[j] = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32, M - 1)];
+        for (int j = 0; j < TA; ++j) inv[j] = re.row_scale[min(m0 + (wm * TA + j) * 32 + l32_e, M - 1)];
 #pragma unroll
         for (int j = 0; j < TA; ++j)
 #pragma unroll
@@ -513,14 +519,14 @@ __device__ __forceinline__ void gemm_tile4(const bf16_t* __restrict__ A, int lda
     const bool wide = (N % 8 == 0) && (ldo % 8 == 0) && (((uintptr_t)C & 15) == 0) &&
                       (EPI != EPI_BIAS || ((uintptr_t)R & 7) == 0);
     if constexpr (EPI == EPI_ROPE) {                     // the launcher has checked what `wide` checks
-        store_tile_rope<TA>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+        store_tile_rope<TA>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane_e,
                             lds + wave * (TA * 32 * TW * 64), re);
     } else {
         if (wide)
-            store_tile_via_lds<TW, TA, EPI_OUT>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane,
+            store_tile_via_lds<TW, TA, EPI_OUT>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, lane_e,
                                             lds + wave * (TA * 32 * TW * 64));
         else
-            store_tile<TW, TA, EPI_OUT>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32, hh);
+            store_tile<TW, TA, EPI_OUT>(acc, R, C, ldo, M, N, m0 + wm * TA * 32, n0 + wn * TW * 32, l32_e, hh_e);
     }
 }
 
