@@ -778,13 +778,16 @@ static int plan_big_tiles(int M, int tiles_n, int n_cu, double small_cost, bool 
 
 // Which tile the residual epilogue runs in.  The 4-wave tile takes the residual tile in as MFMA fragments (16-byte loads
 // at the lane's own rows and features), which needs every tile to have all of its features and 16-byte aligned rows of
-// R.  It is the faster one (output projection of 9856 tokens: -4 % inside the layer) as long as the activation matrix
-// sits in the 256 MB memory-side cache; when it streams from HBM (down projection: 282 MB) the 8-wave tile, which
-// issues a k-tile's loads at once and so leaves them longest to arrive, measured 2.4 % faster.  The 8-wave tile's
-// epilogue parks a coalesced copy of the tile of R in LDS and takes any shape.
+// R.  Measured against the 8-wave tile on one machine, 4096 features out: with rows of 4096 (output projection) it is
+// the faster one at every token count from 2048 to 32768 (-1.5 % to -6 %; -4 % inside the layer at 9856 tokens); with
+// rows of 14336 (down projection) it is 1-2 % faster while the activation matrix sits in the 256 MB memory-side cache
+// and 4-7 % slower once that matrix streams from HBM (282 MB at 9856 tokens), where the 8-wave tile, which issues a
+// k-tile's loads at once and so leaves them longest to arrive, wins.  The 8-wave tile's epilogue parks a coalesced copy
+// of the tile of R in LDS and takes any shape.
 static bool residual_in_four_waves(const bf16_t* R, int M, int N, int K, int ldo) {
     const size_t activation_bytes = (size_t)M * K * sizeof(bf16_t);
-    return N % 256 == 0 && ldo % 8 == 0 && ((uintptr_t)R & 15) == 0 && activation_bytes <= ((size_t)160 << 20);
+    return N % 256 == 0 && ldo % 8 == 0 && ((uintptr_t)R & 15) == 0 &&
+           (K <= 8192 || activation_bytes <= ((size_t)160 << 20));
 }
 
 // What a 128-token tile costs next to a 256-token one of the same launch (measured k-loop + epilogue times): the
@@ -814,10 +817,11 @@ static int launch_two_size(const bf16_t* A, int lda, const bf16_t* W0, const bf1
             attr8_err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         });
         if (attr8_err != hipSuccess) return set_hip_error(attr8_err);
-        // Activations that stream from HBM (they do not fit the memory-side cache): bands of 2 token-tiles, so that the
-        // tiles resident on an XCD cover every feature tile of a token band and each activation panel is fetched once
-        // instead of once per group of 4 feature tiles (down projection of 9856 tokens: -1.8 %).
-        const int band = (size_t)M * K * sizeof(bf16_t) > ((size_t)160 << 20) ? 2 : 8;
+        // Long activation rows that stream from HBM (the matrix does not fit the memory-side cache): bands of 2
+        // token-tiles, so that the tiles resident on an XCD cover every feature tile of a token band and each
+        // activation panel is fetched once instead of once per group of 4 feature tiles (down projection of 9856
+        // tokens -1.8 %, of 32768 tokens -2.6 %; with rows of 4096 the same walk is 6 % slower, so it is not used there).
+        const int band = ((size_t)M * K * sizeof(bf16_t) > ((size_t)160 << 20) && K > 8192) ? 2 : 8;
         hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, A, lda, W0, R, C, ldo, M, N, K, big_tiles_m, small_tiles_m, tiles_n,
                            band);
     } else {
