@@ -17,8 +17,10 @@
 //
 // Softmax: Q is pre-multiplied by scale*log2(e) (bf16), logits are kept relative to a per-query reference that
 // enters through the S accumulators' initial value, so P = exp2(acc) with no multiply or subtract per element;
-// the reference is the row maximum of the first 32 keys and moves only when a later logit exceeds it by 2^8
-// (then O and the row sums are rescaled), so the result does not depend on it.  Row sums add the unrounded P.
+// the reference is the row maximum of the first 32 keys and moves only when the P of a later 32-key unit add up to
+// more than 2^8 in some lane (a logit may then lie more than 8 above the reference; seen before those P are used:
+// the reference moves up to the unit's maximum, O and the row sums are rescaled, the unit's P are formed again),
+// so the result does not depend on it.  Row sums add the unrounded P.
 //
 // The kernel body (main loop, instruction order, register assignment: O accumulators and Q fragments in
 // a0-a191, S tiles and everything the vector ALU touches in v0-v231) is the assembly that gen_attn_asm.py writes

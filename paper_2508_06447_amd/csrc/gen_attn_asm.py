@@ -13,11 +13,17 @@ wave per SIMD the order of matrix, vector and LDS instructions inside the wave i
 written out here.
 
 Schedule.  A unit is 32 keys x 64 queries.  For unit u the wave runs
-  A(u): 16 MFMAs S(u+1) = K Q^T - reference, dealt between them: P(u) = exp2(S(u)) for 10 of its 16 values,
-        row sums, conversion to bf16;
-  B(u): 16 MFMAs O += V^T P(u), dealt between them: the rest of P(u), then the per-lane maxima of S(u+1) and the
-        test whether a logit exceeds the reference by more than 2^8 (then, on a path of its own, the reference
-        moves and O and the row sums are rescaled).
+  A(u): 16 MFMAs S(u+1) = K Q^T - reference, dealt between them: P(u) = exp2(S(u)) for 10 of its 16 values per
+        query sub-tile (into temporaries: S(u) stays whole), their sum, conversion to bf16; at the end the test
+        whether a lane's sum of P(u) exceeds 2^8;
+  B(u): 16 MFMAs O += V^T P(u); between the second eight (the first eight still read the registers that the first
+        bf16 pairs go to): the first 6 values of P(u+1).
+The softmax reference of a query moves only on a path of its own, entered when that test fires, which is before any
+P(u) has been used: a sum above 2^8 means that some logit may lie more than 8 above the reference (or that its
+exponential overflowed).  There the per-query maximum of S(u) is taken, the reference moves up by it, S(u) and
+S(u+1) are shifted, O and the row sums rescaled and P(u) formed again.  Testing the sums, which the row sums need
+anyway, instead of the maxima of S saves 17 vector instructions of 100 per unit; every vector instruction between
+the MFMAs of this loop costs about 1.8 cycles (measured by leaving groups of them out).
 Fragments are read three MFMA pairs ahead into rings of registers.  K/V tiles of 128 keys (4 units) go from global
 memory straight into LDS, two stages each; per tile the workgroup meets at two barriers placed in the middle of a
 phase: one after which the K stage of the tile just finished is refilled, one for the V stage.  The last three
@@ -41,6 +47,9 @@ NRING = 8
 KOFF, VOFF = 144, 152                # 8 + 4 LDS byte addresses
 KOFS, VOFS = 156, 164                # global byte offsets of the tile loads (8 + 8)
 REF, LRUN, TMAX = [172, 173], [174, 175], [176, 177]
+LUNIT = TMAX                         # sum of P over the part of a unit being checked (TMAX is free in the loop)
+EARLY = 3                            # pairs of a unit whose P are formed during the unit before
+EXPT = [188, 189, 190, 191]          # P in fp32 on its way to the row sum and the bf16 pair: two items in flight
 LIMU = [178, 179]
 TMP = 180                            # 180..199 temporaries
 LAST_V, LAST_A = 231, 191
@@ -53,7 +62,7 @@ S_RAGK, S_RAGV = 60, 62
 S_RET, S_TLK, S_TLV, S_MASKC = 64, 65, 66, 67
 S_SAVE = 68
 FIRST_S, LAST_S = 40, 69
-SLACK, NINF, ONES_BF16 = "0x41000000", "0xff800000", "0x3f803f80"
+SUM_LIMIT, NINF, ONES_BF16 = "0x43800000", "0xff800000", "0x3f803f80"      # 2^8
 AHEAD = 3
 
 
@@ -110,25 +119,50 @@ def ld_v(dt, sub, step, vslot):
                 w=vr(v + 2, 2))]
 
 
-def exp_item(buf, qt, pair):
+def exp_item(buf, qt, pair, slot, summed, first):
+    """P for two keys of one query sub-tile: exp2 into temporaries (S stays, for the path that moves the reference),
+    their sum into the part-of-unit sum, the bf16 pair."""
     s = S_BUF[buf][qt] + 2 * pair
     p = PB[qt] + pair
-    l = LRUN[qt]
-    return [valu(f"v_exp_f32 {V(s)}, {V(s)}", r=vr(s), w=vr(s), kind="trans"),
-            valu(f"v_exp_f32 {V(s + 1)}, {V(s + 1)}", r=vr(s + 1), w=vr(s + 1), kind="trans"),
-            valu(f"v_add_f32 {V(l)}, {V(l)}, {V(s)}", r=vr(s) + vr(l), w=vr(l)),
-            valu(f"v_add_f32 {V(l)}, {V(l)}, {V(s + 1)}", r=vr(s + 1) + vr(l), w=vr(l)),
-            valu(f"v_cvt_pk_bf16_f32 {V(p)}, {V(s)}, {V(s + 1)}", r=vr(s, 2), w=vr(p))]
+    t = EXPT[2 * slot]
+    lu = LUNIT[qt]
+    out = [valu(f"v_exp_f32 {V(t)}, {V(s)}", r=vr(s), w=vr(t), kind="trans"),
+           valu(f"v_exp_f32 {V(t + 1)}, {V(s + 1)}", r=vr(s + 1), w=vr(t + 1), kind="trans")]
+    if summed and first:
+        out.append(valu(f"v_add_f32 {V(lu)}, {V(t)}, {V(t + 1)}", r=vr(t, 2), w=vr(lu)))
+    elif summed:
+        out.append(valu(f"v_add_f32 {V(lu)}, {V(lu)}, {V(t)}", r=vr(t) + vr(lu), w=vr(lu)))
+        out.append(valu(f"v_add_f32 {V(lu)}, {V(lu)}, {V(t + 1)}", r=vr(t + 1) + vr(lu), w=vr(lu)))
+    out.append(valu(f"v_cvt_pk_bf16_f32 {V(p)}, {V(t)}, {V(t + 1)}", r=vr(t, 2), w=vr(p)))
+    return out
 
 
-def exp_stream(buf, pairs):
-    out, prev = [], None
-    for sq in [exp_item(buf, qt, p) for p in pairs for qt in (0, 1)]:
-        out += sq[:2]
-        if prev:
-            out += prev[2:]
-        prev = sq
+def exp_stream(buf, pairs, fresh):
+    """The items of `pairs` for both query sub-tiles, the exponentials of an item issued ahead of the previous
+    item's sum and conversion.  fresh: the first item of each sub-tile starts the unit's sum."""
+    out, prev, started, n = [], None, set(), 0
+    for p in pairs:
+        for qt in (0, 1):
+            sq = exp_item(buf, qt, p, n & 1, True, fresh and qt not in started)
+            started.add(qt)
+            n += 1
+            out += sq[:2]
+            if prev:
+                out += prev[2:]
+            prev = sq
     return out + prev[2:]
+
+
+def sum_check():
+    """vcc = some lane's part-of-unit sum exceeds 2^8: some logit may lie more than 8 above the reference (or the
+    exponential overflowed), and nothing computed from these P has been used yet."""
+    return [valu(f"v_max_f32 {V(TMP + 2)}, {V(LUNIT[0])}, {V(LUNIT[1])}", r=vr(LUNIT[0]) + vr(LUNIT[1]), w=vr(TMP + 2)),
+            valu(f"v_cmp_lt_f32 vcc, {SUM_LIMIT}, {V(TMP + 2)}", r=vr(TMP + 2), w=["vcc"], kind="vcmp")]
+
+
+def sum_commit():
+    return [valu(f"v_add_f32 {V(LRUN[qt])}, {V(LRUN[qt])}, {V(LUNIT[qt])}", r=vr(LRUN[qt]) + vr(LUNIT[qt]), w=vr(LRUN[qt]))
+            for qt in (0, 1)]
 
 
 def max_local(buf):
@@ -153,18 +187,6 @@ def max_exchange():
                         w=vr(TMAX[qt]) + vr(TMP + qt), kind="perm"))
     for qt in (0, 1):
         out.append(valu(f"v_max_f32 {V(TMAX[qt])}, {V(TMAX[qt])}, {V(TMP + qt)}", r=vr(TMAX[qt]) + vr(TMP + qt), w=vr(TMAX[qt])))
-    return out
-
-
-def max_stream(buf, with_cmp=True):
-    """Per-lane maxima of S(buf); vcc = some lane saw a logit above the slack (the rare path then combines the
-    halves).  Without the compare (first unit) the halves are combined here."""
-    out = max_local(buf)
-    if with_cmp:
-        out.append(valu(f"v_max_f32 {V(TMP + 2)}, {V(TMAX[0])}, {V(TMAX[1])}", r=vr(TMAX[0]) + vr(TMAX[1]), w=vr(TMP + 2)))
-        out.append(valu(f"v_cmp_lt_f32 vcc, {SLACK}, {V(TMP + 2)}", r=vr(TMP + 2), w=["vcc"], kind="vcmp"))
-    else:
-        out += max_exchange()
     return out
 
 
@@ -329,7 +351,8 @@ def build_groups(masked, tag):
             ks = KRING + (kslot % NRING) * 4
             ag.append(dict(frag=ld_k(st, sub_k, ks), mfma=[mfma_qk(nxt, 0, st, ks), mfma_qk(nxt, 1, st, ks)], fill=[], pre=[], post=[]))
             kslot += 1
-        deal(ag, exp_stream(cur, range(0, 5)))
+        deal(ag, exp_stream(cur, range(EARLY, 8), fresh=False) + sum_check())
+        ag[7]["post"] += [branch(f"s_cbranch_vccnz RARE_{tag}{j}"), label(f"BACK_{tag}{j}")] + sum_commit()
         if masked:
             ag[0]["pre"] += [salu(f"s_add_u32 {S(S_K0N)}, {S(S_K0N)}, 32", r=sr(S_K0N), w=sr(S_K0N) + ["scc"]),
                              salu(f"s_add_u32 {S(S_TMP)}, {S(S_K0N)}, 31", r=sr(S_K0N), w=sr(S_TMP) + ["scc"]),
@@ -344,15 +367,13 @@ def build_groups(masked, tag):
                 bg.append(dict(frag=ld_v(dt, j, step, vslot % NRING), mfma=[mfma_pv(dt, 0, step, vslot % NRING), mfma_pv(dt, 1, step, vslot % NRING)],
                                fill=[], pre=[], post=[]))
                 vslot += 1
-        deal(bg[:4], exp_stream(cur, range(5, 8)))
+        deal(bg[4:], exp_stream(nxt, range(0, EARLY), fresh=True))
         if j == 2:
             bg[4]["pre"] += barrier_block()
             bg[4]["pre"] += [valu(f"v_xor_b32 {V(KOFF + st)}, 0x10000, {V(KOFF + st)}", r=vr(KOFF + st), w=vr(KOFF + st)) for st in range(8)]
         if masked:
             bg[4]["pre"] += [salu(f"s_cmp_lg_u32 {S(S_MASKC)}, 0", r=sr(S_MASKC), w=["scc"]), branch(f"s_cbranch_scc0 SKIPM_{tag}{j}"),
                              ("MASKBLOCK", nxt), label(f"SKIPM_{tag}{j}")]
-        deal(bg[4:], max_stream(nxt))
-        bg[7]["post"] += [branch(f"s_cbranch_vccnz RARE_{tag}{j}"), label(f"BACK_{tag}{j}")]
         G += bg
     iy = 4                      # Y barrier sits before group 4 of A(0)
     deal(G[iy:iy + 12], tile_load_instrs(1) + tile_advance(1))
@@ -414,15 +435,19 @@ def loop_tail(name, bound):
 
 # ----------------------------------------------------------------------------- rare path, prologue, epilogue
 def rare_block(tag, j, ret):
-    nxt = (j + 1) & 1
-    out = [label(f"RARE_{tag}{j}"), nop(8), nop(8)] + max_exchange()
+    """Entered from unit j's check, behind all of its P and before any of them is used.  S of the unit is still whole:
+    take its maximum per query, move the reference up by it (if positive), shift S of this unit and of the next (already
+    computed against the old reference), rescale the row sums and, on the common path behind this block, O."""
+    cur, nxt = j & 1, (j + 1) & 1
+    out = [label(f"RARE_{tag}{j}"), nop(8), nop(8)] + max_local(cur) + max_exchange()
     for qt in (0, 1):
         d = TMP + 6 + qt
         out.append(valu(f"v_max_f32 {V(d)}, 0, {V(TMAX[qt])}", r=vr(TMAX[qt]), w=vr(d)))
         out.append(valu(f"v_add_f32 {V(REF[qt])}, {V(REF[qt])}, {V(d)}", r=vr(REF[qt]) + vr(d), w=vr(REF[qt])))
-        for v in range(16):
-            s = S_BUF[nxt][qt] + v
-            out.append(valu(f"v_sub_f32 {V(s)}, {V(s)}, {V(d)}", r=vr(s) + vr(d), w=vr(s)))
+        for buf in (cur, nxt):
+            for v in range(16):
+                s = S_BUF[buf][qt] + v
+                out.append(valu(f"v_sub_f32 {V(s)}, {V(s)}, {V(d)}", r=vr(s) + vr(d), w=vr(s)))
         out.append(valu(f"v_xor_b32 {V(TMP + 3)}, 0x80000000, {V(REF[qt])}", r=vr(REF[qt]), w=vr(TMP + 3)))
         for v in range(16):
             out.append(valu(f"v_mov_b32 {V(NEGR[qt] + v)}, {V(TMP + 3)}", r=vr(TMP + 3), w=vr(NEGR[qt] + v)))
@@ -431,6 +456,13 @@ def rare_block(tag, j, ret):
     for qt in (0, 1):
         out.append(valu(f"v_mul_f32 {V(LRUN[qt])}, {V(LRUN[qt])}, {V(TMP + 4 + qt)}", r=vr(LRUN[qt]) + vr(TMP + 4 + qt), w=vr(LRUN[qt])))
     out += [salu(f"s_mov_b32 {S(S_RET)}, {ret}", w=sr(S_RET)), branch("s_branch RESCALE")]
+    return out
+
+
+def redo_block(tag, j):
+    """Behind the rescaling: the unit's P and their sum again, from the shifted S."""
+    out = [label(f"REDO_{tag}{j}")] + exp_stream(j & 1, range(0, 8), fresh=True)
+    out += [nop(4), branch(f"s_branch BACK_{tag}{j}")]
     return out
 
 
@@ -516,7 +548,7 @@ def prologue():
     e(branch("s_cbranch_scc1 SKIPM_P"))
     out += mask_block(0)
     e(label("SKIPM_P"))
-    out += max_stream(0, with_cmp=False)
+    out += max_local(0) + max_exchange()
     for qt in (0, 1):
         e(valu(f"v_mov_b32 {V(REF[qt])}, {V(TMAX[qt])}", r=vr(TMAX[qt]), w=vr(REF[qt])))
         for v in range(16):
@@ -525,6 +557,7 @@ def prologue():
         e(valu(f"v_xor_b32 {V(TMP + 3)}, 0x80000000, {V(TMAX[qt])}", r=vr(TMAX[qt]), w=vr(TMP + 3)))
         for v in range(16):
             e(valu(f"v_mov_b32 {V(NEGR[qt] + v)}, {V(TMP + 3)}", r=vr(TMP + 3), w=vr(NEGR[qt] + v)))
+    out += exp_stream(0, range(0, EARLY), fresh=True)
     e(nop(8)); e(nop(8))
     return out
 
@@ -587,8 +620,8 @@ def main():
     for tag in ("m", "d"):
         for j in range(4):
             ret = len(returns)
-            returns.append((ret, f"BACK_{tag}{j}"))
-            seq += fix_hazards(rare_block(tag, j, ret))
+            returns.append((ret, f"REDO_{tag}{j}"))
+            seq += fix_hazards(rare_block(tag, j, ret)) + fix_hazards(redo_block(tag, j))
     seq += fix_hazards(rescale_block(returns)) + [label("DONE")]
     used_v = max(int(r[1:]) for x in seq for r in (x.r | x.w) if r[0] == "v" and r[1:].isdigit())
     used_a = max(int(r[1:]) for x in seq for r in (x.r | x.w) if r[0] == "a" and r[1:].isdigit())

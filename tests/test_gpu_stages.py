@@ -486,6 +486,28 @@ def test_attention_peaked_logits_and_first_row(slim):
     np.testing.assert_array_equal(f64(got)[0], np.repeat(f64(v)[0], Hq // Hkv, 0))   # row 0 sees only key 0
 
 
+def test_attention_reference_moves_at_every_place(slim):
+    """Logits that climb a staircase along the keys (about 12 binary orders per stair, 48 stairs at random keys): for
+    every query the reference of the online softmax has to move at each stair below it, at whatever place in the key
+    tile, unit and part of a unit the stair falls, in the full-tile loop and in the masked loop of the diagonal."""
+    n, Hq, Hkv, d = 1500, 8, 2, 128
+    print(f"attn staircase n={n} H={Hq}/{Hkv} d={d}", flush=True)
+    q, k, v = inputs.stage_qkv(n, Hq, Hkv, d, "bf16", seed=77)
+    g = np.random.default_rng(5)
+    stairs = np.sort(g.choice(np.arange(1, n), 48, replace=False))
+    level = torch.from_numpy(np.searchsorted(stairs, np.arange(n), side="right").astype(np.float32))
+    q = (q.float() * 0.25)
+    k = (k.float() * 0.25)
+    q[:, :, 0] = 8.0
+    k[:, :, 0] = 12.0 * level[:, None]
+    q, k = q.to(torch.bfloat16), k.to(torch.bfloat16)
+    got = slim.slim_prefill_attn(dev(q), dev(k), dev(v))
+    want = so.causal_gqa_attention(f64(q), f64(k), f64(v))
+    mx, mean = errs(got, want)
+    print(f"   max-abs {mx:.3e} mean-abs {mean:.3e}", flush=True)
+    assert np.isfinite(f64(got)).all() and mx <= 4e-2 and mean <= MEAN_ABS * 2
+
+
 def test_kernels_are_deterministic(slim):
     q, k, v = inputs.stage_qkv(700, 8, 2, 128, "bf16", seed=3)
     a = slim.slim_prefill_attn(dev(q), dev(k), dev(v))
