@@ -486,12 +486,14 @@ def test_attention_peaked_logits_and_first_row(slim):
     np.testing.assert_array_equal(f64(got)[0], np.repeat(f64(v)[0], Hq // Hkv, 0))   # row 0 sees only key 0
 
 
-def test_attention_reference_moves_at_every_place(slim):
-    """Logits that climb a staircase along the keys (about 12 binary orders per stair, 48 stairs at random keys): for
-    every query the reference of the online softmax has to move at each stair below it, at whatever place in the key
-    tile, unit and part of a unit the stair falls, in the full-tile loop and in the masked loop of the diagonal."""
+@pytest.mark.parametrize("stair", [12.0, 160.0])
+def test_attention_reference_moves_at_every_place(slim, stair):
+    """Logits that climb a staircase along the keys (48 stairs at random keys, each about 12 binary orders high, or
+    about 160: then exp2 of a logit taken against the old reference overflows): for every query the reference of the
+    online softmax has to move at each stair below it, at whatever place in the key tile, unit and part of a unit the
+    stair falls, in the full-tile loop and in the masked loop of the diagonal."""
     n, Hq, Hkv, d = 1500, 8, 2, 128
-    print(f"attn staircase n={n} H={Hq}/{Hkv} d={d}", flush=True)
+    print(f"attn staircase n={n} H={Hq}/{Hkv} d={d} stair {stair}", flush=True)
     q, k, v = inputs.stage_qkv(n, Hq, Hkv, d, "bf16", seed=77)
     g = np.random.default_rng(5)
     stairs = np.sort(g.choice(np.arange(1, n), 48, replace=False))
@@ -499,7 +501,7 @@ def test_attention_reference_moves_at_every_place(slim):
     q = (q.float() * 0.25)
     k = (k.float() * 0.25)
     q[:, :, 0] = 8.0
-    k[:, :, 0] = 12.0 * level[:, None]
+    k[:, :, 0] = stair * level[:, None]                  # exact in bf16 up to 48 stairs
     q, k = q.to(torch.bfloat16), k.to(torch.bfloat16)
     got = slim.slim_prefill_attn(dev(q), dev(k), dev(v))
     want = so.causal_gqa_attention(f64(q), f64(k), f64(v))
