@@ -47,7 +47,7 @@ NRING = 8
 KOFF, VOFF = 144, 152                # 8 + 4 LDS byte addresses
 KOFS, VOFS = 156, 164                # global byte offsets of the tile loads (8 + 8)
 REF, LRUN, TMAX = [172, 173], [174, 175], [176, 177]
-LUNIT = TMAX                         # sum of P over the part of a unit being checked (TMAX is free in the loop)
+LUNIT = TMAX                         # a lane's sum of P over the unit in progress (TMAX is free outside the rare path)
 EARLY = 3                            # pairs of a unit whose P are formed during the unit before
 EXPT = [188, 189, 190, 191]          # P in fp32 on its way to the row sum and the bf16 pair: two items in flight
 LIMU = [178, 179]
@@ -119,18 +119,18 @@ def ld_v(dt, sub, step, vslot):
                 w=vr(v + 2, 2))]
 
 
-def exp_item(buf, qt, pair, slot, summed, first):
+def exp_item(buf, qt, pair, slot, first):
     """P for two keys of one query sub-tile: exp2 into temporaries (S stays, for the path that moves the reference),
-    their sum into the part-of-unit sum, the bf16 pair."""
+    their sum into the unit's sum (first: the sum starts with them), the bf16 pair."""
     s = S_BUF[buf][qt] + 2 * pair
     p = PB[qt] + pair
     t = EXPT[2 * slot]
     lu = LUNIT[qt]
     out = [valu(f"v_exp_f32 {V(t)}, {V(s)}", r=vr(s), w=vr(t), kind="trans"),
            valu(f"v_exp_f32 {V(t + 1)}, {V(s + 1)}", r=vr(s + 1), w=vr(t + 1), kind="trans")]
-    if summed and first:
+    if first:
         out.append(valu(f"v_add_f32 {V(lu)}, {V(t)}, {V(t + 1)}", r=vr(t, 2), w=vr(lu)))
-    elif summed:
+    else:
         out.append(valu(f"v_add_f32 {V(lu)}, {V(lu)}, {V(t)}", r=vr(t) + vr(lu), w=vr(lu)))
         out.append(valu(f"v_add_f32 {V(lu)}, {V(lu)}, {V(t + 1)}", r=vr(t + 1) + vr(lu), w=vr(lu)))
     out.append(valu(f"v_cvt_pk_bf16_f32 {V(p)}, {V(t)}, {V(t + 1)}", r=vr(t, 2), w=vr(p)))
@@ -143,7 +143,7 @@ def exp_stream(buf, pairs, fresh):
     out, prev, started, n = [], None, set(), 0
     for p in pairs:
         for qt in (0, 1):
-            sq = exp_item(buf, qt, p, n & 1, True, fresh and qt not in started)
+            sq = exp_item(buf, qt, p, n & 1, fresh and qt not in started)
             started.add(qt)
             n += 1
             out += sq[:2]
