@@ -530,7 +530,7 @@ def prologue():
         e(valu(f"v_mul_f32 {V(hi)}, %[scale], {V(hi)}", r=vr(hi), w=vr(hi)))
         e(valu(f"v_cvt_pk_bf16_f32 {V(lo)}, {V(lo)}, {V(hi)}", r=vr(lo) + vr(hi), w=vr(lo)))
         e(valu(f"v_accvgpr_write_b32 {A(Q_ACC + i)}, {V(lo)}", r=vr(lo), w=ar(Q_ACC + i)))
-    e(raw("s_waitcnt vmcnt(0)", "wait"))
+    e(raw("s_waitcnt vmcnt(16)", "wait"))       # K(0) is there; V(0) and K(1) are waited for at the loop's own barriers
     e(raw("s_barrier", "barrier"))
     # S(0): K fragments of unit 0 into the second S buffer's registers (free for now), 16 MFMAs from zero
     for st in range(8):

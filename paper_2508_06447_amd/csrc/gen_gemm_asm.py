@@ -202,7 +202,9 @@ class Shape:
                 for dw in range(4):
                     e(valu(f"v_cmp_eq_u32 vcc, {dw}, {V(idx)}", r=vr(idx), w=["vcc"], kind="vcmp"))
                     e(valu(f"v_cndmask_b32 {V(self.IDENT + 4 * p + dw)}, 0, {V(val)}, vcc", r=vr(val) + ["vcc"], w=vr(self.IDENT + 4 * p + dw)))
-        e(raw(f"s_waitcnt vmcnt({n_res})", "wait"))
+        # only the first k-tile has to be there: the second one (and the residual fragments) may stay in flight
+        # until the first k-tile's own wait before its barrier
+        e(raw(f"s_waitcnt vmcnt({self.NLD + n_res})", "wait"))
         e(raw("s_barrier", "barrier"))
         pro += self.frag_reads(0, 0, 0)
         body0f, body0, body1 = self.k_tile(0, True), self.k_tile(0, False), self.k_tile(1, False)
