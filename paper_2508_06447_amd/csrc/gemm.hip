@@ -411,8 +411,14 @@ __device__ __forceinline__ void gemm_tile(const bf16_t* __restrict__ A, int lda,
         __builtin_amdgcn_sched_barrier(0);
     };
     issue_loads(0, 0);
-    if (KT > 1) issue_loads(BK, 1);
-    __builtin_amdgcn_s_waitcnt(0x0070);                  // vmcnt(0) lgkmcnt(0)
+    if (KT > 1) {
+        // only the first k-tile has to be there; the second stays in flight until the first k-tile's own wait
+        constexpr unsigned kStageLoads = WLD + ALD;
+        issue_loads(BK, 1);
+        __builtin_amdgcn_s_waitcnt((kStageLoads & 15) | 0x0070 | ((kStageLoads >> 4) << 14));
+    } else {
+        __builtin_amdgcn_s_waitcnt(0x0070);              // vmcnt(0) lgkmcnt(0)
+    }
     workgroup_barrier();
     load_frags(Stage0{}, 0, 0);
     for (int kt = 0; kt < KT; kt += 2) {
