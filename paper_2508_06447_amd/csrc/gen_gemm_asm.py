@@ -56,7 +56,7 @@ class Shape:
         self.NLD = (self.WROWS + self.AROWS) // 32
         assert self.STAGE <= 65536 and self.NLW <= 8 and self.NLD - self.NLW <= 8
         self.ROFS = self.TMPV + 1                              # byte offsets of the lane's TA residual rows
-        self.IDENT = (self.ROFS + TA + 1) & ~1                 # two identity slices, 4 registers each
+        self.IDENT = (self.ROFS + TA + 2) & ~1                 # two identity slices, 4 registers each (ROFS + TA stays spare)
         self.RES = self.IDENT + 8                              # residual fragments, 4 registers per (j, i, p)
         self.LAST_V = self.RES + 4 * TA * TW * 2 - 1 if resid else self.TMPV
         assert self.LAST_V < 256
